@@ -1,0 +1,189 @@
+"""Pins for the oracle's cost model (Eq. 6, Sec. 4.2), the Eq. 1-5 helpers and
+the evaluation quantities of Sec. 5: closed forms, exact recovery, invariants,
+brute force and the numbers the paper prints."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def golden_rows(name):
+    return [l.split() for l in open(os.path.join(GOLDEN, name)) if l.strip() and not l.startswith("#")]
+
+
+# ----------------------------------------------------------------------------- Eq. 1-5
+
+def test_tab3_region_variables():
+    for model, N, K, rho, lam, kap in golden_rows("tab3_regions.txt"):
+        N, K = int(N), int(K)
+        assert oracle.rho(N, K, 256, 128) == pytest.approx(float(rho)), model
+        assert oracle.lam(N, 256) == int(lam), model
+        assert oracle.kappa(K, 128) == pytest.approx(float(kap)), model
+
+
+def test_paper_arithmetic():
+    for r in golden_rows("paper_arithmetic.txt"):
+        if r[0] == "omega":
+            assert round(oracle.omega(int(r[1]), int(r[2])), 2) == float(r[3])
+        elif r[0] == "group_m":
+            assert oracle.group_m_threshold(float(r[1]) * 2 ** 20, 256, 128, 1) == float(r[3])
+            assert 256 * 128 * 1 == int(r[2]) * 1024
+        elif r[0] == "table_bytes":
+            assert round(int(r[1]) * int(r[2]) * int(r[3]) / 1000, 1) == float(r[4])
+        elif r[0] == "exhaustive_ms":
+            assert round(int(r[1]) * int(r[2]) / 1000, 1) == float(r[3])
+
+
+def test_grid_is_eq1():
+    counts = [9, 7, 6, 6, 4, 0, 0, 1]
+    for bm in (1, 2, 4, 16, 104):
+        for nt in (1, 2, 8):
+            assert oracle.grid(counts, bm, nt) == sum(math.ceil(c / bm) for c in counts) * nt
+    assert oracle.grid([0, 0], 16, 4) == 0
+
+
+# ----------------------------------------------------------------------------- fit
+
+def test_fit_recovers_exact_synthetic_model():
+    W = 256
+    g = np.array([3, 8, 20, 40, 64, 100, 130, 200, 300, 512, 700, 1000, 24, 48, 96], float)
+    a, s, d = 11.0, 0.031, 4.5
+    t = a + s * g + d * np.log(g + 1)
+    theta, use_log = oracle.fit_cost_model(g, t, W)
+    assert use_log  # lower median 96 < 256
+    pred = oracle.design_matrix(g, W) @ theta
+    assert np.abs(pred - t).max() <= 1e-9 * t.max()
+    assert theta[0] == pytest.approx(a, rel=1e-8) and theta[3] == pytest.approx(d, rel=1e-8)
+    assert theta[1] / W + theta[2] == pytest.approx(s, rel=1e-9)  # only the combined slope is identifiable
+    # extrapolation to an unseen grid is unique too
+    assert oracle.predict(theta.astype(np.float32), 5000, W) == pytest.approx(a + s * 5000 + d * math.log(5001), rel=1e-5)
+
+
+def test_fit_without_log_is_simple_linear_regression():
+    W = 64
+    rng = np.random.default_rng(1)
+    g = rng.integers(100, 5000, 25).astype(float)
+    t = 20 + 0.05 * g + rng.normal(0, 1.0, 25)
+    theta, use_log = oracle.fit_cost_model(g, t, W)
+    assert not use_log and theta[3] == 0.0
+    slope = np.cov(g, t, bias=True)[0, 1] / g.var()
+    icpt = t.mean() - slope * g.mean()
+    assert theta[1] / W + theta[2] == pytest.approx(slope, rel=1e-9)
+    assert theta[0] == pytest.approx(icpt, rel=1e-8)
+    # minimum-norm split of the collinear pair: (b, c) proportional to (1/W, 1)
+    assert theta[1] * 1.0 == pytest.approx(theta[2] / W, rel=1e-6)
+
+
+def test_fit_residual_is_orthogonal_to_columns():
+    W = 256
+    rng = np.random.default_rng(2)
+    g = rng.integers(1, 200, 25).astype(float)
+    t = 5 + 0.2 * g + 3 * np.log(g + 1) + rng.normal(0, 0.5, 25)
+    theta, use_log = oracle.fit_cost_model(g, t, W)
+    assert use_log
+    X = oracle.design_matrix(g, W)
+    r = t - X @ theta
+    assert np.abs(X.T @ r).max() <= 1e-7 * np.abs(X.T @ t).max()
+
+
+def test_prediction_invariant_to_split_of_wave_and_per_block_terms():
+    W = 256
+    theta = np.array([3.0, 5.0, 0.25, 1.5])
+    shifted = theta + 7.0 * np.array([0, 1.0, -1.0 / W, 0])  # null-space direction of the design matrix
+    for g in (1, 77, 256, 100000):
+        x = oracle.design_matrix([g], W)[0]
+        assert x @ theta == pytest.approx(x @ shifted, rel=1e-12)
+
+
+def test_adaptive_log_term_switches_at_median_equal_capacity():
+    W = 100
+    base = np.array([10, 20, 30, 40], float)
+    t = lambda g: 1 + 0.1 * g + 2 * np.log(g + 1)
+    below = np.concatenate([base, [99], base + 500])     # 9 points, median 99 < W
+    at = np.concatenate([base, [100], base + 500])       # median 100 == W  -> no log
+    assert oracle.fit_cost_model(below, t(below), W)[1] is True
+    th, use = oracle.fit_cost_model(at, t(at), W)
+    assert use is False and th[3] == 0.0
+    # even count: lower median decides
+    even = np.array([10, 20, 99, 101, 500, 600], float)
+    assert oracle.lower_median(even) == 99 and oracle.fit_cost_model(even, t(even), W)[1] is True
+
+
+def test_ablation_forms():
+    W = 256
+    g = np.arange(1, 26, dtype=float) * 13
+    t = 2 + 0.3 * g
+    th2, _ = oracle.fit_cost_model(g, t, W, n_terms=2)
+    assert th2[1] == 0 and th2[3] == 0 and th2[0] == pytest.approx(2) and th2[2] == pytest.approx(0.3)
+    th3, use = oracle.fit_cost_model(g, t, W, n_terms=3)
+    assert not use and th3[3] == 0
+
+
+# ----------------------------------------------------------------------------- select
+
+def brute_select(bm, ntiles, W, theta, counts):
+    best, best_t, preds = -1, None, []
+    for c in range(len(bm)):
+        g = sum(-(-int(n) // int(bm[c])) for n in counts) * int(ntiles[c])
+        a, b, cc, d = (float(np.float32(v)) for v in theta[c])
+        t = a + b * (g / W[c]) + cc * g + d * math.log(g + 1.0)
+        preds.append(t)
+        if best_t is None or t < best_t:
+            best, best_t = c, t
+    return best, preds
+
+
+def test_select_matches_brute_force():
+    rng = np.random.default_rng(3)
+    for trial in range(20):
+        n = 12
+        bm = rng.choice([4, 8, 16, 32, 64, 128], n)
+        nt = rng.integers(1, 40, n)
+        W = rng.choice([256, 512, 1024], n)
+        theta = np.abs(rng.normal(0, 1, (n, 4))).astype(np.float32) * [10, 5, 0.05, 2]
+        counts = rng.integers(0, 300, 64)
+        best, pred = oracle.select(bm, nt, W, theta, counts)
+        b2, p2 = brute_select(bm, nt, W, theta, counts)
+        assert best == b2
+        assert np.allclose(pred, p2, rtol=1e-14, atol=0)
+
+
+def test_select_pure_per_block_cost_picks_smallest_grid_and_ties_go_to_lowest_index():
+    counts = [9, 7, 6, 6, 4] + [0] * 11
+    bm = [4, 16, 8, 16]
+    nt = [2, 2, 2, 2]
+    W = [256] * 4
+    theta = np.tile(np.array([0, 0, 1, 0], np.float32), (4, 1))
+    best, pred = oracle.select(bm, nt, W, theta, counts)
+    assert pred.tolist() == [20.0, 10.0, 12.0, 10.0]
+    assert best == 1  # configs 1 and 3 tie; the lower index wins
+
+
+def test_predict_formula_terms():
+    th = np.array([1.5, 2.0, 0.25, 3.0], np.float32)
+    assert oracle.predict(th, 0, 256) == 1.5
+    assert oracle.predict(th, 255, 256) == pytest.approx(1.5 + 2 * 255 / 256 + 0.25 * 255 + 3 * math.log(256), rel=1e-15)
+
+
+# ----------------------------------------------------------------------------- regret / static / speedup
+
+def test_regret_static_speedup():
+    t = np.array([[10.0, 12.0, 9.0], [20.0, 15.0, 30.0]])
+    assert oracle.regret(t[0], 2) == 0.0
+    assert oracle.regret(t[0], 1) == pytest.approx(12 / 9 - 1)
+    assert all(oracle.regret(row, c) >= 0 for row in t for c in range(3))
+    assert oracle.static_choice(t[1]) == 1
+    assert oracle.geomean_speedup([244, 277], [143, 198]) == pytest.approx(math.sqrt(244 / 143 * 277 / 198))
+    # Tab. 5 beta=0.5: the seven printed rows have geomean 1.32x (from either the us columns or the
+    # printed ratios); the table's own summary line says 1.22x, which the rows shown do not reproduce
+    # (the 1.22x must average points that are not listed).  The formula is pinned on the rows.
+    static = [244, 277, 155, 91, 315, 127, 65]
+    ra = [143, 198, 116, 72, 248, 107, 55]
+    assert round(oracle.geomean_speedup(static, ra), 2) in (1.32, 1.33)  # from the printed us columns
+    printed = [1.70, 1.40, 1.33, 1.27, 1.27, 1.19, 1.18]
+    assert round(float(np.exp(np.mean(np.log(printed)))), 2) in (1.32, 1.33)
