@@ -1,0 +1,162 @@
+/*
+ * ramp.h - C ABI of the MI355X (gfx950) routing-aware fused-MoE library.
+ *
+ * The library implements the hot path of RaMP (arxiv 2604.26039): the fused MoE
+ * layer of Sec. 2.2 as a family of tile configurations (Sec. 2.2 "tile
+ * configuration", Sec. 4.3) plus the four-term wave cost model of Sec. 4.2 that
+ * picks one configuration per call from the runtime expert histogram.
+ *
+ * Notation (paper -> here): S -> T tokens; c_e -> n_e pairs routed to expert e;
+ * N -> 2*I (gate and up projections side by side); K -> H; SM -> 256 compute
+ * units; CTA -> workgroup; wn -> wavefronts per workgroup.
+ *
+ * Conventions
+ *  - "dev" pointers are device (HBM) addresses valid on the current HIP device,
+ *    "host" pointers are ordinary host memory.  The library never allocates or
+ *    frees device memory: every buffer, including workspaces, belongs to the
+ *    caller and is sized with the *_bytes / *_capacity queries below.
+ *  - Device work is enqueued on the caller's stream (a hipStream_t passed as
+ *    void*; NULL = the default stream) and is asynchronous.  No call syncs with
+ *    the host.  Calls that share a workspace must be ordered by the caller.
+ *  - Every call returns RAMP_OK or a negative status; nothing throws.
+ *    ramp_last_error() returns a thread-local text for the last failure.
+ *  - bf16 buffers hold raw bfloat16 bit patterns (uint16 each).
+ */
+#ifndef RAMP_H
+#define RAMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    RAMP_OK = 0,
+    RAMP_EINVAL = -1,       /* bad argument (NULL pointer, negative size, misaligned buffer) */
+    RAMP_ENOSPC = -2,       /* a caller-provided buffer or workspace is too small            */
+    RAMP_EUNSUPPORTED = -3, /* configuration not instantiated / shape outside kernel limits  */
+    RAMP_EHIP = -4          /* the HIP runtime reported an error on launch                   */
+};
+
+/* Problem statement of Sec. 2.1/2.2: T tokens, top-k routing over E experts,
+ * hidden size H, expert intermediate size I (SwiGLU experts). */
+typedef struct {
+    int32_t T, k, E, H, I;
+} ramp_shape;
+
+/* Tile configuration (Sec. 2.2, c = (bm, bn, wn, stg)) in this kernel's terms:
+ *   bm     token-block rows per M-tile (1..256; padded to a multiple of 16 inside the MFMA)
+ *   bn     weight rows (columns of the paper's N) per workgroup tile: the up-projection
+ *          tile holds bn/2 gate rows and the matching bn/2 up rows, the down-projection
+ *          tile holds bn output features
+ *   bk     K-slice staged in LDS per pipeline step
+ *   waves  wavefronts (64 lanes) per workgroup
+ *   stages LDS pipeline depth
+ *   mode   kernel variant: bits 0-7 = (wavefront rows along the token dimension) - 1, i.e. how
+ *          the `waves` wavefronts are arranged over the tile (tokens x features);
+ *          bits 8.. = 0 for the LDS-staged two-phase path */
+typedef struct {
+    int32_t bm, bn, bk, waves, stages, mode;
+} ramp_config;
+
+const char *ramp_last_error(void);
+
+/* ---- configuration family (Sec. 4.3 "Configuration diversity") ------------------------- */
+
+/* Number of configurations that are valid for this shape under gfx950 limits
+ * (LDS 160 KB per CU, register budget, MFMA 16x16x32 alignment, H % 32 == 0,
+ * I % 32 == 0, tile widths dividing 2*I and H).  Host only. */
+int ramp_num_configs(const ramp_shape *shape);
+/* idx-th valid configuration, 0 <= idx < ramp_num_configs(). */
+int ramp_get_config(const ramp_shape *shape, int idx, ramp_config *out);
+/* Second factor of Eq. 1 for this kernel: work tiles per M-tile summed over the
+ * two projections, ceil(2I/bn) + ceil(H/bn).  Negative status on error. */
+int ramp_config_ntiles(const ramp_shape *shape, const ramp_config *cfg);
+/* "SM" of Eq. 6 on this chip: 256 compute units times the workgroups of this
+ * configuration that fit on one unit (from its LDS and register footprint). */
+int ramp_config_wave_capacity(const ramp_config *cfg);
+
+/* ---- align (Eq. 1 first factor; Fig. 1) --------------------------------------------------
+ * Pair p = t*k + j is routed to expert topk_ids[p].  Expert e owns
+ * ceil(n_e/bm) consecutive tiles of bm slots; its pairs fill them in increasing p,
+ * unused slots hold the sentinel P = T*k.  Pairs whose id is outside [0,E) are
+ * dropped and counted.  The result is unique, so it can be compared byte for byte. */
+
+/* Slots in sorted_pair_ids: roundup(P + min(E,P)*(bm-1), bm). */
+size_t ramp_align_capacity(int T, int k, int E, int bm);
+/* Scratch bytes ramp_moe_align / ramp_moe_histogram need for (T,k,E). */
+size_t ramp_align_workspace_bytes(int T, int k, int E);
+
+/* expert_counts[e] = n_e (Sec. 4.4 step 1).  dev in, dev out. */
+int ramp_moe_histogram(const int32_t *topk_ids /*dev [T*k]*/, int T, int k, int E,
+                       int32_t *expert_counts /*dev [E]*/,
+                       void *ws /*dev*/, size_t ws_bytes, void *stream);
+
+/* Full align.  meta = {P_pad, M_tiles, dropped, 0}; tile_expert[m] = expert of tile m,
+ * -1 for m >= M_tiles; sorted_pair_ids slots >= P_pad hold the sentinel.
+ * Limits: E <= 1024, 1 <= bm <= 1024, T*k < 2^30. */
+int ramp_moe_align(const int32_t *topk_ids /*dev [T*k]*/, int T, int k, int E, int bm,
+                   int32_t *sorted_pair_ids /*dev [capacity]*/,
+                   int32_t *tile_expert /*dev [capacity/bm]*/,
+                   int32_t *expert_counts /*dev [E]*/, int32_t *meta /*dev [4]*/,
+                   void *ws /*dev*/, size_t ws_bytes, void *stream);
+
+/* ---- expert weights ------------------------------------------------------------------------
+ * Boundary layout (Sec. 2.2): W_gate, W_up bf16 [E,H,I] (x W convention, I contiguous),
+ * W_down bf16 [E,I,H].  The kernels read a packed copy made once per model, outside the
+ * timed path (the analogue of the paper's offline compile step): every 16x32 block of
+ * W^T is stored in the register order of one MFMA 16x16x32 operand so that a wavefront
+ * loads it as one contiguous 1 KB line. */
+size_t ramp_pack_bytes(const ramp_shape *shape);
+int ramp_pack_weights(const ramp_shape *shape, const void *W_gate, const void *W_up,
+                      const void *W_down /*dev bf16*/, void *packed /*dev, 256 B aligned*/,
+                      void *stream);
+
+/* ---- fused MoE layer (Sec. 2.2 phases 1-3, Sec. 4.3) --------------------------------------
+ * out[t,:] = sum_j w[t,j] * ( SiLU(x_t W_gate[e_j]) * (x_t W_up[e_j]) ) W_down[e_j]
+ * bf16 inputs, fp32 accumulation, one bf16 rounding of the activation between the
+ * projections, fp32 per-pair rows summed in fixed j order (no atomics: results are
+ * bit-identical from run to run), one final rounding to bf16.
+ * Runs align(bm) + both projections + combine on `stream`; the grid is an upper
+ * bound with early exit (Sec. 4.3 "grid overlaunch"), so nothing is read back. */
+size_t ramp_fused_moe_workspace_bytes(const ramp_shape *shape, const ramp_config *cfg);
+int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg,
+                   const void *X /*dev bf16 [T,H]*/, const int32_t *topk_ids /*dev [T,k]*/,
+                   const float *topk_w /*dev fp32 [T,k]*/, const void *packed_weights /*dev*/,
+                   void *out /*dev bf16 [T,H]*/, void *ws /*dev, 256 B aligned*/, size_t ws_bytes,
+                   void *stream);
+/* Where ramp_fused_moe leaves the align result inside its workspace (byte offsets),
+ * for tests: sorted_pair_ids, tile_expert, expert_counts, meta. */
+int ramp_fused_moe_workspace_layout(const ramp_shape *shape, const ramp_config *cfg,
+                                    size_t offsets[4]);
+
+/* ---- cost model (Eq. 6, Sec. 4.2) -----------------------------------------------------------
+ * T_hat(c) = a + b*g/W + c*g + d*ln(g+1),  g = (sum_e ceil(n_e/bm_c)) * ntiles_c. */
+
+/* Least-squares fit per configuration from profiling (Sec. 4.2 "Fitting").
+ * grid/time_us are host arrays [n_cfg, n_pts]; wave_cap host [n_cfg].
+ * The log column is used only when the lower median of a configuration's profiling
+ * grids is below its wave capacity.  The columns g/W and g are proportional, so
+ * the minimum-norm least-squares solution is returned; predictions do not depend on
+ * that choice.  theta: host out [n_cfg,4] = a,b,c,d. */
+int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
+                        const double *time_us, float *theta);
+
+/* Evaluate Eq. 6 for every configuration on one histogram (host [E]) and return the
+ * lowest index with the smallest prediction in *best_idx (Sec. 4.2 "Runtime
+ * dispatch").  pred_us: optional host out [n_cfg] (fp64 evaluation). */
+int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
+                           const int32_t *wave_cap, const float *theta,
+                           const int32_t *expert_counts, int *best_idx, double *pred_us);
+
+/* ---- measurement helper ------------------------------------------------------------------------
+ * Plain device copy of `bytes` bytes (multiple of 16, both 16 B aligned): the
+ * known-size reference kernel that profiler byte counters are calibrated against. */
+int ramp_copy_bytes(void *dst /*dev*/, const void *src /*dev*/, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAMP_H */

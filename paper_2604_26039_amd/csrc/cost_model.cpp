@@ -1,0 +1,157 @@
+// Four-term wave cost model (paper Eq. 6, Sec. 4.2): least-squares fit per configuration
+// and the runtime argmin over configurations.  Host code only.
+//
+//   T_hat(c) = a + b * g/W + c * g + d * ln(g + 1),   g = (sum_e ceil(n_e / bm_c)) * ntiles_c
+//
+// The columns g/W and g of the design matrix are proportional for a fixed configuration, so
+// the literal four-column system is rank deficient.  The fit returns the minimum-norm
+// least-squares solution (pseudo-inverse through a one-sided Jacobi SVD, singular values below
+// eps*max(n,4)*sigma_max treated as zero); every solution of the system gives the same
+// predictions, which is all the selection uses.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "ramp.h"
+
+namespace ramp {
+void set_error(const char *fmt, ...);
+}
+
+namespace {
+
+// Minimum-norm least squares  min |A x - t|  for an n x m matrix (column major, m <= 4).
+void lstsq_min_norm(std::vector<double> A, int n, int m, const double *t, double *x)
+{
+    double V[4][4] = {};
+    for (int j = 0; j < m; ++j) V[j][j] = 1.0;
+    auto col = [&](int j) { return A.data() + (size_t)j * n; };
+    for (int sweep = 0; sweep < 60; ++sweep) {
+        double off = 0.0;
+        for (int p = 0; p < m - 1; ++p)
+            for (int q = p + 1; q < m; ++q) {
+                double app = 0, aqq = 0, apq = 0;
+                double *cp = col(p), *cq = col(q);
+                for (int i = 0; i < n; ++i) {
+                    app += cp[i] * cp[i];
+                    aqq += cq[i] * cq[i];
+                    apq += cp[i] * cq[i];
+                }
+                if (apq == 0.0 || app == 0.0 || aqq == 0.0) continue;
+                double rel = std::fabs(apq) / std::sqrt(app * aqq);
+                off = std::max(off, rel);
+                if (rel < 1e-16) continue;
+                double zeta = (aqq - app) / (2.0 * apq);
+                double tn = (zeta >= 0 ? 1.0 : -1.0) / (std::fabs(zeta) + std::sqrt(1.0 + zeta * zeta));
+                double cs = 1.0 / std::sqrt(1.0 + tn * tn), sn = cs * tn;
+                for (int i = 0; i < n; ++i) {
+                    double vp = cp[i], vq = cq[i];
+                    cp[i] = cs * vp - sn * vq;
+                    cq[i] = sn * vp + cs * vq;
+                }
+                for (int i = 0; i < m; ++i) {
+                    double vp = V[i][p], vq = V[i][q];
+                    V[i][p] = cs * vp - sn * vq;
+                    V[i][q] = sn * vp + cs * vq;
+                }
+            }
+        if (off < 1e-15) break;
+    }
+    double sigma[4], smax = 0.0;
+    for (int j = 0; j < m; ++j) {
+        double s = 0;
+        for (int i = 0; i < n; ++i) s += col(j)[i] * col(j)[i];
+        sigma[j] = std::sqrt(s);
+        smax = std::max(smax, sigma[j]);
+    }
+    const double cut = 2.220446049250313e-16 * std::max(n, m) * smax;
+    for (int j = 0; j < m; ++j) x[j] = 0.0;
+    for (int j = 0; j < m; ++j) {
+        if (sigma[j] <= cut || sigma[j] == 0.0) continue;
+        double ut = 0;
+        for (int i = 0; i < n; ++i) ut += col(j)[i] * t[i];
+        double coef = ut / (sigma[j] * sigma[j]);  // (u_j . t) / sigma_j with u_j = A_j / sigma_j
+        for (int i = 0; i < m; ++i) x[i] += V[i][j] * coef;
+    }
+}
+
+}  // namespace
+
+extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
+                                   const double *time_us, float *theta)
+{
+    if (n_cfg < 0 || n_pts <= 0 || !wave_cap || !grid || !time_us || !theta) {
+        ramp::set_error("cost_model_fit: bad argument");
+        return RAMP_EINVAL;
+    }
+    std::vector<double> A((size_t)4 * n_pts), sorted_g(n_pts);
+    for (int c = 0; c < n_cfg; ++c) {
+        const int64_t *g = grid + (size_t)c * n_pts;
+        const double *t = time_us + (size_t)c * n_pts;
+        const double W = (double)wave_cap[c];
+        if (W <= 0) {
+            ramp::set_error("cost_model_fit: wave_cap[%d] <= 0", c);
+            return RAMP_EINVAL;
+        }
+        for (int i = 0; i < n_pts; ++i) sorted_g[i] = (double)g[i];
+        std::sort(sorted_g.begin(), sorted_g.end());
+        const bool use_log = sorted_g[(n_pts - 1) / 2] < W;  // lower median in the sub-wave region
+        const int m = use_log ? 4 : 3;
+        for (int i = 0; i < n_pts; ++i) {
+            const double gi = (double)g[i];
+            A[0 * (size_t)n_pts + i] = 1.0;
+            A[1 * (size_t)n_pts + i] = gi / W;
+            A[2 * (size_t)n_pts + i] = gi;
+            A[3 * (size_t)n_pts + i] = std::log(gi + 1.0);
+        }
+        double x[4] = {0, 0, 0, 0};
+        lstsq_min_norm(std::vector<double>(A.begin(), A.begin() + (size_t)m * n_pts), n_pts, m, t, x);
+        for (int j = 0; j < 4; ++j) theta[(size_t)c * 4 + j] = (j < m) ? (float)x[j] : 0.0f;
+    }
+    return RAMP_OK;
+}
+
+extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
+                                      const int32_t *wave_cap, const float *theta, const int32_t *expert_counts,
+                                      int *best_idx, double *pred_us)
+{
+    if (E <= 0 || n_cfg <= 0 || !cfgs || !ntiles || !wave_cap || !theta || !expert_counts || !best_idx) {
+        ramp::set_error("cost_model_select: bad argument");
+        return RAMP_EINVAL;
+    }
+    int best = -1;
+    double best_t = 0.0;
+    // M-tiles depend only on bm; configurations usually share a handful of bm values
+    int last_bm = -1;
+    int64_t last_mt = 0;
+    for (int c = 0; c < n_cfg; ++c) {
+        const int bm = cfgs[c].bm;
+        if (bm <= 0 || wave_cap[c] <= 0) {
+            ramp::set_error("cost_model_select: config %d has bm=%d wave_cap=%d", c, bm, wave_cap[c]);
+            return RAMP_EINVAL;
+        }
+        if (bm != last_bm) {
+            int64_t mt = 0;
+            for (int e = 0; e < E; ++e) {
+                const int64_t n = expert_counts[e] > 0 ? expert_counts[e] : 0;
+                mt += (n + bm - 1) / bm;
+            }
+            last_bm = bm;
+            last_mt = mt;
+        }
+        const double g = (double)(last_mt * (int64_t)ntiles[c]);
+        const float *th = theta + (size_t)c * 4;
+        double t = (double)th[0];
+        t = t + (double)th[1] * (g / (double)wave_cap[c]);
+        t = t + (double)th[2] * g;
+        t = t + (double)th[3] * std::log(g + 1.0);
+        if (pred_us) pred_us[c] = t;
+        if (best < 0 || t < best_t) {
+            best = c;
+            best_t = t;
+        }
+    }
+    *best_idx = best;
+    return RAMP_OK;
+}

@@ -1,0 +1,325 @@
+// Configuration registry, the top-k combine kernel and the fused-MoE entry point
+// (paper Sec. 2.2 phases 1-3 as align -> up-projection+SwiGLU -> down-projection -> combine).
+#include <mutex>
+
+#include "ramp_internal.h"
+
+namespace ramp {
+
+void register_group0(KernelInfo *, int *);
+void register_group1(KernelInfo *, int *);
+void register_group2(KernelInfo *, int *);
+void register_group3(KernelInfo *, int *);
+
+namespace {
+constexpr int kMaxKernels = 128;
+KernelInfo g_kernels[kMaxKernels];
+int g_num_kernels = 0;
+std::once_flag g_once;
+
+void init_registry()
+{
+    std::call_once(g_once, [] {
+        register_group0(g_kernels, &g_num_kernels);
+        register_group1(g_kernels, &g_num_kernels);
+        register_group2(g_kernels, &g_num_kernels);
+        register_group3(g_kernels, &g_num_kernels);
+    });
+}
+
+// out[t,:] = sum_j Y[t*k+j,:] in increasing j, fp32, one rounding to bf16.  The router weight
+// was applied by the down-projection epilogue.  Pairs with an invalid expert id have no row.
+__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ Y, const int32_t *__restrict__ ids, int T,
+                                                      int k, int E, int H, uint16_t *__restrict__ out)
+{
+    const int hv = H / 4;  // float4 columns
+    const size_t total = (size_t)T * hv;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int t = (int)(i / hv), c = (int)(i % hv);
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < k; ++j) {
+            const int id = ids[(size_t)t * k + j];
+            if (id < 0 || id >= E) continue;
+            const float4 y = *reinterpret_cast<const float4 *>(Y + ((size_t)t * k + j) * H + (size_t)c * 4);
+            s.x += y.x;
+            s.y += y.y;
+            s.z += y.z;
+            s.w += y.w;
+        }
+        const float v[4] = {s.x, s.y, s.z, s.w};
+        union {
+            uint16_t h[4];
+            uint2 u;
+        } o;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t b = __builtin_bit_cast(uint32_t, v[q]);
+            b += 0x7fffu + ((b >> 16) & 1u);
+            o.h[q] = (uint16_t)(b >> 16);
+        }
+        *reinterpret_cast<uint2 *>(out + (size_t)t * H + (size_t)c * 4) = o.u;
+    }
+}
+
+struct Workspace {
+    size_t sorted, tile_expert, counts, meta, align_ws, a_buf, y_buf, total;
+    size_t cap, align_ws_bytes;
+};
+
+Workspace workspace_layout(const ramp_shape &s, const ramp_config &c)
+{
+    Workspace w;
+    w.cap = ramp_align_capacity(s.T, s.k, s.E, c.bm);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    w.sorted = take(w.cap * 4);
+    w.tile_expert = take((w.cap / (size_t)c.bm) * 4);
+    w.counts = take((size_t)s.E * 4);
+    w.meta = take(16);
+    w.align_ws_bytes = ramp_align_workspace_bytes(s.T, s.k, s.E);
+    w.align_ws = take(w.align_ws_bytes);
+    w.a_buf = take(w.cap * (size_t)s.I * 2);
+    w.y_buf = take((size_t)s.T * s.k * s.H * 4);
+    w.total = off;
+    return w;
+}
+
+bool shape_ok(const ramp_shape &s)
+{
+    return s.T >= 0 && s.k >= 1 && s.E >= 1 && s.E <= kAlignMaxE && s.H >= 32 && s.I >= 32 && s.H % 32 == 0 &&
+           s.I % 32 == 0 && (long long)s.T * s.k < (1ll << 30);
+}
+
+}  // namespace
+
+int num_kernels()
+{
+    init_registry();
+    return g_num_kernels;
+}
+const KernelInfo &kernel_info(int i)
+{
+    init_registry();
+    return g_kernels[i];
+}
+const KernelInfo *find_kernel(const ramp_config &c)
+{
+    init_registry();
+    for (int i = 0; i < g_num_kernels; ++i) {
+        const ramp_config &k = g_kernels[i].cfg;
+        if (k.bm == c.bm && k.bn == c.bn && k.bk == c.bk && k.waves == c.waves && k.stages == c.stages &&
+            k.mode == c.mode)
+            return &g_kernels[i];
+    }
+    return nullptr;
+}
+bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s)
+{
+    const ramp_config &c = ki.cfg;
+    if (!shape_ok(s)) return false;
+    if (s.H % c.bk || s.I % c.bk) return false;      // whole k-slices
+    if ((2 * s.I) % c.bn || s.H % c.bn) return false;  // whole feature tiles in both projections
+    // 32-bit element offsets inside the kernels
+    const size_t cap = ramp_align_capacity(s.T, s.k, s.E, c.bm);
+    if (cap * (size_t)s.I >= (1ull << 32) || (size_t)s.T * s.H >= (1ull << 32)) return false;
+    if (2ull * s.I * s.H >= (1ull << 32)) return false;
+    return true;
+}
+int occupancy_estimate(const KernelInfo &ki)
+{
+    // Workgroups of this configuration resident on one compute unit: bounded by LDS, by the
+    // 512-register file per lane (accumulators plus ~96 working registers) and by 8 wavefronts
+    // per SIMD.
+    int by_lds = kLdsBytesPerCU / ki.lds_bytes;
+    int regs = ki.acc_regs + 96;
+    int waves_per_simd = 512 / regs;
+    if (waves_per_simd > 8) waves_per_simd = 8;
+    if (waves_per_simd < 1) waves_per_simd = 1;
+    int by_regs = waves_per_simd * 4 / ki.cfg.waves;
+    if (by_regs < 1) by_regs = 1;
+    int occ = by_lds < by_regs ? by_lds : by_regs;
+    return occ < 1 ? 1 : occ;
+}
+
+int launch_combine(const float *Y, const int32_t *ids, int T, int k, int E, int H, uint16_t *out, hipStream_t stream)
+{
+    if (T == 0) return RAMP_OK;
+    size_t total = (size_t)T * (H / 4);
+    unsigned grid = (unsigned)((total + 255) / 256);
+    if (grid > (unsigned)kNumCU * 16) grid = kNumCU * 16;
+    hipLaunchKernelGGL(combine_kernel, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out);
+    return check_launch("combine_kernel");
+}
+
+}  // namespace ramp
+
+using namespace ramp;
+
+extern "C" int ramp_num_configs(const ramp_shape *shape)
+{
+    if (!shape) {
+        set_error("num_configs: NULL shape");
+        return RAMP_EINVAL;
+    }
+    int n = 0;
+    for (int i = 0; i < num_kernels(); ++i) n += config_valid_for_shape(kernel_info(i), *shape) ? 1 : 0;
+    return n;
+}
+
+extern "C" int ramp_get_config(const ramp_shape *shape, int idx, ramp_config *out)
+{
+    if (!shape || !out || idx < 0) {
+        set_error("get_config: bad argument");
+        return RAMP_EINVAL;
+    }
+    int n = 0;
+    for (int i = 0; i < num_kernels(); ++i) {
+        if (!config_valid_for_shape(kernel_info(i), *shape)) continue;
+        if (n++ == idx) {
+            *out = kernel_info(i).cfg;
+            return RAMP_OK;
+        }
+    }
+    set_error("get_config: index %d out of range (%d valid)", idx, n);
+    return RAMP_EINVAL;
+}
+
+extern "C" int ramp_config_ntiles(const ramp_shape *shape, const ramp_config *cfg)
+{
+    if (!shape || !cfg || cfg->bn <= 0) {
+        set_error("config_ntiles: bad argument");
+        return RAMP_EINVAL;
+    }
+    return (2 * shape->I + cfg->bn - 1) / cfg->bn + (shape->H + cfg->bn - 1) / cfg->bn;
+}
+
+extern "C" int ramp_config_wave_capacity(const ramp_config *cfg)
+{
+    if (!cfg) {
+        set_error("config_wave_capacity: NULL config");
+        return RAMP_EINVAL;
+    }
+    const KernelInfo *ki = find_kernel(*cfg);
+    if (!ki) {
+        set_error("config_wave_capacity: configuration not instantiated");
+        return RAMP_EUNSUPPORTED;
+    }
+    return kNumCU * occupancy_estimate(*ki);
+}
+
+extern "C" size_t ramp_fused_moe_workspace_bytes(const ramp_shape *shape, const ramp_config *cfg)
+{
+    if (!shape || !cfg || cfg->bm <= 0 || !shape_ok(*shape)) return 0;
+    return workspace_layout(*shape, *cfg).total;
+}
+
+extern "C" int ramp_fused_moe_workspace_layout(const ramp_shape *shape, const ramp_config *cfg, size_t offsets[4])
+{
+    if (!shape || !cfg || !offsets || cfg->bm <= 0 || !shape_ok(*shape)) {
+        set_error("workspace_layout: bad argument");
+        return RAMP_EINVAL;
+    }
+    Workspace w = workspace_layout(*shape, *cfg);
+    offsets[0] = w.sorted;
+    offsets[1] = w.tile_expert;
+    offsets[2] = w.counts;
+    offsets[3] = w.meta;
+    return RAMP_OK;
+}
+
+extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, const void *X, const int32_t *topk_ids,
+                              const float *topk_w, const void *packed_weights, void *out, void *ws, size_t ws_bytes,
+                              void *stream)
+{
+    if (!shape || !cfg) {
+        set_error("fused_moe: NULL shape or config");
+        return RAMP_EINVAL;
+    }
+    const ramp_shape &s = *shape;
+    if (!shape_ok(s)) {
+        set_error("fused_moe: unsupported shape T=%d k=%d E=%d H=%d I=%d (need H, I multiples of 32, E<=%d)", s.T, s.k,
+                  s.E, s.H, s.I, kAlignMaxE);
+        return RAMP_EUNSUPPORTED;
+    }
+    const KernelInfo *ki = find_kernel(*cfg);
+    if (!ki) {
+        set_error("fused_moe: configuration (bm=%d bn=%d bk=%d waves=%d stages=%d mode=%d) is not instantiated",
+                  cfg->bm, cfg->bn, cfg->bk, cfg->waves, cfg->stages, cfg->mode);
+        return RAMP_EUNSUPPORTED;
+    }
+    if (!config_valid_for_shape(*ki, s)) {
+        set_error("fused_moe: configuration bm=%d bn=%d bk=%d does not tile H=%d I=%d", cfg->bm, cfg->bn, cfg->bk, s.H,
+                  s.I);
+        return RAMP_EUNSUPPORTED;
+    }
+    if (s.T == 0) return RAMP_OK;
+    if (!X || !topk_ids || !topk_w || !packed_weights || !out || !ws) {
+        set_error("fused_moe: NULL buffer");
+        return RAMP_EINVAL;
+    }
+    if (reinterpret_cast<uintptr_t>(ws) % 256 || reinterpret_cast<uintptr_t>(packed_weights) % 256 ||
+        reinterpret_cast<uintptr_t>(X) % 16 || reinterpret_cast<uintptr_t>(out) % 8) {
+        set_error("fused_moe: misaligned buffer (ws/packed 256 B, X 16 B, out 8 B)");
+        return RAMP_EINVAL;
+    }
+    const Workspace w = workspace_layout(s, *cfg);
+    if (ws_bytes < w.total) {
+        set_error("fused_moe: workspace %zu < %zu bytes", ws_bytes, w.total);
+        return RAMP_ENOSPC;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *base = static_cast<char *>(ws);
+    int32_t *sorted = reinterpret_cast<int32_t *>(base + w.sorted);
+    int32_t *tile_expert = reinterpret_cast<int32_t *>(base + w.tile_expert);
+    int32_t *counts = reinterpret_cast<int32_t *>(base + w.counts);
+    int32_t *meta = reinterpret_cast<int32_t *>(base + w.meta);
+    uint16_t *a_buf = reinterpret_cast<uint16_t *>(base + w.a_buf);
+    float *y_buf = reinterpret_cast<float *>(base + w.y_buf);
+
+    int rc = launch_align(topk_ids, s.T, s.k, s.E, cfg->bm, sorted, tile_expert, counts, meta, base + w.align_ws,
+                          w.align_ws_bytes, st);
+    if (rc) return rc;
+
+    const PackedLayout L = packed_layout(s);
+    const uint16_t *packed = static_cast<const uint16_t *>(packed_weights);
+    GemmArgs g;
+    g.sorted = sorted;
+    g.tile_expert = tile_expert;
+    g.meta = meta;
+    g.topk_w = topk_w;
+    g.a_out = a_buf;
+    g.y_out = y_buf;
+    g.P = s.T * s.k;
+    g.topk = s.k;
+    g.m_tiles_cap = (int)(w.cap / (size_t)cfg->bm);
+
+    // phase 1 + 2: up-projection with SwiGLU epilogue
+    g.act = static_cast<const uint16_t *>(X);
+    g.wpacked = packed;
+    g.expert_stride = L.w1_expert_elems;
+    g.up_offset = L.up_offset_elems;
+    g.K = s.H;
+    g.F = s.I;
+    g.n_tiles = 2 * s.I / cfg->bn;
+    ki->launch(1, g, st);
+    rc = check_launch("moe_gemm_kernel<1>");
+    if (rc) return rc;
+
+    // phase 3: down-projection, router weight applied, one fp32 row per pair
+    g.act = a_buf;
+    g.wpacked = packed + L.w2_base_elems;
+    g.expert_stride = L.w2_expert_elems;
+    g.up_offset = 0;
+    g.K = s.I;
+    g.F = s.H;
+    g.n_tiles = s.H / cfg->bn;
+    ki->launch(2, g, st);
+    rc = check_launch("moe_gemm_kernel<2>");
+    if (rc) return rc;
+
+    return launch_combine(y_buf, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st);
+}

@@ -1,0 +1,89 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "ramp.h"
+
+namespace ramp {
+
+// Thread-local message for ramp_last_error().
+void set_error(const char *fmt, ...);
+
+inline int check_launch(const char *what)
+{
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+        set_error("%s: %s", what, hipGetErrorString(err));
+        return RAMP_EHIP;
+    }
+    return RAMP_OK;
+}
+
+constexpr int kNumCU = 256;           // MI355X compute units
+constexpr int kLdsBytesPerCU = 160 * 1024;
+constexpr int kWave = 64;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- align ----
+constexpr int kAlignThreads = 1024;   // one workgroup = 16 wavefronts
+constexpr int kAlignChunk = 4096;     // pairs per workgroup in the multi-workgroup path
+constexpr int kAlignSingleMaxP = 4096; // up to this many pairs one workgroup does everything
+constexpr int kAlignMaxE = 1024;
+
+int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
+                 int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream);
+
+// ---- packed weights ----
+// One fragment = 16 weight rows x 32 k-values = 512 bf16 = 1 KB, stored in the lane order
+// of the A operand of v_mfma_f32_16x16x32_bf16: element (row r, k = 8*q + j) at (q*16 + r)*8 + j.
+constexpr int kFragElems = 512;
+struct PackedLayout {
+    size_t w1_expert_elems;  // gate then up: 2 * I * H
+    size_t up_offset_elems;  // I * H
+    size_t w2_expert_elems;  // H * I
+    size_t w2_base_elems;    // E * 2 * I * H
+    size_t total_bytes;
+};
+PackedLayout packed_layout(const ramp_shape &s);
+
+// ---- projections ----
+struct GemmArgs {
+    const uint16_t *act;        // stage 1: X [T,H]; stage 2: A [cap,I]
+    const uint16_t *wpacked;    // base of this stage's packed weights
+    size_t expert_stride;       // elements between experts
+    size_t up_offset;           // stage 1: offset of the up rows inside an expert
+    const int32_t *sorted;      // [cap]
+    const int32_t *tile_expert; // [cap/bm]
+    const int32_t *meta;        // [4]
+    const float *topk_w;        // stage 2: [P]
+    uint16_t *a_out;            // stage 1: A [cap,I]
+    float *y_out;               // stage 2: Y [P,H]
+    int K;                      // reduction length (H or I)
+    int F;                      // output features (I or H)
+    int P;                      // pairs = T*k (the sentinel)
+    int topk;                   // k
+    int n_tiles;                // feature tiles of this stage
+    int m_tiles_cap;            // launched M-tiles (upper bound)
+};
+
+struct KernelInfo {
+    ramp_config cfg;
+    int wm, wn;                 // wavefront grid inside the workgroup (tokens x features)
+    int lds_bytes;
+    int acc_regs;               // fp32 accumulators per lane (stage 1, the larger one)
+    void (*launch)(int stage, const GemmArgs &, hipStream_t);
+};
+int num_kernels();
+const KernelInfo &kernel_info(int i);
+const KernelInfo *find_kernel(const ramp_config &cfg);
+bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s);
+int occupancy_estimate(const KernelInfo &ki);
+
+int launch_combine(const float *Y, const int32_t *ids, int T, int k, int E, int H, uint16_t *out,
+                   hipStream_t stream);
+
+}  // namespace ramp

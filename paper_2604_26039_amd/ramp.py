@@ -1,0 +1,244 @@
+"""Thin ctypes binding of libramp.so: argument marshalling only.
+
+Every function has the name of the C entry point it wraps (include/ramp.h) minus the
+`ramp_` prefix.  Device buffers are torch tensors (torch is used for device memory and
+streams only); all arithmetic of the path runs in the library's HIP kernels.  There is no
+CPU fallback: if the library is missing the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libramp.so")
+
+OK, EINVAL, ENOSPC, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "k", "E", "H", "I")]
+
+    def __repr__(self):
+        return f"Shape(T={self.T}, k={self.k}, E={self.E}, H={self.H}, I={self.I})"
+
+
+class Config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("bm", "bn", "bk", "waves", "stages", "mode")]
+
+    def key(self):
+        return (self.bm, self.bn, self.bk, self.waves, self.stages, self.mode)
+
+    def __repr__(self):
+        return f"Config(bm={self.bm}, bn={self.bn}, bk={self.bk}, waves={self.waves}, stages={self.stages}, mode={self.mode})"
+
+
+class RampError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"ramp status {status}: {msg}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libramp.so (built by `python -m paper_2604_26039_amd.build`); raise if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2604_26039_amd.build` first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32p, f32p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+        sp, cp = ctypes.POINTER(Shape), ctypes.POINTER(Config)
+        sz, ci = ctypes.c_size_t, ctypes.c_int
+        L.ramp_last_error.restype = ctypes.c_char_p
+        L.ramp_last_error.argtypes = []
+        L.ramp_num_configs.restype = ci
+        L.ramp_num_configs.argtypes = [sp]
+        L.ramp_get_config.restype = ci
+        L.ramp_get_config.argtypes = [sp, ci, cp]
+        L.ramp_config_ntiles.restype = ci
+        L.ramp_config_ntiles.argtypes = [sp, cp]
+        L.ramp_config_wave_capacity.restype = ci
+        L.ramp_config_wave_capacity.argtypes = [cp]
+        L.ramp_align_capacity.restype = sz
+        L.ramp_align_capacity.argtypes = [ci, ci, ci, ci]
+        L.ramp_align_workspace_bytes.restype = sz
+        L.ramp_align_workspace_bytes.argtypes = [ci, ci, ci]
+        L.ramp_moe_histogram.restype = ci
+        L.ramp_moe_histogram.argtypes = [i32p, ci, ci, ci, i32p, vp, sz, vp]
+        L.ramp_moe_align.restype = ci
+        L.ramp_moe_align.argtypes = [i32p, ci, ci, ci, ci, i32p, i32p, i32p, i32p, vp, sz, vp]
+        L.ramp_pack_bytes.restype = sz
+        L.ramp_pack_bytes.argtypes = [sp]
+        L.ramp_pack_weights.restype = ci
+        L.ramp_pack_weights.argtypes = [sp, vp, vp, vp, vp, vp]
+        L.ramp_fused_moe_workspace_bytes.restype = sz
+        L.ramp_fused_moe_workspace_bytes.argtypes = [sp, cp]
+        L.ramp_fused_moe_workspace_layout.restype = ci
+        L.ramp_fused_moe_workspace_layout.argtypes = [sp, cp, ctypes.POINTER(sz)]
+        L.ramp_fused_moe.restype = ci
+        L.ramp_fused_moe.argtypes = [sp, cp, vp, i32p, f32p, vp, vp, vp, sz, vp]
+        L.ramp_cost_model_fit.restype = ci
+        L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp]
+        L.ramp_cost_model_select.restype = ci
+        L.ramp_cost_model_select.argtypes = [ci, ci, cp, vp, vp, vp, vp, ctypes.POINTER(ci), vp]
+        L.ramp_copy_bytes.restype = ci
+        L.ramp_copy_bytes.argtypes = [vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+EXPORTS = [
+    "ramp_last_error", "ramp_num_configs", "ramp_get_config", "ramp_config_ntiles", "ramp_config_wave_capacity",
+    "ramp_align_capacity", "ramp_align_workspace_bytes", "ramp_moe_histogram", "ramp_moe_align", "ramp_pack_bytes",
+    "ramp_pack_weights", "ramp_fused_moe_workspace_bytes", "ramp_fused_moe_workspace_layout", "ramp_fused_moe",
+    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_copy_bytes",
+]
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise RampError(rc, lib().ramp_last_error().decode())
+
+
+def last_error() -> str:
+    return lib().ramp_last_error().decode()
+
+
+def _dev(t: Optional[torch.Tensor]) -> int:
+    if t is None:
+        return 0
+    assert t.is_cuda and t.is_contiguous(), "device buffers must be contiguous GPU tensors"
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _np(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+# ----------------------------------------------------------------------------- configuration family
+
+def num_configs(shape: Shape) -> int:
+    n = lib().ramp_num_configs(ctypes.byref(shape))
+    if n < 0:
+        _check(n)
+    return n
+
+
+def get_config(shape: Shape, idx: int) -> Config:
+    c = Config()
+    _check(lib().ramp_get_config(ctypes.byref(shape), idx, ctypes.byref(c)))
+    return c
+
+
+def configs(shape: Shape):
+    return [get_config(shape, i) for i in range(num_configs(shape))]
+
+
+def config_ntiles(shape: Shape, cfg: Config) -> int:
+    n = lib().ramp_config_ntiles(ctypes.byref(shape), ctypes.byref(cfg))
+    if n < 0:
+        _check(n)
+    return n
+
+
+def config_wave_capacity(cfg: Config) -> int:
+    n = lib().ramp_config_wave_capacity(ctypes.byref(cfg))
+    if n < 0:
+        _check(n)
+    return n
+
+
+# ----------------------------------------------------------------------------- align
+
+def align_capacity(T: int, k: int, E: int, bm: int) -> int:
+    return int(lib().ramp_align_capacity(T, k, E, bm))
+
+
+def align_workspace_bytes(T: int, k: int, E: int) -> int:
+    return int(lib().ramp_align_workspace_bytes(T, k, E))
+
+
+def moe_histogram(topk_ids: torch.Tensor, T: int, k: int, E: int, expert_counts: torch.Tensor,
+                  ws: Optional[torch.Tensor], stream=None):
+    _check(lib().ramp_moe_histogram(_dev(topk_ids), T, k, E, _dev(expert_counts), _dev(ws),
+                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def moe_align(topk_ids, T, k, E, bm, sorted_pair_ids, tile_expert, expert_counts, meta, ws, stream=None):
+    _check(lib().ramp_moe_align(_dev(topk_ids), T, k, E, bm, _dev(sorted_pair_ids), _dev(tile_expert),
+                                _dev(expert_counts), _dev(meta), _dev(ws),
+                                ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+# ----------------------------------------------------------------------------- weights and the fused layer
+
+def pack_bytes(shape: Shape) -> int:
+    return int(lib().ramp_pack_bytes(ctypes.byref(shape)))
+
+
+def pack_weights(shape: Shape, W_gate, W_up, W_down, packed, stream=None):
+    _check(lib().ramp_pack_weights(ctypes.byref(shape), _dev(W_gate), _dev(W_up), _dev(W_down), _dev(packed),
+                                   _stream(stream)))
+
+
+def fused_moe_workspace_bytes(shape: Shape, cfg: Config) -> int:
+    return int(lib().ramp_fused_moe_workspace_bytes(ctypes.byref(shape), ctypes.byref(cfg)))
+
+
+def fused_moe_workspace_layout(shape: Shape, cfg: Config):
+    off = (ctypes.c_size_t * 4)()
+    _check(lib().ramp_fused_moe_workspace_layout(ctypes.byref(shape), ctypes.byref(cfg), off))
+    return [int(v) for v in off]
+
+
+def fused_moe(shape: Shape, cfg: Config, X, topk_ids, topk_w, packed_weights, out, ws, stream=None):
+    _check(lib().ramp_fused_moe(ctypes.byref(shape), ctypes.byref(cfg), _dev(X), _dev(topk_ids), _dev(topk_w),
+                                _dev(packed_weights), _dev(out), _dev(ws), ws.numel() * ws.element_size(),
+                                _stream(stream)))
+
+
+def copy_bytes(dst: torch.Tensor, src: torch.Tensor, nbytes: int, stream=None):
+    _check(lib().ramp_copy_bytes(_dev(dst), _dev(src), nbytes, _stream(stream)))
+
+
+# ----------------------------------------------------------------------------- cost model (host)
+
+def cost_model_fit(wave_cap: Sequence[int], grid, time_us) -> np.ndarray:
+    """grid, time_us: [n_cfg, n_pts].  Returns theta float32 [n_cfg, 4]."""
+    grid = _np(grid, np.int64)
+    time_us = _np(time_us, np.float64)
+    n_cfg, n_pts = grid.shape
+    assert time_us.shape == (n_cfg, n_pts)
+    wc = _np(wave_cap, np.int32)
+    assert wc.size == n_cfg
+    theta = np.zeros((n_cfg, 4), np.float32)
+    _check(lib().ramp_cost_model_fit(n_cfg, wc.ctypes.data, n_pts, grid.ctypes.data, time_us.ctypes.data,
+                                     theta.ctypes.data))
+    return theta
+
+
+def cost_model_select(E: int, cfgs: Sequence[Config], ntiles, wave_cap, theta, expert_counts, want_pred=False):
+    n = len(cfgs)
+    arr = (Config * n)(*cfgs)
+    nt, wc = _np(ntiles, np.int32), _np(wave_cap, np.int32)
+    th = _np(theta, np.float32).reshape(n, 4)
+    counts = _np(expert_counts, np.int32)
+    assert counts.size == E and nt.size == n and wc.size == n
+    best = ctypes.c_int(-1)
+    pred = np.zeros(n, np.float64) if want_pred else None
+    _check(lib().ramp_cost_model_select(E, n, arr, nt.ctypes.data, wc.ctypes.data, th.ctypes.data, counts.ctypes.data,
+                                        ctypes.byref(best), pred.ctypes.data if want_pred else None))
+    return (best.value, pred) if want_pred else best.value

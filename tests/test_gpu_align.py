@@ -1,0 +1,113 @@
+"""GPU parity: ramp_moe_align / ramp_moe_histogram against the oracle, bit for bit, through
+the C ABI.  Covers the single-workgroup and multi-workgroup paths, several tiles with a ragged
+tail, empty input, dropped ids and the largest benchmark sizes."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2604_26039_amd import ramp, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def gpu_align(ids_np, T, k, E, bm, guard=64):
+    cap = ramp.align_capacity(T, k, E, bm)
+    ids = torch.from_numpy(np.ascontiguousarray(ids_np.reshape(-1), dtype=np.int32)).to(DEV)
+    # guard words after each output catch writes past the end
+    sorted_ids = torch.full((cap + guard,), -7, dtype=torch.int32, device=DEV)
+    tile_expert = torch.full((cap // bm + guard,), -7, dtype=torch.int32, device=DEV)
+    counts = torch.full((E + guard,), -7, dtype=torch.int32, device=DEV)
+    meta = torch.full((4 + guard,), -7, dtype=torch.int32, device=DEV)
+    ws = torch.empty(ramp.align_workspace_bytes(T, k, E), dtype=torch.uint8, device=DEV)
+    ramp.moe_align(ids, T, k, E, bm, sorted_ids, tile_expert, counts, meta, ws)
+    torch.cuda.synchronize()
+    outs = [t.cpu().numpy() for t in (sorted_ids, tile_expert, counts, meta)]
+    sizes = [cap, cap // bm, E, 4]
+    for o, n in zip(outs, sizes):
+        assert (o[n:] == -7).all(), "write past the end of an output buffer"
+    return [o[:n] for o, n in zip(outs, sizes)]
+
+
+def check(ids, T, k, E, bm):
+    got = gpu_align(ids, T, k, E, bm)
+    ref = oracle.align(ids.reshape(-1), T, k, E, bm)
+    for name, g, r in zip(("sorted", "tile_expert", "counts", "meta"), got, ref):
+        assert g.dtype == r.dtype and g.shape == r.shape, name
+        assert np.array_equal(g, r), f"{name} differs (T={T} k={k} E={E} bm={bm})"
+
+
+CASES = [
+    # (shape, T, beta, bm)
+    ("tiny", 16, 1.0, 4), ("tiny", 16, 0.2, 4), ("tiny", 16, 0.2, 16), ("tiny", 16, 1.0, 16),
+    ("olmoe", 1, 1.0, 16), ("olmoe", 16, 0.5, 16), ("olmoe", 64, 0.1, 32), ("olmoe", 256, 0.2, 64),
+    ("olmoe", 512, 1.0, 128),   # P = 4096: last single-workgroup size
+    ("olmoe", 513, 1.0, 128),   # first multi-workgroup size, ragged tail
+    ("olmoe", 1024, 0.1, 256), ("olmoe", 4096, 1.0, 256), ("olmoe", 4096, 0.1, 16),
+    ("qwen3", 8192, 0.08, 64), ("qwen3", 2048, 0.3, 16), ("qwen3", 8192, 1.0, 7),
+    ("mixtral", 8192, "zipf1.2", 128), ("mixtral", 1, 1.0, 16), ("mixtral", 1000, "zipf1.2", 104),
+    ("dsv3", 8192, 0.1, 256), ("dsv3", 8192, 1.0, 16), ("dsv3", 64, 0.2, 1), ("dsv3", 2048, 0.2, 32),
+]
+
+
+@pytest.mark.parametrize("name,T,beta,bm", CASES)
+def test_align_bit_exact(name, T, beta, bm):
+    s = synth.SHAPES[name]
+    ids, _ = synth.routing(T, s, beta, seed=T + bm)
+    check(ids, T, s.k, s.E, bm)
+
+
+def test_align_empty_and_single():
+    check(np.zeros((0, 8), np.int32), 0, 8, 64, 16)
+    check(np.array([[5]], np.int32), 1, 1, 8, 4)
+
+
+@pytest.mark.parametrize("T", [40, 3000])
+def test_align_drops_out_of_range_ids(T):
+    rng = np.random.default_rng(T)
+    ids = rng.integers(-3, 70, size=(T, 8)).astype(np.int32)  # E = 64: -3..-1 and 64..69 dropped
+    check(ids, T, 8, 64, 16)
+
+
+def test_align_all_pairs_on_one_expert_and_max_experts():
+    ids = np.full((700, 8), 3, np.int32)
+    check(ids, 700, 8, 64, 256)
+    rng = np.random.default_rng(0)
+    ids = rng.integers(0, 1024, size=(900, 8)).astype(np.int32)
+    check(ids, 900, 8, 1024, 8)     # E at the kernel limit, multi-workgroup
+    check(ids[:100], 100, 8, 1024, 8)  # single workgroup, LDS-heavy
+
+
+def test_align_is_deterministic():
+    s = synth.SHAPES["dsv3"]
+    ids, _ = synth.routing(4096, s, 0.1, seed=1)
+    a = gpu_align(ids, 4096, s.k, s.E, 32)
+    b = gpu_align(ids, 4096, s.k, s.E, 32)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+@pytest.mark.parametrize("name,T,beta", [("olmoe", 64, 0.2), ("dsv3", 8192, 0.1), ("qwen3", 600, 1.0)])
+def test_histogram(name, T, beta):
+    s = synth.SHAPES[name]
+    ids, _ = synth.routing(T, s, beta, seed=3)
+    d_ids = torch.from_numpy(ids.reshape(-1)).to(DEV)
+    counts = torch.full((s.E + 8,), -7, dtype=torch.int32, device=DEV)
+    ws = torch.empty(ramp.align_workspace_bytes(T, s.k, s.E), dtype=torch.uint8, device=DEV)
+    ramp.moe_histogram(d_ids, T, s.k, s.E, counts, ws)
+    torch.cuda.synchronize()
+    got = counts.cpu().numpy()
+    assert (got[s.E:] == -7).all()
+    assert np.array_equal(got[: s.E], oracle.align(ids.reshape(-1), T, s.k, s.E, 16)[2])
+
+
+def test_align_rejects_bad_arguments():
+    ids = torch.zeros(16, dtype=torch.int32, device=DEV)
+    buf = torch.zeros(4096, dtype=torch.int32, device=DEV)
+    with pytest.raises(ramp.RampError) as ei:
+        ramp.moe_align(ids, 2, 8, 2000, 16, buf, buf, buf, buf, None)  # E above the limit
+    assert ei.value.status == ramp.EINVAL
+    big = torch.zeros(8192 * 8, dtype=torch.int32, device=DEV)
+    with pytest.raises(ramp.RampError) as ei:
+        ramp.moe_align(big, 8192, 8, 64, 16, buf, buf, buf, buf, None)  # multi-workgroup path needs a workspace
+    assert ei.value.status == ramp.ENOSPC

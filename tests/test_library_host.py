@@ -1,0 +1,130 @@
+"""Host-side checks of libramp.so that need no GPU: the library loads, exports every symbol the
+header declares, enumerates a sane configuration family, and its cost-model fit/select agree
+with the oracle (predictions and argmin; the raw b/c split is not identifiable)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2604_26039_amd import ramp, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "ramp.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(ramp_[a-z_0-9]+)\s*\(", hdr)))
+    assert declared, "no declarations found"
+    L = ramp.lib()
+    for name in declared:
+        assert hasattr(L, name), f"libramp.so does not export {name}"
+    assert sorted(ramp.EXPORTS) == declared
+
+
+def shape_of(name, T):
+    s = synth.SHAPES[name]
+    return ramp.Shape(T, s.k, s.E, s.H, s.I)
+
+
+@pytest.mark.parametrize("name", ["tiny", "olmoe", "qwen3", "mixtral", "dsv3"])
+def test_config_family(name):
+    sh = shape_of(name, 64)
+    cfgs = ramp.configs(sh)
+    assert len(cfgs) >= 12
+    assert len({c.key() for c in cfgs}) == len(cfgs)
+    bms = {c.bm for c in cfgs}
+    assert {16, 64, 256} <= bms
+    if name == "tiny":
+        assert {4, 16} <= bms
+    for c in cfgs:
+        assert (2 * sh.I) % c.bn == 0 and sh.H % c.bn == 0 and sh.H % c.bk == 0 and sh.I % c.bk == 0
+        assert ramp.config_ntiles(sh, c) == 2 * sh.I // c.bn + sh.H // c.bn
+        W = ramp.config_wave_capacity(c)
+        assert W >= 256 and W % 256 == 0
+        assert ramp.fused_moe_workspace_bytes(sh, c) > 0
+
+
+def test_unknown_config_is_rejected():
+    bad = ramp.Config(24, 64, 128, 2, 2, 0)  # bm=24 is not in the family
+    with pytest.raises(ramp.RampError) as ei:
+        ramp.config_wave_capacity(bad)
+    assert ei.value.status == ramp.EUNSUPPORTED
+    assert "not instantiated" in ramp.last_error()
+
+
+@pytest.mark.parametrize("T,k,E,bm", [(16, 2, 16, 4), (1, 8, 64, 16), (4096, 8, 64, 256), (0, 8, 4, 16), (3, 8, 256, 7)])
+def test_align_capacity_matches_oracle(T, k, E, bm):
+    assert ramp.align_capacity(T, k, E, bm) == oracle.align_capacity(T, k, E, bm)
+
+
+def synthetic_profile(rng, n_cfg, n_pts):
+    W = rng.choice([256, 512, 1024, 2048], n_cfg).astype(np.int32)
+    g = np.empty((n_cfg, n_pts), np.int64)
+    t = np.empty((n_cfg, n_pts), np.float64)
+    for c in range(n_cfg):
+        scale = rng.choice([8, 60, 900])
+        g[c] = rng.integers(1, 40, n_pts) * scale
+        t[c] = 8 + rng.uniform(0.001, 0.05) * g[c] + rng.uniform(0, 4) * np.log(g[c] + 1) + rng.normal(0, 0.3, n_pts)
+    return W, g, t
+
+
+def test_fit_predictions_match_oracle():
+    rng = np.random.default_rng(0)
+    W, g, t = synthetic_profile(rng, 30, 25)
+    theta = ramp.cost_model_fit(W, g, t)
+    saw_log = saw_nolog = False
+    for c in range(30):
+        th_o, use_log = oracle.fit_cost_model(g[c], t[c], int(W[c]))
+        saw_log |= use_log
+        saw_nolog |= not use_log
+        assert (theta[c, 3] != 0) == use_log
+        Xd = oracle.design_matrix(g[c], int(W[c]))
+        q = np.array([1, 7, 100, 5000, 200000], float)
+        Xq = oracle.design_matrix(q, int(W[c]))
+        for X in (Xd, Xq):
+            po, pl = X @ th_o, X @ theta[c].astype(np.float64)
+            assert np.abs(po - pl).max() <= 2e-5 * np.abs(po).max()  # theta is stored as fp32
+        # identifiable quantities
+        assert theta[c, 0] == pytest.approx(th_o[0], rel=1e-5, abs=1e-4)
+        assert theta[c, 1] / W[c] + theta[c, 2] == pytest.approx(th_o[1] / W[c] + th_o[2], rel=1e-5)
+    assert saw_log and saw_nolog
+
+
+def test_fit_handles_constant_grid():
+    # every profiling point has the same grid (T=1: one tile per routed expert whatever the skew)
+    W = np.array([256], np.int32)
+    g = np.full((1, 25), 40, np.int64)
+    t = np.full((1, 25), 17.0) + np.linspace(-0.1, 0.1, 25)[None]
+    theta = ramp.cost_model_fit(W, g, t)
+    th_o, _ = oracle.fit_cost_model(g[0], t[0], 256)
+    x = oracle.design_matrix([40], 256)[0]
+    assert x @ theta[0].astype(float) == pytest.approx(17.0, rel=1e-5)
+    assert x @ th_o == pytest.approx(17.0, rel=1e-9)
+
+
+def test_select_matches_oracle_bit_for_bit():
+    rng = np.random.default_rng(1)
+    sh = shape_of("olmoe", 256)
+    cfgs = ramp.configs(sh)
+    n = len(cfgs)
+    nt = [ramp.config_ntiles(sh, c) for c in cfgs]
+    wc = [ramp.config_wave_capacity(c) for c in cfgs]
+    bm = [c.bm for c in cfgs]
+    for trial in range(25):
+        theta = (np.abs(rng.normal(0, 1, (n, 4))) * [20, 3, 0.02, 2]).astype(np.float32)
+        beta = rng.choice([1.0, 0.5, 0.2, 0.1])
+        counts = synth.histogram_subset(int(rng.choice([1, 16, 64, 256, 1024])), sh.k, sh.E, beta, seed=trial)
+        best, pred = ramp.cost_model_select(sh.E, cfgs, nt, wc, theta, counts, want_pred=True)
+        b_o, p_o = oracle.select(bm, nt, wc, theta, counts)
+        assert best == b_o
+        assert (pred == p_o).all()
+
+
+def test_select_rejects_bad_arguments():
+    sh = shape_of("tiny", 16)
+    cfgs = ramp.configs(sh)[:2]
+    with pytest.raises(ramp.RampError):
+        ramp.cost_model_select(sh.E, cfgs, [1, 1], [0, 256], np.zeros((2, 4), np.float32), np.zeros(sh.E, np.int32))
