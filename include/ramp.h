@@ -151,6 +151,15 @@ int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int3
                            const int32_t *wave_cap, const float *theta,
                            const int32_t *expert_counts, int *best_idx, double *pred_us);
 
+/* ---- measurement hooks --------------------------------------------------------------------------
+ * ramp_probe_enable(stage): from now on every ramp_fused_moe call of this process records a
+ * HIP event pair on its stream around one stage (1 = align, 2 = up-projection + SwiGLU,
+ * 3 = down-projection, 4 = combine; 0 = off).  At most 4096 pairs are kept between reads.
+ * ramp_probe_read: waits for the recorded events, returns the summed stage time and the
+ * number of launches, and clears the list.  For benchmarks; not thread safe. */
+int ramp_probe_enable(int stage);
+int ramp_probe_read(double *total_ms /*host*/, int *launches /*host*/);
+
 /* ---- measurement helper ------------------------------------------------------------------------
  * Plain device copy of `bytes` bytes (multiple of 16, both 16 B aligned): the
  * known-size reference kernel that profiler byte counters are calibrated against. */

@@ -61,6 +61,32 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
     }
 }
 
+// ---- stage probe (benchmark instrumentation) ----
+constexpr int kMaxProbe = 4096;
+int g_probe_stage = 0;
+int g_probe_used = 0;
+int g_probe_created = 0;
+hipEvent_t g_probe_ev[kMaxProbe][2];
+
+struct ProbeScope {
+    bool on;
+    hipStream_t st;
+    ProbeScope(int stage, hipStream_t stream) : on(false), st(stream)
+    {
+        if (stage != g_probe_stage || g_probe_used >= kMaxProbe) return;
+        if (g_probe_used >= g_probe_created) {
+            if (hipEventCreate(&g_probe_ev[g_probe_created][0]) != hipSuccess) return;
+            if (hipEventCreate(&g_probe_ev[g_probe_created][1]) != hipSuccess) return;
+            ++g_probe_created;
+        }
+        on = hipEventRecord(g_probe_ev[g_probe_used][0], st) == hipSuccess;
+    }
+    ~ProbeScope()
+    {
+        if (on && hipEventRecord(g_probe_ev[g_probe_used][1], st) == hipSuccess) ++g_probe_used;
+    }
+};
+
 struct Workspace {
     size_t sorted, tile_expert, counts, meta, align_ws, a_buf, y_buf, total;
     size_t cap, align_ws_bytes;
@@ -280,8 +306,12 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     uint16_t *a_buf = reinterpret_cast<uint16_t *>(base + w.a_buf);
     float *y_buf = reinterpret_cast<float *>(base + w.y_buf);
 
-    int rc = launch_align(topk_ids, s.T, s.k, s.E, cfg->bm, sorted, tile_expert, counts, meta, base + w.align_ws,
+    int rc;
+    {
+        ProbeScope probe(1, st);
+        rc = launch_align(topk_ids, s.T, s.k, s.E, cfg->bm, sorted, tile_expert, counts, meta, base + w.align_ws,
                           w.align_ws_bytes, st);
+    }
     if (rc) return rc;
 
     const PackedLayout L = packed_layout(s);
@@ -305,7 +335,10 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     g.K = s.H;
     g.F = s.I;
     g.n_tiles = 2 * s.I / cfg->bn;
-    ki->launch(1, g, st);
+    {
+        ProbeScope probe(2, st);
+        ki->launch(1, g, st);
+    }
     rc = check_launch("moe_gemm_kernel<1>");
     if (rc) return rc;
 
@@ -317,9 +350,46 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     g.K = s.I;
     g.F = s.H;
     g.n_tiles = s.H / cfg->bn;
-    ki->launch(2, g, st);
+    {
+        ProbeScope probe(3, st);
+        ki->launch(2, g, st);
+    }
     rc = check_launch("moe_gemm_kernel<2>");
     if (rc) return rc;
 
+    ProbeScope probe(4, st);
     return launch_combine(y_buf, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st);
+}
+
+extern "C" int ramp_probe_enable(int stage)
+{
+    if (stage < 0 || stage > 4) {
+        set_error("probe_enable: stage must be 0..4");
+        return RAMP_EINVAL;
+    }
+    g_probe_stage = stage;
+    return RAMP_OK;
+}
+
+extern "C" int ramp_probe_read(double *total_ms, int *launches)
+{
+    if (!total_ms || !launches) {
+        set_error("probe_read: NULL argument");
+        return RAMP_EINVAL;
+    }
+    double sum = 0.0;
+    for (int i = 0; i < g_probe_used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_probe_ev[i][1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_probe_ev[i][0], g_probe_ev[i][1]) != hipSuccess) {
+            set_error("probe_read: event query failed");
+            g_probe_used = 0;
+            return RAMP_EHIP;
+        }
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = g_probe_used;
+    g_probe_used = 0;
+    return RAMP_OK;
 }

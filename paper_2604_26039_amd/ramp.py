@@ -88,6 +88,10 @@ def lib() -> ctypes.CDLL:
         L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp]
         L.ramp_cost_model_select.restype = ci
         L.ramp_cost_model_select.argtypes = [ci, ci, cp, vp, vp, vp, vp, ctypes.POINTER(ci), vp]
+        L.ramp_probe_enable.restype = ci
+        L.ramp_probe_enable.argtypes = [ci]
+        L.ramp_probe_read.restype = ci
+        L.ramp_probe_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
         L.ramp_copy_bytes.restype = ci
         L.ramp_copy_bytes.argtypes = [vp, vp, sz, vp]
         _lib = L
@@ -98,7 +102,7 @@ EXPORTS = [
     "ramp_last_error", "ramp_num_configs", "ramp_get_config", "ramp_config_ntiles", "ramp_config_wave_capacity",
     "ramp_align_capacity", "ramp_align_workspace_bytes", "ramp_moe_histogram", "ramp_moe_align", "ramp_pack_bytes",
     "ramp_pack_weights", "ramp_fused_moe_workspace_bytes", "ramp_fused_moe_workspace_layout", "ramp_fused_moe",
-    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_copy_bytes",
+    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_copy_bytes", "ramp_probe_enable", "ramp_probe_read",
 ]
 
 
@@ -208,6 +212,17 @@ def fused_moe(shape: Shape, cfg: Config, X, topk_ids, topk_w, packed_weights, ou
     _check(lib().ramp_fused_moe(ctypes.byref(shape), ctypes.byref(cfg), _dev(X), _dev(topk_ids), _dev(topk_w),
                                 _dev(packed_weights), _dev(out), _dev(ws), ws.numel() * ws.element_size(),
                                 _stream(stream)))
+
+
+def probe_enable(stage: int):
+    _check(lib().ramp_probe_enable(stage))
+
+
+def probe_read():
+    """Returns (total_ms, launches) of the probed stage since the last read."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int(0)
+    _check(lib().ramp_probe_read(ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
 
 
 def copy_bytes(dst: torch.Tensor, src: torch.Tensor, nbytes: int, stream=None):

@@ -1,0 +1,188 @@
+"""One-time profiling, cost-model fitting and dispatch on top of the C ABI (paper Sec. 4.2
+"Fitting", Sec. 4.4, Sec. 5.1 protocol).
+
+Nothing here computes the layer: it allocates device buffers with torch, calls the library,
+times it with HIP events and feeds grids/times to ramp_cost_model_fit / ramp_cost_model_select.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Sequence
+
+import numpy as np
+import torch
+
+from . import ramp, synth
+
+
+def fit_batch_sizes(sweep_T: Sequence[int], n: int = 5) -> List[int]:
+    """Profiling batch sizes: n log-spaced values from 2 up to half of the largest benchmark
+    batch, so the largest benchmark batch is an extrapolation (Sec. 5.2)."""
+    hi = max(4, max(sweep_T) // 2)
+    vals = np.unique(np.round(np.geomspace(2, hi, n)).astype(int))
+    return [int(v) for v in vals]
+
+
+FIT_BETAS = [1.0, 0.7, 0.4, 0.25, 0.12]  # none of them is a benchmark skew level
+
+
+class LayerSet:
+    """`n_layers` copies of one synthetic MoE layer (distinct weights at distinct addresses), so a
+    timing loop that walks over them reads weights from HBM as a model's layers would, instead
+    of re-reading one layer out of the 256 MB last-level cache."""
+
+    def __init__(self, shape: synth.Shape, T_max: int, n_layers: int, seed: int, device="cuda:0", x_std=None):
+        self.shape, self.T_max, self.device = shape, T_max, device
+        self.packed = []
+        self.X = None
+        for l in range(n_layers):
+            X, Wg, Wu, Wd = synth.layer_tensors(shape, T_max if l == 0 else 1, seed + 7919 * l, device=device, x_std=x_std)
+            if l == 0:
+                self.X = X
+            rs = ramp.Shape(T_max, shape.k, shape.E, shape.H, shape.I)
+            buf = torch.empty(ramp.pack_bytes(rs), dtype=torch.uint8, device=device)
+            ramp.pack_weights(rs, Wg, Wu, Wd, buf)
+            torch.cuda.synchronize()
+            self.packed.append(buf)
+            if l == 0:
+                self.raw0 = (Wg, Wu, Wd)  # kept for oracle checks
+            else:
+                del Wg, Wu, Wd
+        self.n_layers = n_layers
+        self._ws = None
+        self.out = torch.empty((T_max, shape.H), dtype=torch.bfloat16, device=device)
+
+    def rs(self, T: int) -> ramp.Shape:
+        s = self.shape
+        return ramp.Shape(T, s.k, s.E, s.H, s.I)
+
+    def workspace(self, nbytes: int) -> torch.Tensor:
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = None
+            self._ws = torch.empty(int(nbytes * 1.25) + 4096, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+
+@dataclass
+class Point:
+    T: int
+    beta: object
+    seed: int
+    ids: np.ndarray = field(repr=False, default=None)
+    w: np.ndarray = field(repr=False, default=None)
+    counts: np.ndarray = field(repr=False, default=None)
+
+    def materialise(self, shape: synth.Shape):
+        if self.ids is None:
+            self.ids, self.w = synth.routing(self.T, shape, self.beta, self.seed)
+            self.counts = np.bincount(self.ids.reshape(-1), minlength=shape.E).astype(np.int32)
+        return self
+
+
+def time_config(layers: LayerSet, cfg: ramp.Config, pt: Point, warmup: int = 10, iters: int = 50,
+                budget_ms: float = 400.0) -> float:
+    """Median time in microseconds of ramp_fused_moe(cfg) at one operating point, HIP events
+    around each call, walking over the layer copies (Sec. 5.1: 10 warm-up + 50 timed, median).
+    The iteration count is cut so one measurement stays within budget_ms."""
+    pt.materialise(layers.shape)
+    T = pt.T
+    rs = layers.rs(T)
+    dev = layers.device
+    d_ids = torch.from_numpy(pt.ids).to(dev)
+    d_w = torch.from_numpy(pt.w).to(dev)
+    ws = layers.workspace(ramp.fused_moe_workspace_bytes(rs, cfg))
+    X = layers.X[:T]
+    out = layers.out[:T]
+    L = layers.n_layers
+
+    def call(i):
+        ramp.fused_moe(rs, cfg, X, d_ids, d_w, layers.packed[i % L], out, ws)
+
+    # one probing call decides how many iterations the budget allows
+    call(0)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    call(1)
+    e1.record()
+    torch.cuda.synchronize()
+    one = max(e0.elapsed_time(e1), 1e-3)
+    iters = int(max(5, min(iters, budget_ms / one)))
+    warmup = int(max(1, min(warmup, iters // 3)))
+    for i in range(warmup):
+        call(i)
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    for i in range(iters):
+        starts[i].record()
+        call(i)
+        stops[i].record()
+    torch.cuda.synchronize()
+    t = np.array([s.elapsed_time(e) for s, e in zip(starts, stops)]) * 1e3
+    return float(np.median(t))
+
+
+@dataclass
+class Family:
+    shape: ramp.Shape
+    cfgs: List[ramp.Config]
+    ntiles: np.ndarray
+    wave_cap: np.ndarray
+
+    @staticmethod
+    def of(s: synth.Shape, T: int = 1) -> "Family":
+        rs = ramp.Shape(T, s.k, s.E, s.H, s.I)
+        cfgs = ramp.configs(rs)
+        return Family(rs, cfgs, np.array([ramp.config_ntiles(rs, c) for c in cfgs], np.int32),
+                      np.array([ramp.config_wave_capacity(c) for c in cfgs], np.int32))
+
+    def grid(self, counts: np.ndarray) -> np.ndarray:
+        """Eq. 1 for every configuration."""
+        c = np.asarray(counts, np.int64)
+        return np.array([int((-(-c // cfg.bm)).sum()) * int(nt) for cfg, nt in zip(self.cfgs, self.ntiles)], np.int64)
+
+
+def profile(layers: LayerSet, fam: Family, points: Sequence[Point], log=None, **timing) -> tuple:
+    """Times every configuration at every point.  Returns (grid [n_cfg,n_pts], time_us [n_cfg,n_pts])."""
+    n_cfg, n_pts = len(fam.cfgs), len(points)
+    grid = np.zeros((n_cfg, n_pts), np.int64)
+    t_us = np.zeros((n_cfg, n_pts), np.float64)
+    for j, pt in enumerate(points):
+        pt.materialise(layers.shape)
+        grid[:, j] = fam.grid(pt.counts)
+        for i, cfg in enumerate(fam.cfgs):
+            t_us[i, j] = time_config(layers, cfg, pt, **timing)
+        if log:
+            b = int(np.argmin(t_us[:, j]))
+            log(f"  T={pt.T:<5} beta={pt.beta!s:<8} best {t_us[b, j]:9.1f} us  {fam.cfgs[b]}")
+    return grid, t_us
+
+
+def fit(fam: Family, grid: np.ndarray, t_us: np.ndarray) -> np.ndarray:
+    return ramp.cost_model_fit(fam.wave_cap, grid, t_us)
+
+
+def select(fam: Family, theta: np.ndarray, counts: np.ndarray) -> int:
+    return ramp.cost_model_select(fam.shape.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, counts)
+
+
+def entropy_beta(counts) -> float:
+    """The paper's balancedness (Sec. 2.1), reported next to the subset fraction."""
+    c = np.asarray(counts, np.float64)
+    tot = c.sum()
+    if tot <= 0 or c.size <= 1:
+        return 1.0
+    p = c[c > 0] / tot
+    return float(-(p * np.log(p)).sum() / math.log(c.size))
+
+
+def roofline_lower_bound_us(s: synth.Shape, T: int, counts: np.ndarray, hbm_tbs: float = 8.0,
+                            mfma_pflops: float = 2.5):
+    """Algorithmic minimum time: weights of the active experts once + activations in/out + routing,
+    against HBM peak; 6*P*H*I flops against dense bf16 MFMA peak.  Returns (t_hbm, t_mfma, bytes, flops)."""
+    e_act = int((np.asarray(counts) > 0).sum())
+    P = int(np.asarray(counts).sum())
+    nbytes = e_act * 3 * s.H * s.I * 2 + 2 * T * s.H * 2 + P * 8
+    flops = 6.0 * P * s.H * s.I
+    return nbytes / (hbm_tbs * 1e12) * 1e6, flops / (mfma_pflops * 1e15) * 1e6, nbytes, flops
