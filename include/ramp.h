@@ -56,7 +56,10 @@ typedef struct {
  *   stages LDS pipeline depth
  *   mode   kernel variant: bits 0-7 = (wavefront rows along the token dimension) - 1, i.e. how
  *          the `waves` wavefronts are arranged over the tile (tokens x features);
- *          bits 8.. = 0 for the LDS-staged two-phase path */
+ *          bits 8.. = 0 for the LDS-staged path; 0x100 | WK selects the weight-streaming
+ *          path for small token blocks (weights go from HBM straight into MFMA operand
+ *          registers, the K reduction is split WK ways over the workgroup's wavefronts;
+ *          bk is then the k-extent of one register load batch) */
 typedef struct {
     int32_t bm, bn, bk, waves, stages, mode;
 } ramp_config;

@@ -10,6 +10,8 @@ void register_group0(KernelInfo *, int *);
 void register_group1(KernelInfo *, int *);
 void register_group2(KernelInfo *, int *);
 void register_group3(KernelInfo *, int *);
+void register_stream_group0(KernelInfo *, int *);
+void register_stream_group1(KernelInfo *, int *);
 
 namespace {
 constexpr int kMaxKernels = 128;
@@ -24,6 +26,8 @@ void init_registry()
         register_group1(g_kernels, &g_num_kernels);
         register_group2(g_kernels, &g_num_kernels);
         register_group3(g_kernels, &g_num_kernels);
+        register_stream_group0(g_kernels, &g_num_kernels);
+        register_stream_group1(g_kernels, &g_num_kernels);
     });
 }
 
