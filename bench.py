@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--heldout", type=int, default=0, help="extra seeded held-out histograms for regret (dsv3: 200)")
     ap.add_argument("--iters", type=int, default=50)
+    ap.add_argument("--config", default=None,
+                    help="bm,bn,bk,waves,stages,mode: skip profiling/fit and run the headline with this fixed "
+                         "configuration (for profiler runs)")
     ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out"))
     args = ap.parse_args()
 
@@ -82,12 +85,28 @@ def main():
     log(f"[bench] {args.model}: H={s.H} I={s.I} E={s.E} k={s.k}; {n_cfg} configurations; {n_layers} weight copies "
         f"({layer_bytes * n_layers / 2**30:.1f} GiB); setup {time.time() - t0:.1f}s")
 
+    fixed_cfg = None
+    if args.config:
+        want = tuple(int(v) for v in args.config.split(","))
+        match = [i for i, c in enumerate(fam.cfgs) if c.key() == want]
+        assert match, f"configuration {want} is not in the family for this shape"
+        fixed_cfg = match[0]
+        args.no_sweep = True
+
     # ------------------------------------------------------------------ one-time profiling + fit (Sec. 4.2)
     fit_T = tuner.fit_batch_sizes(sweep["T"])
     fit_pts = [tuner.Point(T, b, seed=100000 + 97 * i + j) for i, T in enumerate(fit_T) for j, b in enumerate(tuner.FIT_BETAS)]
     t0 = time.time()
+    if fixed_cfg is not None:
+        fit_pts = fit_pts[:2]
     log(f"[bench] profiling {len(fit_pts)} fit points x {n_cfg} configs (T in {fit_T}, beta in {tuner.FIT_BETAS})")
-    g_fit, t_fit = tuner.profile(layers, fam, fit_pts, iters=min(args.iters, 30), warmup=5, budget_ms=150.0)
+    if fixed_cfg is None:
+        g_fit, t_fit = tuner.profile(layers, fam, fit_pts, iters=min(args.iters, 30), warmup=5, budget_ms=150.0)
+    else:
+        for pt in fit_pts:
+            pt.materialise(s)
+        g_fit = np.stack([fam.grid(pt.counts) for pt in fit_pts], axis=1)
+        t_fit = np.ones_like(g_fit, dtype=np.float64)
     theta = tuner.fit(fam, g_fit, t_fit)
     pred_fit = np.array([[ramp.cost_model_select(s.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, p.counts, want_pred=True)[1][c]
                           for p in fit_pts] for c in range(n_cfg)])
@@ -175,6 +194,8 @@ def main():
         h_counts.copy_(d_counts, non_blocking=True)
         torch.cuda.current_stream().synchronize()          # the path's one host sync (Sec. 4.4)
         c = tuner.select(fam, theta, h_counts.numpy())
+        if fixed_cfg is not None:
+            c = fixed_cfg
         ramp.fused_moe(rs, fam.cfgs[c], X, d_ids, d_w, layers.packed[i % layers.n_layers], out, ws)
         return c
 

@@ -10,6 +10,8 @@ void register_group0(KernelInfo *, int *);
 void register_group1(KernelInfo *, int *);
 void register_group2(KernelInfo *, int *);
 void register_group3(KernelInfo *, int *);
+void register_group4(KernelInfo *, int *);
+void register_group5(KernelInfo *, int *);
 void register_stream_group0(KernelInfo *, int *);
 void register_stream_group1(KernelInfo *, int *);
 
@@ -26,6 +28,8 @@ void init_registry()
         register_group1(g_kernels, &g_num_kernels);
         register_group2(g_kernels, &g_num_kernels);
         register_group3(g_kernels, &g_num_kernels);
+        register_group4(g_kernels, &g_num_kernels);
+        register_group5(g_kernels, &g_num_kernels);
         register_stream_group0(g_kernels, &g_num_kernels);
         register_stream_group1(g_kernels, &g_num_kernels);
     });
@@ -33,31 +37,41 @@ void init_registry()
 
 // out[t,:] = sum_j Y[t*k+j,:] in increasing j, fp32, one rounding to bf16.  The router weight
 // was applied by the down-projection epilogue.  Pairs with an invalid expert id have no row.
+// Y rows are fp32, or bf16 (Y16) for large batches.
+template <bool Y16>
 __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ Y, const int32_t *__restrict__ ids, int T,
                                                       int k, int E, int H, uint16_t *__restrict__ out)
 {
-    const int hv = H / 4;  // float4 columns
+    const int hv = H / 4;  // 4-feature columns
     const size_t total = (size_t)T * hv;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int t = (int)(i / hv), c = (int)(i % hv);
-        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        float s[4] = {0.f, 0.f, 0.f, 0.f};
         for (int j = 0; j < k; ++j) {
             const int id = ids[(size_t)t * k + j];
             if (id < 0 || id >= E) continue;
-            const float4 y = *reinterpret_cast<const float4 *>(Y + ((size_t)t * k + j) * H + (size_t)c * 4);
-            s.x += y.x;
-            s.y += y.y;
-            s.z += y.z;
-            s.w += y.w;
+            const size_t elem = ((size_t)t * k + j) * H + (size_t)c * 4;
+            if (Y16) {
+                const uint2 y = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(Y) + elem);
+                s[0] += __builtin_bit_cast(float, y.x << 16);
+                s[1] += __builtin_bit_cast(float, y.x & 0xffff0000u);
+                s[2] += __builtin_bit_cast(float, y.y << 16);
+                s[3] += __builtin_bit_cast(float, y.y & 0xffff0000u);
+            } else {
+                const float4 y = *reinterpret_cast<const float4 *>(Y + elem);
+                s[0] += y.x;
+                s[1] += y.y;
+                s[2] += y.z;
+                s[3] += y.w;
+            }
         }
-        const float v[4] = {s.x, s.y, s.z, s.w};
         union {
             uint16_t h[4];
             uint2 u;
         } o;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            uint32_t b = __builtin_bit_cast(uint32_t, v[q]);
+            uint32_t b = __builtin_bit_cast(uint32_t, s[q]);
             b += 0x7fffu + ((b >> 16) & 1u);
             o.h[q] = (uint16_t)(b >> 16);
         }
@@ -90,6 +104,8 @@ struct ProbeScope {
         if (on && hipEventRecord(g_probe_ev[g_probe_used][1], st) == hipSuccess) ++g_probe_used;
     }
 };
+
+constexpr size_t kPairRowsBf16Elems = (size_t)8 << 20;
 
 struct Workspace {
     size_t sorted, tile_expert, counts, meta, align_ws, a_buf, y_buf, total;
@@ -175,13 +191,17 @@ int occupancy_estimate(const KernelInfo &ki)
     return occ < 1 ? 1 : occ;
 }
 
-int launch_combine(const float *Y, const int32_t *ids, int T, int k, int E, int H, uint16_t *out, hipStream_t stream)
+int launch_combine(const float *Y, int y_bf16, const int32_t *ids, int T, int k, int E, int H, uint16_t *out,
+                   hipStream_t stream)
 {
     if (T == 0) return RAMP_OK;
     size_t total = (size_t)T * (H / 4);
     unsigned grid = (unsigned)((total + 255) / 256);
     if (grid > (unsigned)kNumCU * 16) grid = kNumCU * 16;
-    hipLaunchKernelGGL(combine_kernel, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out);
+    if (y_bf16)
+        hipLaunchKernelGGL(combine_kernel<true>, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out);
+    else
+        hipLaunchKernelGGL(combine_kernel<false>, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out);
     return check_launch("combine_kernel");
 }
 
@@ -327,6 +347,8 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     g.topk_w = topk_w;
     g.a_out = a_buf;
     g.y_out = y_buf;
+    // per-pair rows: fp32 while they are small, bf16 once they would exceed 32 MB
+    g.y_bf16 = ((size_t)s.T * s.k * s.H >= kPairRowsBf16Elems) ? 1 : 0;
     g.P = s.T * s.k;
     g.topk = s.k;
     g.m_tiles_cap = (int)(w.cap / (size_t)cfg->bm);
@@ -362,7 +384,7 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     if (rc) return rc;
 
     ProbeScope probe(4, st);
-    return launch_combine(y_buf, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st);
+    return launch_combine(y_buf, g.y_bf16, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st);
 }
 
 extern "C" int ramp_probe_enable(int stage)

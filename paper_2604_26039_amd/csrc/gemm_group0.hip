@@ -5,7 +5,7 @@
 namespace ramp {
 void register_group0(KernelInfo *out, int *n)
 {
-#define X(BM, BN, BK, WM, WN, NS) out[(*n)++] = make_info<BM, BN, BK, WM, WN, NS>();
+#define X(BM, BN, BK, WM, WN, NS, PIPE) out[(*n)++] = make_info<BM, BN, BK, WM, WN, NS, PIPE>();
     RAMP_CONFIG_GROUP0(X)
 #undef X
 }

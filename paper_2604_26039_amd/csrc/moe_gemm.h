@@ -60,6 +60,24 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
 
 __device__ __forceinline__ float silu_f32(float x) { return x / (1.0f + __expf(-x)); }
 
+// Four consecutive features of one weighted per-pair output row: fp32, or bf16 for large batches.
+__device__ __forceinline__ void store_pair_row(const GemmArgs &a, size_t elem, float v0, float v1, float v2, float v3)
+{
+    if (a.y_bf16) {
+        union {
+            uint16_t h[4];
+            uint2 v;
+        } o;
+        o.h[0] = f32_to_bf16_bits(v0);
+        o.h[1] = f32_to_bf16_bits(v1);
+        o.h[2] = f32_to_bf16_bits(v2);
+        o.h[3] = f32_to_bf16_bits(v3);
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y_out) + elem) = o.v;
+    } else {
+        *reinterpret_cast<float4 *>(a.y_out + elem) = make_float4(v0, v1, v2, v3);
+    }
+}
+
 // 16 bytes per lane from global memory straight into LDS at lds_base + lane*16.
 __device__ __forceinline__ void load_to_lds_16B(const void *gptr, void *lds_base)
 {
@@ -75,7 +93,7 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE, bool PIPE>
 __global__ __launch_bounds__(WM *WN * 64) void moe_gemm_kernel(GemmArgs a)
 {
     using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
@@ -86,8 +104,19 @@ __global__ __launch_bounds__(WM *WN * 64) void moe_gemm_kernel(GemmArgs a)
 
     __shared__ __attribute__((aligned(1024))) uint16_t lds[NSTAGE * TT::BUF_ELEMS];
 
-    const int n_tile = blockIdx.x % a.n_tiles;
-    const int m_tile = blockIdx.x / a.n_tiles;
+    // Workgroup -> tile.  Workgroups are handed to the 8 XCDs round robin (id % 8), each XCD has
+    // its own 4 MB L2 and runs 32 workgroups of this size at a time.  Consecutive workgroups of
+    // one XCD therefore take a block of group_m M-tiles x all N-tiles: the token slices are shared
+    // by the N-tiles and the weight slices by the M-tiles of the same expert while they are
+    // still in that XCD's L2 (the XCD-aware analogue of the GROUP_M swizzle, Sec. 4.1 Eq. 4).
+    int n_tile, m_tile;
+    {
+        const int xcd = blockIdx.x & 7, s = blockIdx.x >> 3;
+        const int per_group = a.group_m * a.n_tiles;
+        const int gi = s / per_group, r = s - gi * per_group;
+        n_tile = r / a.group_m;
+        m_tile = (gi * 8 + xcd) * a.group_m + (r - n_tile * a.group_m);
+    }
     if (m_tile >= a.meta[1]) return;  // overlaunched grid: surplus workgroups leave at once
 
     const int lane = threadIdx.x & 63;
@@ -149,29 +178,116 @@ __global__ __launch_bounds__(WM *WN * 64) void moe_gemm_kernel(GemmArgs a)
             gptr[s] += gstep[s];
         }
     };
+    // Padding sits at the end of a tile, so this wavefront's token blocks are real up to some
+    // block and sentinel-only after it: the products of all-padding blocks are skipped (the ragged
+    // last tile of an expert then costs its loads but only the MFMAs of its real rows).
+    int nb_valid = 0;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int tr0 = (wm * NB + nb) * 16;
+        if (tr0 < BM && a.sorted[m_tile * BM + tr0] < a.P) nb_valid = nb + 1;
+    }
+    nb_valid = __builtin_amdgcn_readfirstlane(nb_valid);
+
     auto compute_slice = [&](int buf) {
         const uint16_t *xs = &lds[buf * TT::BUF_ELEMS + lane * 8];
         const uint16_t *ws = xs + TT::X_FRAGS * kFragElems;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 b[NB];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                b[nb] = *reinterpret_cast<const bf16x8 *>(xs + ((wm * NB + nb) * KS + ks) * kFragElems);
+            bf16x8 w[NACC];
 #pragma unroll
             for (int i = 0; i < NACC; ++i) {
                 int rb;
                 if (STAGE == 1) rb = (i < FB) ? (wn * FB + i) : (TT::RB / 2 + wn * FB + (i - FB));
                 else rb = wn * FB + i;
-                const bf16x8 w = *reinterpret_cast<const bf16x8 *>(ws + (rb * KS + ks) * kFragElems);
+                w[i] = *reinterpret_cast<const bf16x8 *>(ws + (rb * KS + ks) * kFragElems);
+            }
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, b[nb], acc[i][nb], 0, 0, 0);
+            for (int nb = 0; nb < NB; ++nb) {
+                if (nb < nb_valid) {
+                    const bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + ((wm * NB + nb) * KS + ks) * kFragElems);
+#pragma unroll
+                    for (int i = 0; i < NACC; ++i)
+                        acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[i], b, acc[i][nb], 0, 0, 0);
+                }
             }
         }
     };
 
     const int KT = K / BK;
+    if constexpr (PIPE) {
+        // Register-pipelined main loop for one wavefront per SIMD: two register sets of operand
+        // fragments; while the MFMAs of k-step g run on one set, the ds_reads of k-step g+1 fill
+        // the other.  All NSTAGE buffers are kept full: at the last k-step of slice kt every
+        // wavefront already holds its last fragments of that slice in registers, so after one
+        // barrier the buffer is handed to the loads of slice kt+NSTAGE.
+        static_assert(!PIPE || KS % 2 == 0, "register sets alternate per k-step: bk must be a multiple of 64");
+        bf16x8 fx[2][NB], fw[2][NACC];
+        auto read_frags = [&](int set, int buf, int ks) {
+            const uint16_t *xs = &lds[buf * TT::BUF_ELEMS + lane * 8];
+            const uint16_t *ws = xs + TT::X_FRAGS * kFragElems;
+#pragma unroll
+            for (int i = 0; i < NACC; ++i) {
+                int rb;
+                if (STAGE == 1) rb = (i < FB) ? (wn * FB + i) : (TT::RB / 2 + wn * FB + (i - FB));
+                else rb = wn * FB + i;
+                fw[set][i] = *reinterpret_cast<const bf16x8 *>(ws + (rb * KS + ks) * kFragElems);
+            }
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                fx[set][nb] = *reinterpret_cast<const bf16x8 *>(xs + ((wm * NB + nb) * KS + ks) * kFragElems);
+        };
+        auto mfma_step = [&](int set) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                if (nb < nb_valid) {
+#pragma unroll
+                    for (int i = 0; i < NACC; ++i)
+                        acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[set][i], fx[set][nb], acc[i][nb], 0, 0, 0);
+                }
+            }
+        };
+        auto wait_for_next = [&](int later) {  // `later` younger slices may stay in flight
+            if (NSTAGE >= 4 && later >= 2) wait_vmcnt<(NSTAGE >= 4 ? 2 : 0) * SLOTS>();
+            else if (NSTAGE >= 3 && later >= 1) wait_vmcnt<(NSTAGE >= 3 ? 1 : 0) * SLOTS>();
+            else wait_vmcnt<0>();
+        };
+#pragma unroll
+        for (int s = 0; s < NSTAGE; ++s)
+            if (s < KT) issue_slice(s);
+        wait_for_next(min(NSTAGE - 1, KT - 1));
+        __builtin_amdgcn_s_barrier();
+        read_frags(0, 0, 0);
+#ifdef RAMP_ABL_NOLDS
+        read_frags(1, 0, 1);
+#endif
+        int buf_cur = 0;
+        for (int kt = 0; kt < KT; ++kt) {
+            const int buf_next = (buf_cur + 1 == NSTAGE) ? 0 : buf_cur + 1;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int cur = ks & 1, nxt = cur ^ 1;
+                if (ks + 1 < KS) {
+#ifndef RAMP_ABL_NOLDS
+                    read_frags(nxt, buf_cur, ks + 1);
+#endif
+                } else if (kt + 1 < KT) {
+                    // every fragment of slice kt is in registers by now (requested one k-step ago)
+                    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): no LDS read of this buffer pending
+                    wait_for_next(min(NSTAGE - 2, KT - 2 - kt));
+                    __builtin_amdgcn_s_barrier();
+#ifndef RAMP_ABL_NOLOAD
+                    if (kt + NSTAGE < KT) issue_slice(buf_cur);
+#endif
+#ifndef RAMP_ABL_NOLDS
+                    read_frags(nxt, buf_next, 0);
+#endif
+                }
+                mfma_step(cur);
+            }
+            buf_cur = buf_next;
+        }
+    } else {
     // prologue: slices 0 .. NSTAGE-2 in flight
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s)
@@ -192,12 +308,13 @@ __global__ __launch_bounds__(WM *WN * 64) void moe_gemm_kernel(GemmArgs a)
         buf_cur = (buf_cur + 1 == NSTAGE) ? 0 : buf_cur + 1;
         buf_issue = (buf_issue + 1 == NSTAGE) ? 0 : buf_issue + 1;
     }
+    }
 
     // ---- epilogue: lane holds features f = fblock*16 + 4*q + {0..3} of token n = r16 ----
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int tr = (wm * NB + nb) * 16 + r16;
-        if (tr >= BM) continue;
+        if (tr >= BM || nb >= nb_valid) continue;
         const int slot = m_tile * BM + tr;
         if (STAGE == 1) {
 #pragma unroll
@@ -220,35 +337,43 @@ __global__ __launch_bounds__(WM *WN * 64) void moe_gemm_kernel(GemmArgs a)
             for (int i = 0; i < FB; ++i) {
                 const floatx4 y = acc[i][nb];
                 const int f = f0 + (wn * FB + i) * 16 + q * 4;
-                float4 o = make_float4(wgt * y[0], wgt * y[1], wgt * y[2], wgt * y[3]);
-                *reinterpret_cast<float4 *>(a.y_out + (size_t)pair * a.F + f) = o;
+                store_pair_row(a, (size_t)pair * a.F + f, wgt * y[0], wgt * y[1], wgt * y[2], wgt * y[3]);
             }
         }
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, bool PIPE>
 void launch_gemm(int stage, const GemmArgs &a, hipStream_t stream)
 {
-    const dim3 grid((unsigned)a.n_tiles * (unsigned)a.m_tiles_cap), block(WM * WN * 64);
-    if (grid.x == 0) return;
+    if (a.n_tiles <= 0 || a.m_tiles_cap <= 0) return;
+    GemmArgs g = a;
+    // 32 workgroups of an XCD run together: group_m M-tiles x n_tiles N-tiles of them share operands
+    g.group_m = 32 / a.n_tiles;
+    if (g.group_m < 1) g.group_m = 1;
+    if (g.group_m > 8) g.group_m = 8;
+    const int per_round = 8 * g.group_m;  // M-tiles handed out per round over the 8 XCDs
+    const int rounds = (a.m_tiles_cap + per_round - 1) / per_round;
+    const dim3 grid((unsigned)rounds * (unsigned)per_round * (unsigned)a.n_tiles), block(WM * WN * 64);
     if (stage == 1)
-        hipLaunchKernelGGL((moe_gemm_kernel<1, BM, BN, BK, WM, WN, NSTAGE>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL((moe_gemm_kernel<1, BM, BN, BK, WM, WN, NSTAGE, PIPE>), grid, block, 0, stream, g);
     else
-        hipLaunchKernelGGL((moe_gemm_kernel<2, BM, BN, BK, WM, WN, NSTAGE>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL((moe_gemm_kernel<2, BM, BN, BK, WM, WN, NSTAGE, PIPE>), grid, block, 0, stream, g);
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+constexpr int kModePipe = 0x200;  // config.mode bit: register-pipelined main loop
+
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, bool PIPE>
 KernelInfo make_info()
 {
     using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
     KernelInfo ki;
-    ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, WM - 1};
+    ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | (PIPE ? kModePipe : 0)};
     ki.wm = WM;
     ki.wn = WN;
     ki.lds_bytes = TT::LDS_BYTES;
     ki.acc_regs = TT::ACC_REGS;
-    ki.launch = &launch_gemm<BM, BN, BK, WM, WN, NSTAGE>;
+    ki.launch = &launch_gemm<BM, BN, BK, WM, WN, NSTAGE, PIPE>;
     return ki;
 }
 

@@ -184,8 +184,8 @@ __global__ __launch_bounds__(WF *WK * 64) void moe_stream_kernel(GemmArgs a)
 #pragma unroll
             for (int i = 0; i < FPW; ++i) {
                 const floatx4 y = acc[i][nb];
-                float4 o = make_float4(wgt * y[0], wgt * y[1], wgt * y[2], wgt * y[3]);
-                *reinterpret_cast<float4 *>(a.y_out + (size_t)pair * a.F + f0 + i * 16 + q * 4) = o;
+                store_pair_row(a, (size_t)pair * a.F + f0 + i * 16 + q * 4, wgt * y[0], wgt * y[1], wgt * y[2],
+                               wgt * y[3]);
             }
         }
     }

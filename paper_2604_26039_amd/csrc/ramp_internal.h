@@ -30,8 +30,8 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- align ----
 constexpr int kAlignThreads = 1024;   // one workgroup = 16 wavefronts
-constexpr int kAlignChunk = 4096;     // pairs per workgroup in the multi-workgroup path
-constexpr int kAlignSingleMaxP = 4096; // up to this many pairs one workgroup does everything
+constexpr int kAlignChunk = 1024;     // pairs per workgroup in the multi-workgroup path
+constexpr int kAlignSingleMaxP = 2048; // up to this many pairs one workgroup does everything
 constexpr int kAlignMaxE = 1024;
 
 int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
@@ -61,13 +61,15 @@ struct GemmArgs {
     const int32_t *meta;        // [4]
     const float *topk_w;        // stage 2: [P]
     uint16_t *a_out;            // stage 1: A [cap,I]
-    float *y_out;               // stage 2: Y [P,H]
+    float *y_out;               // stage 2: Y [P,H] (fp32, or bf16 in the same buffer when y_bf16 != 0)
+    int y_bf16;                 // large batches keep the per-pair rows in bf16 to halve their HBM traffic
     int K;                      // reduction length (H or I)
     int F;                      // output features (I or H)
     int P;                      // pairs = T*k (the sentinel)
     int topk;                   // k
     int n_tiles;                // feature tiles of this stage
     int m_tiles_cap;            // launched M-tiles (upper bound)
+    int group_m;                // M-tiles per XCD block of the workgroup->tile map (set by the launcher)
 };
 
 struct KernelInfo {
@@ -83,7 +85,7 @@ const KernelInfo *find_kernel(const ramp_config &cfg);
 bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s);
 int occupancy_estimate(const KernelInfo &ki);
 
-int launch_combine(const float *Y, const int32_t *ids, int T, int k, int E, int H, uint16_t *out,
+int launch_combine(const float *Y, int y_bf16, const int32_t *ids, int T, int k, int E, int H, uint16_t *out,
                    hipStream_t stream);
 
 }  // namespace ramp

@@ -17,10 +17,10 @@ from . import ramp, synth
 
 
 def fit_batch_sizes(sweep_T: Sequence[int], n: int = 5) -> List[int]:
-    """Profiling batch sizes: n log-spaced values from 2 up to half of the largest benchmark
+    """Profiling batch sizes: n log-spaced values from 1 up to half of the largest benchmark
     batch, so the largest benchmark batch is an extrapolation (Sec. 5.2)."""
     hi = max(4, max(sweep_T) // 2)
-    vals = np.unique(np.round(np.geomspace(2, hi, n)).astype(int))
+    vals = np.unique(np.round(np.geomspace(1, hi, n)).astype(int))
     return [int(v) for v in vals]
 
 

@@ -42,8 +42,9 @@ CASES = [
     # (shape, T, beta, bm)
     ("tiny", 16, 1.0, 4), ("tiny", 16, 0.2, 4), ("tiny", 16, 0.2, 16), ("tiny", 16, 1.0, 16),
     ("olmoe", 1, 1.0, 16), ("olmoe", 16, 0.5, 16), ("olmoe", 64, 0.1, 32), ("olmoe", 256, 0.2, 64),
-    ("olmoe", 512, 1.0, 128),   # P = 4096: last single-workgroup size
-    ("olmoe", 513, 1.0, 128),   # first multi-workgroup size, ragged tail
+    ("olmoe", 256, 1.0, 128),   # P = 2048: last single-workgroup size
+    ("olmoe", 257, 1.0, 128),   # first multi-workgroup size, ragged tail
+    ("olmoe", 512, 1.0, 128), ("olmoe", 513, 0.5, 16),
     ("olmoe", 1024, 0.1, 256), ("olmoe", 4096, 1.0, 256), ("olmoe", 4096, 0.1, 16),
     ("qwen3", 8192, 0.08, 64), ("qwen3", 2048, 0.3, 16), ("qwen3", 8192, 1.0, 7),
     ("mixtral", 8192, "zipf1.2", 128), ("mixtral", 1, 1.0, 16), ("mixtral", 1000, "zipf1.2", 104),
