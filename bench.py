@@ -107,17 +107,31 @@ def main():
             pt.materialise(s)
         g_fit = np.stack([fam.grid(pt.counts) for pt in fit_pts], axis=1)
         t_fit = np.ones_like(g_fit, dtype=np.float64)
-    theta = tuner.fit(fam, g_fit, t_fit)
-    pred_fit = np.array([[ramp.cost_model_select(s.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, p.counts, want_pred=True)[1][c]
-                          for p in fit_pts] for c in range(n_cfg)])
-    ss_res = ((pred_fit - t_fit) ** 2).sum(axis=1)
-    ss_tot = ((t_fit - t_fit.mean(axis=1, keepdims=True)) ** 2).sum(axis=1)
-    r2 = 1.0 - ss_res / np.maximum(ss_tot, 1e-30)
-    log(f"[bench] fit done in {time.time() - t0:.1f}s; R^2 min {r2.min():.3f} median {np.median(r2):.3f}; "
+    counts_fit = [p.materialise(s).counts for p in fit_pts]
+    MODELS = {"eq6": ramp.CM_EQ6, "eq6_mi355x": tuner.MI355X_MODEL}   # as printed / cache-aware + relative fit
+    thetas = {name: tuner.fit(fam, g_fit, t_fit, counts_fit, flags) for name, flags in MODELS.items()}
+    DISPATCH = "eq6_mi355x"
+    theta, dispatch_flags = thetas[DISPATCH], MODELS[DISPATCH]
+
+    def predictions(name, counts):
+        return ramp.cost_model_select(s.E, fam.cfgs, fam.ntiles, fam.wave_cap, thetas[name], counts, want_pred=True,
+                                      flags=MODELS[name])[1]
+
+    r2 = {}
+    for name in MODELS:
+        pred_fit = np.stack([predictions(name, c) for c in counts_fit], axis=1)
+        ss_res = ((pred_fit - t_fit) ** 2).sum(axis=1)
+        ss_tot = ((t_fit - t_fit.mean(axis=1, keepdims=True)) ** 2).sum(axis=1)
+        r2[name] = 1.0 - ss_res / np.maximum(ss_tot, 1e-30)
+    log(f"[bench] fit done in {time.time() - t0:.1f}s; R^2 (eq6) min {r2['eq6'].min():.3f} median {np.median(r2['eq6']):.3f}; "
         f"log term active in {(theta[:, 3] != 0).sum()}/{n_cfg} configs")
 
     # ------------------------------------------------------------------ sweep: exhaustive vs cost model vs static
-    report = {"model": args.model, "configs": [c.key() for c in fam.cfgs], "theta": theta.tolist(), "r2": r2.tolist(),
+    report = {"model": args.model, "configs": [c.key() for c in fam.cfgs],
+              "theta": {k: v.tolist() for k, v in thetas.items()}, "r2": {k: v.tolist() for k, v in r2.items()},
+              "ntiles": fam.ntiles.tolist(), "wave_cap": fam.wave_cap.tolist(),
+              "fit": {"T": [p.T for p in fit_pts], "beta": [p.beta for p in fit_pts], "grid": g_fit.tolist(),
+                      "time_us": t_fit.tolist(), "counts": [c.tolist() for c in counts_fit]},
               "points": []}
     summary = {}
     if not args.no_sweep:
@@ -127,40 +141,50 @@ def main():
         g_ev, t_ev = tuner.profile(layers, fam, pts, log=log, iters=args.iters, warmup=10, budget_ms=300.0)
         static_of_T = {}
         for j, p in enumerate(pts):
-            if p.beta == 1.0:
-                static_of_T[p.T] = int(np.argmin(t_ev[:, j]))
-        regrets, speedups = [], {}
-        hdr = f"{'T':>5} {'beta':>8} {'bH':>5} {'best us':>9} {'RA us':>9} {'static us':>9} {'regret%':>8} {'RA/static':>9} {'bound':>5} {'roof%':>6} {'TFLOP/s':>8} {'GB/s':>7}  best / RA / static bm"
+            if p.beta == 1.0 or p.beta == sweep["beta"][0]:
+                static_of_T.setdefault(p.T, int(np.argmin(t_ev[:, j])))
+        regrets = {name: [] for name in MODELS}
+        speedups = {}
+        hdr = (f"{'T':>5} {'beta':>8} {'bH':>5} {'best us':>9} {'RA us':>9} {'static us':>9} {'regret%':>8} {'eq6 reg%':>8} "
+               f"{'RA/static':>9} {'bound':>5} {'roof%':>6} {'TFLOP/s':>8} {'GB/s':>7}  best / RA / static bm")
         log(hdr)
         for j, p in enumerate(pts):
-            chosen = tuner.select(fam, theta, p.counts)
             best = int(np.argmin(t_ev[:, j]))
             st = static_of_T[p.T]
-            reg = t_ev[chosen, j] / t_ev[best, j] - 1.0
+            picks = {name: tuner.select(fam, thetas[name], p.counts, MODELS[name]) for name in MODELS}
+            for name in MODELS:
+                regrets[name].append(t_ev[picks[name], j] / t_ev[best, j] - 1.0)
+            chosen = picks[DISPATCH]
+            reg = regrets[DISPATCH][-1]
             spd = t_ev[st, j] / t_ev[chosen, j]
-            regrets.append(reg)
             speedups.setdefault(str(p.beta), []).append(spd)
             t_hbm, t_mfma, nbytes, flops = tuner.roofline_lower_bound_us(s, p.T, p.counts, HBM_PEAK_TBS, MFMA_PEAK_PFLOPS)
             bound = "hbm" if t_hbm >= t_mfma else "mfma"
             frac = max(t_hbm, t_mfma) / t_ev[chosen, j]
             row = dict(T=p.T, beta=p.beta, beta_entropy=tuner.entropy_beta(p.counts), best_us=t_ev[best, j],
-                       ra_us=t_ev[chosen, j], static_us=t_ev[st, j], regret=reg, ra_over_static=spd, bound=bound,
-                       roofline_frac=frac, tflops=flops / t_ev[chosen, j] * 1e-6, gbs=nbytes / t_ev[chosen, j] * 1e-3,
+                       ra_us=t_ev[chosen, j], static_us=t_ev[st, j], regret=reg, regret_eq6=regrets["eq6"][-1],
+                       ra_over_static=spd, bound=bound, roofline_frac=frac, roofline_frac_best=max(t_hbm, t_mfma) / t_ev[best, j],
+                       tflops=flops / t_ev[chosen, j] * 1e-6, gbs=nbytes / t_ev[chosen, j] * 1e-3,
                        best_cfg=fam.cfgs[best].key(), ra_cfg=fam.cfgs[chosen].key(), static_cfg=fam.cfgs[st].key(),
-                       all_us=t_ev[:, j].tolist(), grid=g_ev[:, j].tolist())
+                       all_us=t_ev[:, j].tolist(), grid=g_ev[:, j].tolist(), counts=p.counts.tolist())
             report["points"].append(row)
             log(f"{p.T:>5} {p.beta!s:>8} {row['beta_entropy']:5.2f} {row['best_us']:9.1f} {row['ra_us']:9.1f} "
-                f"{row['static_us']:9.1f} {100 * reg:8.2f} {spd:9.3f} {bound:>5} {100 * frac:6.1f} {row['tflops']:8.1f} "
-                f"{row['gbs']:7.0f}  {fam.cfgs[best].bm}/{fam.cfgs[chosen].bm}/{fam.cfgs[st].bm}")
-        summary = dict(mean_regret=float(np.mean(regrets)), max_regret=float(np.max(regrets)),
+                f"{row['static_us']:9.1f} {100 * reg:8.2f} {100 * row['regret_eq6']:8.2f} {spd:9.3f} {bound:>5} {100 * frac:6.1f} "
+                f"{row['tflops']:8.1f} {row['gbs']:7.0f}  {fam.cfgs[best].bm}/{fam.cfgs[chosen].bm}/{fam.cfgs[st].bm}")
+        skew = [r for r in report["points"] if str(r["beta"]) != str(sweep["beta"][0])]
+        summary = dict(dispatch_model=DISPATCH,
+                       mean_regret=float(np.mean(regrets[DISPATCH])), max_regret=float(np.max(regrets[DISPATCH])),
+                       median_regret=float(np.median(regrets[DISPATCH])),
+                       mean_regret_eq6_as_printed=float(np.mean(regrets["eq6"])),
+                       max_regret_eq6_as_printed=float(np.max(regrets["eq6"])),
                        ra_over_static_geomean={b: geomean(v) for b, v in speedups.items()},
-                       ra_over_static_geomean_skewed=geomean([v for b, vs in speedups.items() if b != "1.0" for v in vs]),
-                       best_over_static_geomean_skewed=geomean(
-                           [r["static_us"] / r["best_us"] for r in report["points"] if r["beta"] != 1.0]),
+                       ra_over_static_geomean_skewed=geomean([r["ra_over_static"] for r in skew]),
+                       best_over_static_geomean_skewed=geomean([r["static_us"] / r["best_us"] for r in skew]),
                        paper_context=dict(mean_regret=0.0093, ra_over_static=1.22, hardware="H200 FP8"))
         log(f"[bench] sweep {time.time() - t0:.1f}s: mean regret {100 * summary['mean_regret']:.2f}% "
-            f"(max {100 * summary['max_regret']:.2f}%); RA/static geomean on skewed points "
-            f"{summary['ra_over_static_geomean_skewed']:.3f}x (ceiling {summary['best_over_static_geomean_skewed']:.3f}x)")
+            f"(median {100 * summary['median_regret']:.2f}%, max {100 * summary['max_regret']:.2f}%; Eq. 6 as printed: "
+            f"{100 * summary['mean_regret_eq6_as_printed']:.2f}%); RA/static geomean on skewed points "
+            f"{summary['ra_over_static_geomean_skewed']:.3f}x (exhaustive ceiling {summary['best_over_static_geomean_skewed']:.3f}x)")
 
     if args.heldout > 0:
         rng = np.random.default_rng(7)
@@ -168,10 +192,10 @@ def main():
         t0 = time.time()
         for h in range(args.heldout):
             T = int(rng.choice(sweep["T"][1:]))
-            b = rng.choice([x for x in sweep["beta"]])
-            p = tuner.Point(T, b if isinstance(b, str) else float(b), seed=900000 + h).materialise(s)
+            b = sweep["beta"][int(rng.integers(len(sweep["beta"])))]
+            p = tuner.Point(T, b, seed=900000 + h).materialise(s)
             times = np.array([tuner.time_config(layers, c, p, warmup=2, iters=8, budget_ms=40.0) for c in fam.cfgs])
-            regs.append(times[tuner.select(fam, theta, p.counts)] / times.min() - 1.0)
+            regs.append(times[tuner.select(fam, theta, p.counts, dispatch_flags)] / times.min() - 1.0)
             if h % 20 == 19:
                 log(f"[bench] held-out {h + 1}/{args.heldout}: mean regret so far {100 * np.mean(regs):.2f}%")
         summary["heldout_histograms"] = dict(n=args.heldout, mean_regret=float(np.mean(regs)), max_regret=float(np.max(regs)))
@@ -193,7 +217,7 @@ def main():
         ramp.moe_histogram(d_ids, T_head, s.k, s.E, d_counts, hist_ws)
         h_counts.copy_(d_counts, non_blocking=True)
         torch.cuda.current_stream().synchronize()          # the path's one host sync (Sec. 4.4)
-        c = tuner.select(fam, theta, h_counts.numpy())
+        c = tuner.select(fam, theta, h_counts.numpy(), dispatch_flags)
         if fixed_cfg is not None:
             c = fixed_cfg
         ramp.fused_moe(rs, fam.cfgs[c], X, d_ids, d_w, layers.packed[i % layers.n_layers], out, ws)

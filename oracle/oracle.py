@@ -70,7 +70,7 @@ def _load():
         lib.oracle_predict.restype = ctypes.c_double
         lib.oracle_predict.argtypes = [f32p, ctypes.c_int64, ctypes.c_int]
         lib.oracle_select.restype = ctypes.c_int
-        lib.oracle_select.argtypes = [ctypes.c_int, i32p, i32p, i32p, f32p, i32p, ctypes.c_int, f64p]
+        lib.oracle_select.argtypes = [ctypes.c_int, i32p, i32p, i32p, f32p, i32p, ctypes.c_int, ctypes.c_int, f64p]
         lib.oracle_f64_to_bf16.restype = ctypes.c_uint16
         lib.oracle_f64_to_bf16.argtypes = [ctypes.c_double]
         lib.oracle_bf16_to_f64.restype = ctypes.c_double
@@ -211,8 +211,9 @@ def predict(theta4, g: int, wave_cap: int) -> float:
     return float(_load().oracle_predict(_ptr(th, ctypes.c_float), int(g), int(wave_cap)))
 
 
-def select(bm, ntiles, wave_cap, theta, counts):
-    """Evaluate Eq. 6 for all configs on one histogram.  Returns (argmin, predictions)."""
+def select(bm, ntiles, wave_cap, theta, counts, distinct_tiles: bool = False):
+    """Evaluate Eq. 6 for all configs on one histogram.  Returns (argmin, predictions).
+    distinct_tiles: the per-block traffic term uses (#active experts * ntiles) instead of g."""
     bm, ntiles, wave_cap, counts = _i32(bm), _i32(ntiles), _i32(wave_cap), _i32(counts)
     theta = np.ascontiguousarray(theta, dtype=np.float32).reshape(-1, 4)
     n = bm.size
@@ -220,14 +221,16 @@ def select(bm, ntiles, wave_cap, theta, counts):
     pred = np.empty(n, np.float64)
     best = _load().oracle_select(n, _ptr(bm, ctypes.c_int32), _ptr(ntiles, ctypes.c_int32),
                                  _ptr(wave_cap, ctypes.c_int32), _ptr(theta, ctypes.c_float),
-                                 _ptr(counts, ctypes.c_int32), counts.size, _ptr(pred, ctypes.c_double))
+                                 _ptr(counts, ctypes.c_int32), counts.size, int(distinct_tiles),
+                                 _ptr(pred, ctypes.c_double))
     return int(best), pred
 
 
-def design_matrix(g, wave_cap: int) -> np.ndarray:
-    """Rows [1, g/W, g, ln(g+1)] of Eq. 6."""
+def design_matrix(g, wave_cap: int, distinct=None) -> np.ndarray:
+    """Rows [1, g/W, m, ln(g+1)] of Eq. 6; m = g as printed, or the distinct-weight-tile count."""
     g = np.asarray(g, dtype=np.float64)
-    return np.stack([np.ones_like(g), g / float(wave_cap), g, np.log(g + 1.0)], axis=1)
+    m = g if distinct is None else np.asarray(distinct, dtype=np.float64)
+    return np.stack([np.ones_like(g), g / float(wave_cap), m, np.log(g + 1.0)], axis=1)
 
 
 def lower_median(v) -> float:
@@ -235,8 +238,12 @@ def lower_median(v) -> float:
     return float(s[(s.size - 1) // 2])
 
 
-def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4):
+def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4, distinct=None, relative: bool = False):
     """Sec. 4.2 "Fitting" for ONE configuration.
+
+    distinct / relative are the two documented departures from the printed recipe that the
+    GPU library also offers: the traffic column holds the number of distinct weight tiles
+    instead of g, and the residuals are relative (every row divided by its measured time).
 
     g: profiling grids, t_us: measured times.  The log column is used only if
     the (lower) median profiling grid is below wave_cap.  Solves the literal
@@ -246,12 +253,15 @@ def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4):
     """
     g = np.asarray(g, dtype=np.float64)
     t = np.asarray(t_us, dtype=np.float64)
-    X = design_matrix(g, wave_cap)
+    X = design_matrix(g, wave_cap, distinct)
     use_log = (n_terms >= 4) and (lower_median(g) < wave_cap)
     cols = [0, 1, 2] + ([3] if use_log else [])
     if n_terms == 2:
         cols = [0, 2]
-    sol = np.linalg.lstsq(X[:, cols], t, rcond=None)[0]
+    A, rhs = X[:, cols], t
+    if relative:
+        A, rhs = A / t[:, None], np.ones_like(t)
+    sol = np.linalg.lstsq(A, rhs, rcond=None)[0]
     theta = np.zeros(4, np.float64)
     theta[cols] = sol
     return theta, use_log

@@ -201,15 +201,22 @@ int oracle_moe(const uint16_t *X, const int32_t *ids, const float *w,
 
 /* ---------- Eq. 6 and the argmin ---------- */
 
-/* T_hat = a + b*g/W + c*g + d*ln(g+1), evaluated left to right in fp64. */
-double oracle_predict(const float *theta4, int64_t g, int wave_cap)
+/* T_hat = a + b*g/W + c*m + d*ln(g+1), evaluated left to right in fp64.
+ * m = g is Eq. 6 as printed; m = number of distinct weight tiles is the cache-aware
+ * reading of the per-block traffic term (see oracle.py). */
+double oracle_predict2(const float *theta4, int64_t g, int64_t m, int wave_cap)
 {
     double gd = (double)g;
     double t = (double)theta4[0];
     t = t + (double)theta4[1] * (gd / (double)wave_cap);
-    t = t + (double)theta4[2] * gd;
+    t = t + (double)theta4[2] * (double)m;
     t = t + (double)theta4[3] * log(gd + 1.0);
     return t;
+}
+
+double oracle_predict(const float *theta4, int64_t g, int wave_cap)
+{
+    return oracle_predict2(theta4, g, g, wave_cap);
 }
 
 /*
@@ -218,13 +225,18 @@ double oracle_predict(const float *theta4, int64_t g, int wave_cap)
  * n_cfg <= 0).  pred (optional) receives all predictions.
  */
 int oracle_select(int n_cfg, const int32_t *bm, const int32_t *ntiles, const int32_t *wave_cap,
-                  const float *theta /*[n_cfg,4]*/, const int32_t *counts, int E, double *pred)
+                  const float *theta /*[n_cfg,4]*/, const int32_t *counts, int E, int distinct_tiles,
+                  double *pred)
 {
     int best = -1;
     double best_t = 0.0;
+    int64_t active = 0;
+    for (int e = 0; e < E; ++e)
+        if (counts[e] > 0) ++active;
     for (int c = 0; c < n_cfg; ++c) {
         int64_t g = oracle_grid(counts, E, bm[c], ntiles[c]);
-        double t = oracle_predict(theta + 4 * (size_t)c, g, wave_cap[c]);
+        int64_t m = distinct_tiles ? active * ntiles[c] : g;
+        double t = oracle_predict2(theta + 4 * (size_t)c, g, m, wave_cap[c]);
         if (pred) pred[c] = t;
         if (best < 0 || t < best_t) { best = c; best_t = t; }
     }

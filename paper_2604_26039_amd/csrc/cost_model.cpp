@@ -1,7 +1,9 @@
 // Four-term wave cost model (paper Eq. 6, Sec. 4.2): least-squares fit per configuration
 // and the runtime argmin over configurations.  Host code only.
 //
-//   T_hat(c) = a + b * g/W + c * g + d * ln(g + 1),   g = (sum_e ceil(n_e / bm_c)) * ntiles_c
+//   T_hat(c) = a + b * g/W + c * m + d * ln(g + 1),   g = (sum_e ceil(n_e / bm_c)) * ntiles_c
+//   m = g as printed, or the number of distinct weight tiles (active experts * ntiles_c) when the
+//   per-block traffic term is made cache aware (RAMP_CM_DISTINCT_TILES).
 //
 // The columns g/W and g of the design matrix are proportional for a fixed configuration, so
 // the literal four-column system is rank deficient.  The fit returns the minimum-norm
@@ -79,13 +81,16 @@ void lstsq_min_norm(std::vector<double> A, int n, int m, const double *t, double
 }  // namespace
 
 extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
-                                   const double *time_us, float *theta)
+                                   const int64_t *distinct, const double *time_us, int flags, float *theta)
 {
-    if (n_cfg < 0 || n_pts <= 0 || !wave_cap || !grid || !time_us || !theta) {
+    const bool use_distinct = (flags & RAMP_CM_DISTINCT_TILES) != 0;
+    const bool relative = (flags & RAMP_CM_RELATIVE) != 0;
+    if (n_cfg < 0 || n_pts <= 0 || !wave_cap || !grid || !time_us || !theta || (use_distinct && !distinct) ||
+        (flags & ~(RAMP_CM_RELATIVE | RAMP_CM_DISTINCT_TILES))) {
         ramp::set_error("cost_model_fit: bad argument");
         return RAMP_EINVAL;
     }
-    std::vector<double> A((size_t)4 * n_pts), sorted_g(n_pts);
+    std::vector<double> A((size_t)4 * n_pts), sorted_g(n_pts), rhs(n_pts);
     for (int c = 0; c < n_cfg; ++c) {
         const int64_t *g = grid + (size_t)c * n_pts;
         const double *t = time_us + (size_t)c * n_pts;
@@ -100,13 +105,23 @@ extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts
         const int m = use_log ? 4 : 3;
         for (int i = 0; i < n_pts; ++i) {
             const double gi = (double)g[i];
-            A[0 * (size_t)n_pts + i] = 1.0;
-            A[1 * (size_t)n_pts + i] = gi / W;
-            A[2 * (size_t)n_pts + i] = gi;
-            A[3 * (size_t)n_pts + i] = std::log(gi + 1.0);
+            const double mi = use_distinct ? (double)distinct[(size_t)c * n_pts + i] : gi;
+            double scale = 1.0;
+            if (relative) {
+                if (!(t[i] > 0.0)) {
+                    ramp::set_error("cost_model_fit: relative fit needs positive times (config %d point %d)", c, i);
+                    return RAMP_EINVAL;
+                }
+                scale = 1.0 / t[i];
+            }
+            A[0 * (size_t)n_pts + i] = 1.0 * scale;
+            A[1 * (size_t)n_pts + i] = gi / W * scale;
+            A[2 * (size_t)n_pts + i] = mi * scale;
+            A[3 * (size_t)n_pts + i] = std::log(gi + 1.0) * scale;
+            rhs[i] = t[i] * scale;
         }
         double x[4] = {0, 0, 0, 0};
-        lstsq_min_norm(std::vector<double>(A.begin(), A.begin() + (size_t)m * n_pts), n_pts, m, t, x);
+        lstsq_min_norm(std::vector<double>(A.begin(), A.begin() + (size_t)m * n_pts), n_pts, m, rhs.data(), x);
         for (int j = 0; j < 4; ++j) theta[(size_t)c * 4 + j] = (j < m) ? (float)x[j] : 0.0f;
     }
     return RAMP_OK;
@@ -114,12 +129,16 @@ extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts
 
 extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
                                       const int32_t *wave_cap, const float *theta, const int32_t *expert_counts,
-                                      int *best_idx, double *pred_us)
+                                      int flags, int *best_idx, double *pred_us)
 {
-    if (E <= 0 || n_cfg <= 0 || !cfgs || !ntiles || !wave_cap || !theta || !expert_counts || !best_idx) {
+    if (E <= 0 || n_cfg <= 0 || !cfgs || !ntiles || !wave_cap || !theta || !expert_counts || !best_idx ||
+        (flags & ~(RAMP_CM_RELATIVE | RAMP_CM_DISTINCT_TILES))) {
         ramp::set_error("cost_model_select: bad argument");
         return RAMP_EINVAL;
     }
+    const bool use_distinct = (flags & RAMP_CM_DISTINCT_TILES) != 0;
+    int64_t active = 0;
+    for (int e = 0; e < E; ++e) active += expert_counts[e] > 0 ? 1 : 0;
     int best = -1;
     double best_t = 0.0;
     // M-tiles depend only on bm; configurations usually share a handful of bm values
@@ -144,7 +163,8 @@ extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs,
         const float *th = theta + (size_t)c * 4;
         double t = (double)th[0];
         t = t + (double)th[1] * (g / (double)wave_cap[c]);
-        t = t + (double)th[2] * g;
+        const double m = use_distinct ? (double)(active * (int64_t)ntiles[c]) : g;
+        t = t + (double)th[2] * m;
         t = t + (double)th[3] * std::log(g + 1.0);
         if (pred_us) pred_us[c] = t;
         if (best < 0 || t < best_t) {

@@ -18,6 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libramp.so")
 
 OK, EINVAL, ENOSPC, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
+CM_EQ6, CM_RELATIVE, CM_DISTINCT_TILES = 0, 1, 2
 
 
 class Shape(ctypes.Structure):
@@ -85,9 +86,9 @@ def lib() -> ctypes.CDLL:
         L.ramp_fused_moe.restype = ci
         L.ramp_fused_moe.argtypes = [sp, cp, vp, i32p, f32p, vp, vp, vp, sz, vp]
         L.ramp_cost_model_fit.restype = ci
-        L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp]
+        L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp, ci, vp]
         L.ramp_cost_model_select.restype = ci
-        L.ramp_cost_model_select.argtypes = [ci, ci, cp, vp, vp, vp, vp, ctypes.POINTER(ci), vp]
+        L.ramp_cost_model_select.argtypes = [ci, ci, cp, vp, vp, vp, vp, ci, ctypes.POINTER(ci), vp]
         L.ramp_probe_enable.restype = ci
         L.ramp_probe_enable.argtypes = [ci]
         L.ramp_probe_read.restype = ci
@@ -231,21 +232,26 @@ def copy_bytes(dst: torch.Tensor, src: torch.Tensor, nbytes: int, stream=None):
 
 # ----------------------------------------------------------------------------- cost model (host)
 
-def cost_model_fit(wave_cap: Sequence[int], grid, time_us) -> np.ndarray:
-    """grid, time_us: [n_cfg, n_pts].  Returns theta float32 [n_cfg, 4]."""
+def cost_model_fit(wave_cap: Sequence[int], grid, time_us, distinct=None, flags: int = CM_EQ6) -> np.ndarray:
+    """grid, time_us (and distinct with CM_DISTINCT_TILES): [n_cfg, n_pts].  Returns theta float32 [n_cfg, 4]."""
     grid = _np(grid, np.int64)
     time_us = _np(time_us, np.float64)
     n_cfg, n_pts = grid.shape
     assert time_us.shape == (n_cfg, n_pts)
+    if distinct is not None:
+        distinct = _np(distinct, np.int64)
+        assert distinct.shape == (n_cfg, n_pts)
     wc = _np(wave_cap, np.int32)
     assert wc.size == n_cfg
     theta = np.zeros((n_cfg, 4), np.float32)
-    _check(lib().ramp_cost_model_fit(n_cfg, wc.ctypes.data, n_pts, grid.ctypes.data, time_us.ctypes.data,
-                                     theta.ctypes.data))
+    _check(lib().ramp_cost_model_fit(n_cfg, wc.ctypes.data, n_pts, grid.ctypes.data,
+                                     distinct.ctypes.data if distinct is not None else None, time_us.ctypes.data,
+                                     flags, theta.ctypes.data))
     return theta
 
 
-def cost_model_select(E: int, cfgs: Sequence[Config], ntiles, wave_cap, theta, expert_counts, want_pred=False):
+def cost_model_select(E: int, cfgs: Sequence[Config], ntiles, wave_cap, theta, expert_counts, want_pred=False,
+                      flags: int = CM_EQ6):
     n = len(cfgs)
     arr = (Config * n)(*cfgs)
     nt, wc = _np(ntiles, np.int32), _np(wave_cap, np.int32)
@@ -255,5 +261,5 @@ def cost_model_select(E: int, cfgs: Sequence[Config], ntiles, wave_cap, theta, e
     best = ctypes.c_int(-1)
     pred = np.zeros(n, np.float64) if want_pred else None
     _check(lib().ramp_cost_model_select(E, n, arr, nt.ctypes.data, wc.ctypes.data, th.ctypes.data, counts.ctypes.data,
-                                        ctypes.byref(best), pred.ctypes.data if want_pred else None))
+                                        flags, ctypes.byref(best), pred.ctypes.data if want_pred else None))
     return (best.value, pred) if want_pred else best.value

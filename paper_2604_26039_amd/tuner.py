@@ -159,12 +159,24 @@ def profile(layers: LayerSet, fam: Family, points: Sequence[Point], log=None, **
     return grid, t_us
 
 
-def fit(fam: Family, grid: np.ndarray, t_us: np.ndarray) -> np.ndarray:
-    return ramp.cost_model_fit(fam.wave_cap, grid, t_us)
+# The dispatch model used on this chip: Eq. 6 with the traffic term on distinct weight tiles,
+# fitted on relative residuals.  EQ6 (= 0) is the model exactly as printed.
+MI355X_MODEL = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES
 
 
-def select(fam: Family, theta: np.ndarray, counts: np.ndarray) -> int:
-    return ramp.cost_model_select(fam.shape.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, counts)
+def distinct_tiles(fam: Family, counts_list: Sequence[np.ndarray]) -> np.ndarray:
+    """[n_cfg, n_pts]: active experts x ntiles(c), the distinct weight tiles a point touches."""
+    active = np.array([int((np.asarray(c) > 0).sum()) for c in counts_list], np.int64)
+    return fam.ntiles.astype(np.int64)[:, None] * active[None, :]
+
+
+def fit(fam: Family, grid: np.ndarray, t_us: np.ndarray, counts_list=None, flags: int = ramp.CM_EQ6) -> np.ndarray:
+    distinct = distinct_tiles(fam, counts_list) if (flags & ramp.CM_DISTINCT_TILES) else None
+    return ramp.cost_model_fit(fam.wave_cap, grid, t_us, distinct=distinct, flags=flags)
+
+
+def select(fam: Family, theta: np.ndarray, counts: np.ndarray, flags: int = ramp.CM_EQ6) -> int:
+    return ramp.cost_model_select(fam.shape.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, counts, flags=flags)
 
 
 def entropy_beta(counts) -> float:

@@ -128,3 +128,37 @@ def test_select_rejects_bad_arguments():
     cfgs = ramp.configs(sh)[:2]
     with pytest.raises(ramp.RampError):
         ramp.cost_model_select(sh.E, cfgs, [1, 1], [0, 256], np.zeros((2, 4), np.float32), np.zeros(sh.E, np.int32))
+
+
+def test_adapted_model_fit_and_select_match_oracle():
+    """RAMP_CM_RELATIVE | RAMP_CM_DISTINCT_TILES: predictions agree with the oracle's fit, and the
+    selection is bit-identical to the oracle's for the same theta."""
+    rng = np.random.default_rng(4)
+    sh = shape_of("qwen3", 512)
+    cfgs = ramp.configs(sh)
+    n = len(cfgs)
+    nt = np.array([ramp.config_ntiles(sh, c) for c in cfgs])
+    wc = np.array([ramp.config_wave_capacity(c) for c in cfgs])
+    bm = [c.bm for c in cfgs]
+    hists = [synth.histogram_subset(int(T), sh.k, sh.E, b, seed=i) for i, (T, b) in
+             enumerate((T, b) for T in (1, 6, 40, 250, 1500) for b in (1.0, 0.7, 0.4, 0.25, 0.12))]
+    g = np.array([[oracle.grid(h, bm[c], int(nt[c])) for h in hists] for c in range(n)], np.int64)
+    act = np.array([int((h > 0).sum()) for h in hists])
+    u = nt[:, None] * act[None, :]
+    t = 9 + 0.02 * g + 0.3 * u + rng.normal(0, 0.2, g.shape) + 0.002 * g * rng.random(g.shape)
+    flags = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES
+    theta = ramp.cost_model_fit(wc, g, t, distinct=u, flags=flags)
+    for c in range(0, n, 3):
+        th_o, use_log = oracle.fit_cost_model(g[c], t[c], int(wc[c]), distinct=u[c], relative=True)
+        X = oracle.design_matrix(g[c], int(wc[c]), u[c])
+        po, pl = X @ th_o, X @ theta[c].astype(np.float64)
+        assert np.abs(po - pl).max() <= 5e-5 * np.abs(po).max()
+        assert (theta[c, 3] != 0) == use_log
+    for i, h in enumerate(hists[::4]):
+        best, pred = ramp.cost_model_select(sh.E, cfgs, nt, wc, theta, h, want_pred=True, flags=flags)
+        b_o, p_o = oracle.select(bm, nt, wc, theta, h, distinct_tiles=True)
+        assert best == b_o and (pred == p_o).all()
+    with pytest.raises(ramp.RampError):
+        ramp.cost_model_fit(wc, g, t, distinct=None, flags=flags)   # distinct tiles required
+    with pytest.raises(ramp.RampError):
+        ramp.cost_model_fit(wc, g, -t, distinct=u, flags=flags)     # relative fit needs positive times

@@ -187,3 +187,58 @@ def test_regret_static_speedup():
     assert round(oracle.geomean_speedup(static, ra), 2) in (1.32, 1.33)  # from the printed us columns
     printed = [1.70, 1.40, 1.33, 1.27, 1.27, 1.19, 1.18]
     assert round(float(np.exp(np.mean(np.log(printed)))), 2) in (1.32, 1.33)
+
+
+# ----------------------------------------------------------------------------- the two documented departures
+
+def test_distinct_tile_column_makes_all_four_terms_identifiable():
+    W = 256
+    rng = np.random.default_rng(5)
+    g = rng.integers(2, 200, 25).astype(float)          # sub-wave grids -> log term active
+    u = np.minimum(g, rng.integers(1, 64, 25) * 2.0)     # distinct weight tiles never exceed the grid
+    a, b, c, d = 7.0, 30.0, 0.4, 2.5
+    t = a + b * g / W + c * u + d * np.log(g + 1)
+    theta, use_log = oracle.fit_cost_model(g, t, W, distinct=u)
+    assert use_log
+    assert np.allclose(theta, [a, b, c, d], rtol=1e-7)
+    th_rel, _ = oracle.fit_cost_model(g, t, W, distinct=u, relative=True)
+    assert np.allclose(th_rel, [a, b, c, d], rtol=1e-7)   # exact data: weighting does not matter
+    assert np.allclose(oracle.design_matrix(g, W, u) @ theta, t, rtol=1e-10)
+    assert (oracle.design_matrix(g, W, u)[:, 2] == u).all() and (oracle.design_matrix(g, W)[:, 2] == g).all()
+
+
+def test_relative_fit_is_weighted_least_squares_closed_form():
+    # two-parameter form a + k*g with weights 1/t^2: solve the 2x2 normal equations by hand
+    g = np.array([1, 4, 10, 50, 200, 1000, 5000], float)
+    t = np.array([12.0, 13.0, 16.0, 30.0, 90.0, 400.0, 1900.0])
+    theta, _ = oracle.fit_cost_model(g, t, 64, n_terms=2, relative=True)
+    w = 1.0 / t ** 2
+    S, Sg, Sgg, St, Sgt = w.sum(), (w * g).sum(), (w * g * g).sum(), (w * t).sum(), (w * g * t).sum()
+    k = (S * Sgt - Sg * St) / (S * Sgg - Sg ** 2)
+    a = (St - k * Sg) / S
+    assert theta[0] == pytest.approx(a, rel=1e-9) and theta[2] == pytest.approx(k, rel=1e-9)
+    # ordinary least squares is dominated by the largest times, the relative fit is not
+    th_ols, _ = oracle.fit_cost_model(g, t, 64, n_terms=2)
+    rel_err = lambda th: np.abs((th[0] + th[2] * g) / t - 1)
+    assert rel_err(theta)[:3].max() < rel_err(th_ols)[:3].max()
+    # scale equivariance: times in other units scale theta and nothing else
+    th2, _ = oracle.fit_cost_model(g, 1000 * t, 64, n_terms=2, relative=True)
+    assert np.allclose(th2, 1000 * theta, rtol=1e-9)
+
+
+def test_select_with_distinct_tiles_matches_brute_force():
+    rng = np.random.default_rng(9)
+    n = 10
+    bm = rng.choice([16, 32, 64, 128, 256], n)
+    nt = rng.integers(8, 80, n)
+    W = rng.choice([256, 512, 1024], n)
+    theta = (np.abs(rng.normal(0, 1, (n, 4))) * [10, 5, 0.05, 2]).astype(np.float32)
+    counts = rng.integers(0, 40, 64) * (rng.random(64) < 0.3)
+    active = int((counts > 0).sum())
+    best, pred = oracle.select(bm, nt, W, theta, counts, distinct_tiles=True)
+    exp = []
+    for c in range(n):
+        g = sum(-(-int(x) // int(bm[c])) for x in counts) * int(nt[c])
+        a, b, cc, d = (float(np.float32(v)) for v in theta[c])
+        exp.append(a + b * (g / W[c]) + cc * (active * int(nt[c])) + d * math.log(g + 1.0))
+    assert np.allclose(pred, exp, rtol=1e-14) and best == int(np.argmin(exp))
