@@ -179,6 +179,41 @@ def select(fam: Family, theta: np.ndarray, counts: np.ndarray, flags: int = ramp
     return ramp.cost_model_select(fam.shape.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, counts, flags=flags)
 
 
+class Dispatcher:
+    """Runtime dispatch (Sec. 4.4): histogram kernel -> E counts to pinned host memory -> one
+    ramp_cost_model_select call.  All marshalling is done once here so a step costs two library
+    calls, one small device-to-host copy and one stream synchronisation."""
+
+    def __init__(self, fam: Family, theta: np.ndarray, flags: int, T: int, device="cuda:0"):
+        import ctypes
+        self.fam, self.flags, self.T = fam, flags, T
+        s = fam.shape
+        self.E, self.k = s.E, s.k
+        self._cfgs = (ramp.Config * len(fam.cfgs))(*fam.cfgs)
+        self._nt = np.ascontiguousarray(fam.ntiles, np.int32)
+        self._wc = np.ascontiguousarray(fam.wave_cap, np.int32)
+        self._theta = np.ascontiguousarray(theta, np.float32)
+        self.d_counts = torch.zeros(self.E, dtype=torch.int32, device=device)
+        self.h_counts = torch.zeros(self.E, dtype=torch.int32).pin_memory()
+        self._h_ptr = self.h_counts.data_ptr()
+        self.ws = torch.empty(max(256, ramp.align_workspace_bytes(T, s.k, s.E)), dtype=torch.uint8, device=device)
+        self._best = ctypes.c_int(-1)
+        self._best_ref = ctypes.byref(self._best)
+        self._lib = ramp.lib()
+
+    def select(self, d_ids: torch.Tensor) -> int:
+        stream = torch.cuda.current_stream()
+        ramp.moe_histogram(d_ids, self.T, self.k, self.E, self.d_counts, self.ws, stream)
+        self.h_counts.copy_(self.d_counts, non_blocking=True)
+        stream.synchronize()  # the path's one host sync
+        rc = self._lib.ramp_cost_model_select(self.E, len(self.fam.cfgs), self._cfgs, self._nt.ctypes.data,
+                                              self._wc.ctypes.data, self._theta.ctypes.data, self._h_ptr, self.flags,
+                                              self._best_ref, None)
+        if rc != ramp.OK:
+            raise ramp.RampError(rc, ramp.last_error())
+        return self._best.value
+
+
 def entropy_beta(counts) -> float:
     """The paper's balancedness (Sec. 2.1), reported next to the subset fraction."""
     c = np.asarray(counts, np.float64)
