@@ -28,6 +28,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_TBS = 8.0       # MI355X HBM3E
 MFMA_PEAK_PFLOPS = 2.5   # dense bf16
 
+# HBM bytes per launch of the dominant kernel (up-projection + SwiGLU) from two separate
+# `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same
+# counter reads for the library's 1 GiB copy kernel: x2.000 and x1.000); the runs and their
+# per-kernel tables are kept as text under profiles/.  Keyed by (model, T, beta); other workloads
+# report null until they have been measured the same way.
+MEASURED_TRAFFIC_BYTES = {("olmoe", 4096, "1.0"): 1014.6e6 + 68.1e6}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -269,7 +276,7 @@ def main():
     else:
         roof = dict(bound="hbm", achieved=k_bytes / k_us * 1e-3, peak=HBM_PEAK_TBS * 1e3, unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof.update(traffic=None, kernel="moe_gemm_kernel<1> (up-projection + SwiGLU)", kernel_us=k_us, launches=probe_n,
+    roof.update(traffic=MEASURED_TRAFFIC_BYTES.get((args.model, T_head, str(beta_head))), kernel="moe_gemm_kernel<1> (up-projection + SwiGLU)", kernel_us=k_us, launches=probe_n,
                 algorithmic_flops=k_flops, algorithmic_bytes=k_bytes)
     t_hbm, t_mfma, nbytes, flops = tuner.roofline_lower_bound_us(s, T_head, p.counts, HBM_PEAK_TBS, MFMA_PEAK_PFLOPS)
     whole = dict(bound="hbm" if t_hbm >= t_mfma else "mfma", lower_bound_us=max(t_hbm, t_mfma),

@@ -45,6 +45,13 @@
     X(64, 128, 64, 2, 2, 3, true)   \
     X(32, 128, 64, 1, 4, 3, true)
 
+// two independent 4-wavefront workgroups per compute unit (72 KB of LDS each)
+#define RAMP_CONFIG_GROUP6(X) \
+    X(128, 256, 32, 2, 2, 3, false) \
+    X(256, 128, 32, 2, 2, 3, false) \
+    X(128, 256, 32, 1, 4, 3, false) \
+    X(128, 128, 32, 2, 2, 4, false)
+
 // Weight-streaming family (moe_stream.h): X(bm, FBW, WF, WK, U) ->
 // bn = WF*FBW*16 weight rows per tile, WF*WK wavefronts, K split WK ways inside the workgroup,
 // U k-steps per load batch.

@@ -1,0 +1,12 @@
+// Instantiates one group of the tile family; see config_list.h and moe_gemm.h.
+#include "config_list.h"
+#include "moe_gemm.h"
+
+namespace ramp {
+void register_group6(KernelInfo *out, int *n)
+{
+#define X(BM, BN, BK, WM, WN, NS, PIPE) out[(*n)++] = make_info<BM, BN, BK, WM, WN, NS, PIPE>();
+    RAMP_CONFIG_GROUP6(X)
+#undef X
+}
+}  // namespace ramp
