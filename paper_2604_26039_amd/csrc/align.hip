@@ -108,16 +108,18 @@ __device__ void block_scatter_chunk(const int32_t *ids, int base, int P, int E, 
     }
     int rank = 0;
     bool pending = (e >= 0);
-    for (;;) {
-        unsigned long long rem = __ballot(pending);
-        if (rem == 0) break;
-        int leader = __ffsll((long long)rem) - 1;
-        int e0 = __shfl(e, leader, kWave);
-        unsigned long long same = __ballot(e == e0);
-        if (e == e0) {
-            rank = __popcll(same & ((1ull << lane) - 1ull));
-            if (rank == 0) wcnt[wv * E + e0] = (stamp << 8) | (unsigned)__popcll(same);
-            pending = false;
+    // One round per distinct expert in the wavefront: the first pending lane names its expert
+    // (scalar read, no cross-lane traffic), all pending lanes with that expert take their rank
+    // from the ballot and retire together.
+    while (__ballot(pending) != 0) {
+        if (pending) {
+            const int e0 = __builtin_amdgcn_readfirstlane(e);
+            const unsigned long long same = __ballot(e == e0);  // among the pending lanes
+            if (e == e0) {
+                rank = __popcll(same & ((1ull << lane) - 1ull));
+                if (rank == 0) wcnt[wv * E + e0] = (stamp << 8) | (unsigned)__popcll(same);
+                pending = false;
+            }
         }
     }
     __syncthreads();
@@ -214,18 +216,22 @@ __global__ __launch_bounds__(NT) void align_scan_kernel(int B, int E, int bm, in
     int *toff = lds, *wsum = lds + E + 1;
     const int e = threadIdx.x;
     int n_e = 0;
-    if (e < E)
+    if (e < E) {
+#pragma unroll 8
         for (int b = 0; b < B; ++b) n_e += block_counts[(size_t)b * E + e];
+    }
     if (!scatter) {
         if (e < E) counts[e] = n_e;
         return;
     }
     int dropped = 0;
+#pragma unroll 8
     for (int b = 0; b < B; ++b) dropped += block_dropped[b];
     block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, counts, meta, tile_expert);
     __syncthreads();
     if (e < E) {
         int run = toff[e];
+#pragma unroll 8
         for (int b = 0; b < B; ++b) {
             block_base[(size_t)b * E + e] = run;
             run += block_counts[(size_t)b * E + e];

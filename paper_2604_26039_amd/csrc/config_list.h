@@ -50,7 +50,9 @@
     X(128, 256, 32, 2, 2, 3, false) \
     X(256, 128, 32, 2, 2, 3, false) \
     X(128, 256, 32, 1, 4, 3, false) \
-    X(128, 128, 32, 2, 2, 4, false)
+    X(128, 128, 32, 2, 2, 4, false) \
+    X(128, 128, 32, 2, 2, 3, false) \
+    X(64, 256, 32, 1, 4, 3, false)
 
 // Weight-streaming family (moe_stream.h): X(bm, FBW, WF, WK, U) ->
 // bn = WF*FBW*16 weight rows per tile, WF*WK wavefronts, K split WK ways inside the workgroup,

@@ -44,40 +44,47 @@ template <bool Y16>
 __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ Y, const int32_t *__restrict__ ids, int T,
                                                       int k, int E, int H, uint16_t *__restrict__ out)
 {
-    const int hv = H / 4;  // 4-feature columns
+    const int hv = H / 8;  // 8-feature columns: one 16-byte bf16 load (or two fp32 ones) per pair row
     const size_t total = (size_t)T * hv;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int t = (int)(i / hv), c = (int)(i % hv);
-        float s[4] = {0.f, 0.f, 0.f, 0.f};
+        float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        const int32_t *row_ids = ids + (size_t)t * k;
+#pragma unroll 4
         for (int j = 0; j < k; ++j) {
-            const int id = ids[(size_t)t * k + j];
-            if (id < 0 || id >= E) continue;
-            const size_t elem = ((size_t)t * k + j) * H + (size_t)c * 4;
+            const int id = row_ids[j];
+            const bool live = id >= 0 && id < E;
+            const size_t elem = ((size_t)t * k + j) * H + (size_t)c * 8;
             if (Y16) {
-                const uint2 y = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(Y) + elem);
-                s[0] += __builtin_bit_cast(float, y.x << 16);
-                s[1] += __builtin_bit_cast(float, y.x & 0xffff0000u);
-                s[2] += __builtin_bit_cast(float, y.y << 16);
-                s[3] += __builtin_bit_cast(float, y.y & 0xffff0000u);
+                uint4 y = make_uint4(0, 0, 0, 0);
+                if (live) y = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(Y) + elem);
+                const uint32_t w[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    s[2 * q] += __builtin_bit_cast(float, w[q] << 16);
+                    s[2 * q + 1] += __builtin_bit_cast(float, w[q] & 0xffff0000u);
+                }
             } else {
-                const float4 y = *reinterpret_cast<const float4 *>(Y + elem);
-                s[0] += y.x;
-                s[1] += y.y;
-                s[2] += y.z;
-                s[3] += y.w;
+                float4 y0 = make_float4(0.f, 0.f, 0.f, 0.f), y1 = y0;
+                if (live) {
+                    y0 = *reinterpret_cast<const float4 *>(Y + elem);
+                    y1 = *reinterpret_cast<const float4 *>(Y + elem + 4);
+                }
+                s[0] += y0.x; s[1] += y0.y; s[2] += y0.z; s[3] += y0.w;
+                s[4] += y1.x; s[5] += y1.y; s[6] += y1.z; s[7] += y1.w;
             }
         }
         union {
-            uint16_t h[4];
-            uint2 u;
+            uint16_t h[8];
+            uint4 u;
         } o;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < 8; ++q) {
             uint32_t b = __builtin_bit_cast(uint32_t, s[q]);
             b += 0x7fffu + ((b >> 16) & 1u);
             o.h[q] = (uint16_t)(b >> 16);
         }
-        *reinterpret_cast<uint2 *>(out + (size_t)t * H + (size_t)c * 4) = o.u;
+        *reinterpret_cast<uint4 *>(out + (size_t)t * H + (size_t)c * 8) = o.u;
     }
 }
 
@@ -197,7 +204,7 @@ int launch_combine(const float *Y, int y_bf16, const int32_t *ids, int T, int k,
                    hipStream_t stream)
 {
     if (T == 0) return RAMP_OK;
-    size_t total = (size_t)T * (H / 4);
+    size_t total = (size_t)T * (H / 8);
     unsigned grid = (unsigned)((total + 255) / 256);
     if (grid > (unsigned)kNumCU * 16) grid = kNumCU * 16;
     if (y_bf16)
@@ -314,8 +321,8 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
         return RAMP_EINVAL;
     }
     if (reinterpret_cast<uintptr_t>(ws) % 256 || reinterpret_cast<uintptr_t>(packed_weights) % 256 ||
-        reinterpret_cast<uintptr_t>(X) % 16 || reinterpret_cast<uintptr_t>(out) % 8) {
-        set_error("fused_moe: misaligned buffer (ws/packed 256 B, X 16 B, out 8 B)");
+        reinterpret_cast<uintptr_t>(X) % 16 || reinterpret_cast<uintptr_t>(out) % 16) {
+        set_error("fused_moe: misaligned buffer (ws/packed 256 B, X and out 16 B)");
         return RAMP_EINVAL;
     }
     const Workspace w = workspace_layout(s, *cfg);

@@ -41,10 +41,11 @@ struct TileTraits {
     static constexpr int FB1 = RB / 2 / WN;          // stage 1: feature blocks per wavefront (gate and up each)
     static constexpr int FB2 = RB / WN;              // stage 2
     static constexpr int ACC_REGS = 2 * FB1 * NB * 4;
-    // 4-wavefront tiles that need at most half of the LDS are compiled for two workgroups per compute
-    // unit (two wavefronts per SIMD, <= 256 registers each): the two workgroups share no barrier, so one
+    // 4-wavefront tiles that need at most half (a third) of the LDS are compiled for two (three) workgroups
+    // per compute unit (that many wavefronts per SIMD, <= 256 (170) registers each): the two workgroups share no barrier, so one
     // computes while the other waits for its loads.
-    static constexpr int MIN_WAVES_PER_SIMD = (NWAVE == 4 && LDS_BYTES <= 80 * 1024) ? 2 : 1;
+    static constexpr int MIN_WAVES_PER_SIMD =
+        (NWAVE == 4 && LDS_BYTES <= 53 * 1024 && ACC_REGS <= 64) ? 3 : ((NWAVE == 4 && LDS_BYTES <= 80 * 1024) ? 2 : 1);
     static_assert(NBT % WM == 0, "token blocks must split evenly over WM");
     static_assert(RB % (2 * WN) == 0, "bn must be a multiple of 32*WN");
     static_assert(BK % 32 == 0, "bk must be a multiple of 32");
