@@ -69,8 +69,8 @@ const char *ramp_last_error(void);
 /* ---- configuration family (Sec. 4.3 "Configuration diversity") ------------------------- */
 
 /* Number of configurations that are valid for this shape under gfx950 limits
- * (LDS 160 KB per CU, register budget, MFMA 16x16x32 alignment, H % 32 == 0,
- * I % 32 == 0, tile widths dividing 2*I and H).  Host only. */
+ * (LDS 160 KB per CU, register budget, MFMA 16x16x32 alignment, H % 128 == 0,
+ * I % 128 == 0, tile widths dividing 2*I and H).  Host only. */
 int ramp_num_configs(const ramp_shape *shape);
 /* idx-th valid configuration, 0 <= idx < ramp_num_configs(). */
 int ramp_get_config(const ramp_shape *shape, int idx, ramp_config *out);

@@ -145,8 +145,8 @@ Workspace workspace_layout(const ramp_shape &s, const ramp_config &c)
 
 bool shape_ok(const ramp_shape &s)
 {
-    return s.T >= 0 && s.k >= 1 && s.E >= 1 && s.E <= kAlignMaxE && s.H >= 32 && s.I >= 32 && s.H % 32 == 0 &&
-           s.I % 32 == 0 && (long long)s.T * s.k < (1ll << 30);
+    return s.T >= 0 && s.k >= 1 && s.E >= 1 && s.E <= kAlignMaxE && s.H >= 128 && s.I >= 128 && s.H % 128 == 0 &&
+           s.I % 128 == 0 && (long long)s.T * s.k < (1ll << 30);
 }
 
 }  // namespace
@@ -300,7 +300,7 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     }
     const ramp_shape &s = *shape;
     if (!shape_ok(s)) {
-        set_error("fused_moe: unsupported shape T=%d k=%d E=%d H=%d I=%d (need H, I multiples of 32, E<=%d)", s.T, s.k,
+        set_error("fused_moe: unsupported shape T=%d k=%d E=%d H=%d I=%d (need H, I multiples of 128, E<=%d)", s.T, s.k,
                   s.E, s.H, s.I, kAlignMaxE);
         return RAMP_EUNSUPPORTED;
     }

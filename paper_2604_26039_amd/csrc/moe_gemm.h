@@ -63,7 +63,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
     return (uint16_t)(u >> 16);
 }
 
-__device__ __forceinline__ float silu_f32(float x) { return x / (1.0f + __expf(-x)); }
+// SiLU(x) = x / (1 + e^-x) with the hardware exp2 and reciprocal (1 ulp each; the result is rounded to
+// bf16 right after, which is 2^16 times coarser).
+__device__ __forceinline__ float silu_f32(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 
 // Four consecutive features of one weighted per-pair output row: fp32, or bf16 for large batches.
 __device__ __forceinline__ void store_pair_row(const GemmArgs &a, size_t elem, float v0, float v1, float v2, float v3)
@@ -80,6 +82,73 @@ __device__ __forceinline__ void store_pair_row(const GemmArgs &a, size_t elem, f
         *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y_out) + elem) = o.v;
     } else {
         *reinterpret_cast<float4 *>(a.y_out + elem) = make_float4(v0, v1, v2, v3);
+    }
+}
+
+// Eight consecutive bf16 features (two neighbouring row blocks of one interleave group) in one 16-byte store.
+__device__ __forceinline__ void store_bf16x8(uint16_t *dst, const float *v)
+{
+    union {
+        uint16_t h[8];
+        uint4 u;
+    } o;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o.h[c] = f32_to_bf16_bits(v[c]);
+    *reinterpret_cast<uint4 *>(dst) = o.u;
+}
+__device__ __forceinline__ void store_bf16x4(uint16_t *dst, const float *v)
+{
+    union {
+        uint16_t h[4];
+        uint2 u;
+    } o;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) o.h[c] = f32_to_bf16_bits(v[c]);
+    *reinterpret_cast<uint2 *>(dst) = o.u;
+}
+
+// Epilogue of one token row of a wavefront: FB consecutive row blocks starting at row block rb0, lane
+// group q.  Stage 1 turns (gate, up) into SiLU(g)*u -> bf16; stage 2 scales by the router weight and
+// stores fp32 or bf16.  Neighbouring row blocks of an interleave group are adjacent in memory, so bf16
+// results leave in 16-byte stores wherever two of them line up.
+template <int STAGE, int FB>
+__device__ __forceinline__ void store_token_row(const GemmArgs &a, const floatx4 *acc_g, const floatx4 *acc_u, int stride,
+                                                size_t row_elem, int rb0, int q, float wgt)
+{
+    float v[FB][4];
+#pragma unroll
+    for (int i = 0; i < FB; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float g = acc_g[i * stride][c];
+            v[i][c] = (STAGE == 1) ? silu_f32(g) * acc_u[i * stride][c] : wgt * g;
+        }
+    if (STAGE == 2 && !a.y_bf16) {
+#pragma unroll
+        for (int i = 0; i < FB; ++i)
+            *reinterpret_cast<float4 *>(a.y_out + row_elem + packed_row_feature(rb0 + i, q * 4)) =
+                make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
+        return;
+    }
+    uint16_t *base = (STAGE == 1) ? a.a_out : reinterpret_cast<uint16_t *>(a.y_out);
+    // row blocks rb0.. are consecutive; pairs (even, odd) inside a group of kPermBlocks are 8 adjacent features
+    int i = 0;
+    if ((rb0 & 1) && FB > 0) {
+        store_bf16x4(base + row_elem + packed_row_feature(rb0, q * 4), v[0]);
+        i = 1;
+    }
+#pragma unroll
+    for (int j = 0; j < FB; ++j) {
+        if (j < i) continue;
+        if (((j - i) & 1) == 0) {
+            if (j + 1 < FB) {
+                float w8[8] = {v[j][0], v[j][1], v[j][2], v[j][3], v[j + 1 < FB ? j + 1 : j][0], v[j + 1 < FB ? j + 1 : j][1],
+                               v[j + 1 < FB ? j + 1 : j][2], v[j + 1 < FB ? j + 1 : j][3]};
+                store_bf16x8(base + row_elem + packed_row_feature(rb0 + j, q * 4), w8);
+            } else {
+                store_bf16x4(base + row_elem + packed_row_feature(rb0 + j, q * 4), v[j]);
+            }
+        }
     }
 }
 
@@ -194,6 +263,19 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
         if (tr0 < BM && a.sorted[m_tile * BM + tr0] < a.P) nb_valid = nb + 1;
     }
     nb_valid = __builtin_amdgcn_readfirstlane(nb_valid);
+
+    // stage 2: destination pair and router weight of this lane's token rows, fetched now so the
+    // epilogue does not end on two dependent global loads
+    int out_pair[NB];
+    float out_wgt[NB];
+    if (STAGE == 2) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int tr = (wm * NB + nb) * 16 + r16;
+            out_pair[nb] = (tr < BM && nb < nb_valid) ? a.sorted[m_tile * BM + tr] : a.P;
+            out_wgt[nb] = (out_pair[nb] < a.P) ? a.topk_w[out_pair[nb]] : 0.0f;
+        }
+    }
 
     auto compute_slice = [&](int buf) {
         const uint16_t *xs = &lds[buf * TT::BUF_ELEMS + lane * 8];
@@ -317,34 +399,21 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
     }
 
     // ---- epilogue: lane holds features f = fblock*16 + 4*q + {0..3} of token n = r16 ----
+#ifdef RAMP_ABL_NOSTORE
+    if (acc[0][0][0] != 12345.678f) return;
+#endif
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int tr = (wm * NB + nb) * 16 + r16;
         if (tr >= BM || nb >= nb_valid) continue;
         const int slot = m_tile * BM + tr;
+        const int rb0 = f0 / 16 + wn * FB;
         if (STAGE == 1) {
-#pragma unroll
-            for (int i = 0; i < FB; ++i) {
-                const floatx4 g = acc[i][nb], u = acc[FB + i][nb];
-                const int f = f0 + (wn * FB + i) * 16 + q * 4;
-                union {
-                    uint16_t h[4];
-                    uint2 v;
-                } o;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) o.h[c] = f32_to_bf16_bits(silu_f32(g[c]) * u[c]);
-                *reinterpret_cast<uint2 *>(a.a_out + (size_t)slot * a.F + f) = o.v;
-            }
+            store_token_row<1, FB>(a, &acc[0][nb], &acc[FB][nb], NB, (size_t)slot * a.F, rb0, q, 1.0f);
         } else {
-            const int pair = a.sorted[slot];
+            const int pair = out_pair[nb];
             if (pair >= a.P) continue;
-            const float wgt = a.topk_w[pair];
-#pragma unroll
-            for (int i = 0; i < FB; ++i) {
-                const floatx4 y = acc[i][nb];
-                const int f = f0 + (wn * FB + i) * 16 + q * 4;
-                store_pair_row(a, (size_t)pair * a.F + f, wgt * y[0], wgt * y[1], wgt * y[2], wgt * y[3]);
-            }
+            store_token_row<2, FB>(a, &acc[0][nb], &acc[0][nb], NB, (size_t)pair * a.F, rb0, q, out_wgt[nb]);
         }
     }
 }

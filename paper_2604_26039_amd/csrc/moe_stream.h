@@ -166,27 +166,11 @@ __global__ __launch_bounds__(WF *WK * 64) void moe_stream_kernel(GemmArgs a)
         if (tr >= BM) continue;
         const int slot = m_tile * BM + tr;
         if (STAGE == 1) {
-#pragma unroll
-            for (int i = 0; i < FPW; ++i) {
-                const floatx4 g = acc[i][nb], u = acc[FPW + i][nb];
-                union {
-                    uint16_t h[4];
-                    uint2 v;
-                } o;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) o.h[c] = f32_to_bf16_bits(silu_f32(g[c]) * u[c]);
-                *reinterpret_cast<uint2 *>(a.a_out + (size_t)slot * a.F + f0 + i * 16 + q * 4) = o.v;
-            }
+            store_token_row<1, FPW>(a, &acc[0][nb], &acc[FPW][nb], NB, (size_t)slot * a.F, f0 / 16, q, 1.0f);
         } else {
             const int pair = pair_of[nb];
             if (pair >= a.P) continue;
-            const float wgt = a.topk_w[pair];
-#pragma unroll
-            for (int i = 0; i < FPW; ++i) {
-                const floatx4 y = acc[i][nb];
-                store_pair_row(a, (size_t)pair * a.F + f0 + i * 16 + q * 4, wgt * y[0], wgt * y[1], wgt * y[2],
-                               wgt * y[3]);
-            }
+            store_token_row<2, FPW>(a, &acc[0][nb], &acc[0][nb], NB, (size_t)pair * a.F, f0 / 16, q, a.topk_w[pair]);
         }
     }
 }

@@ -3,7 +3,8 @@
 // Boundary layout: W_gate, W_up [E,H,I] and W_down [E,I,H] (x W convention, Sec. 2.2).
 // Packed layout: per expert, W^T cut into fragments of 16 output rows x 32 k-values, each
 // stored as the 64-lane register image of one v_mfma_f32_16x16x32_bf16 operand
-// (row r = lane % 16, k = 8*(lane / 16) + j  ->  element lane*8 + j).  Fragments of one
+// (row r = lane % 16, k = 8*(lane / 16) + j  ->  element lane*8 + j; the feature in row r of row
+// block rb is packed_row_feature(rb, r), an interleave inside groups of 128 features).  Fragments of one
 // 16-row block are contiguous along k, so a wavefront streaming a row block reads one
 // contiguous range and every load is a full 1 KB line.
 //   [E][gate: I/16 row blocks][H/32 k-steps][512]  then  [up: same]      (up-projection)
@@ -52,7 +53,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t *__restrict__ 
         const int kst = K / 32;
         const int ks = (int)(frag % kst);
         const int rb = (int)(frag / kst);
-        const int f = rb * 16 + (lane % 16);
+        const int f = packed_row_feature(rb, lane % 16);
         const int k0 = ks * 32 + (lane / 16) * 8;
         const uint16_t *s = src + (size_t)e * K * F + (size_t)k0 * F + f;
         union {
@@ -91,8 +92,8 @@ extern "C" int ramp_pack_weights(const ramp_shape *shape, const void *W_gate, co
         return RAMP_EINVAL;
     }
     const ramp_shape &s = *shape;
-    if (s.E <= 0 || s.H <= 0 || s.I <= 0 || s.H % 32 || s.I % 32) {
-        set_error("pack: need E>0 and H, I multiples of 32 (H=%d I=%d)", s.H, s.I);
+    if (s.E <= 0 || s.H <= 0 || s.I <= 0 || s.H % 128 || s.I % 128) {
+        set_error("pack: need E>0 and H, I multiples of 128 (H=%d I=%d)", s.H, s.I);
         return RAMP_EUNSUPPORTED;
     }
     if (reinterpret_cast<uintptr_t>(packed) % 256) {

@@ -41,6 +41,16 @@ int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorte
 // One fragment = 16 weight rows x 32 k-values = 512 bf16 = 1 KB, stored in the lane order
 // of the A operand of v_mfma_f32_16x16x32_bf16: element (row r, k = 8*q + j) at (q*16 + r)*8 + j.
 constexpr int kFragElems = 512;
+// Which output feature sits in row r of packed row block rb.  Inside every group of 8 row blocks
+// (128 features) the rows are interleaved so that, after the MFMA, lane group q of a wavefront holds
+// 4 consecutive features per row block it owns, consecutive row blocks continuing the run: a lane
+// that owns all 8 row blocks of a group stores 32 consecutive features (64 B of bf16) per token
+// instead of 8 separate 8-byte pieces.  Pure relabelling: the packing kernel and the epilogues agree.
+constexpr int kPermBlocks = 8;
+__host__ __device__ inline int packed_row_feature(int rb, int r)
+{
+    return (rb / kPermBlocks) * (16 * kPermBlocks) + (r >> 2) * (4 * kPermBlocks) + (rb % kPermBlocks) * 4 + (r & 3);
+}
 struct PackedLayout {
     size_t w1_expert_elems;  // gate then up: 2 * I * H
     size_t up_offset_elems;  // I * H
