@@ -317,7 +317,8 @@ def main():
 
     report["summary"] = summary
     report["headline"] = dict(T=T_head, beta=beta_head, us=ms_per_step * 1e3, config=cfg_head.key(), whole_path=whole)
-    with open(os.path.join(args.out, f"bench_{args.model}.json"), "w") as f:
+    tag = "_fixed_config" if fixed_cfg is not None else ""
+    with open(os.path.join(args.out, f"bench_{args.model}{tag}.json"), "w") as f:
         json.dump(report, f)
 
     line = {

@@ -3,56 +3,65 @@
 // Split in groups only so that the groups compile in parallel.
 #pragma once
 
-// LDS-staged family (moe_gemm.h): X(bm, bn, bk, WM, WN, NSTAGE, PIPE); PIPE = register-pipelined
-// main loop (one wavefront per SIMD, explicit double buffering of the operand fragments).
+// LDS-staged family (moe_gemm.h): X(bm, bn, bk, WM, WN, NSTAGE, LOOP); LOOP 0 = one barrier per slice,
+// 1 = register-pipelined (explicit double buffering of the operand fragments), 2 = ping-pong (two
+// groups of four wavefronts alternate memory and MFMA phases).
 #define RAMP_CONFIG_GROUP0(X) \
-    X(32, 128, 64, 1, 4, 3, false)   \
-    X(32, 256, 64, 1, 4, 2, false)   \
-    X(64, 128, 64, 2, 2, 3, false)   \
-    X(64, 256, 64, 2, 2, 2, false)
+    X(32, 128, 64, 1, 4, 3, 0)   \
+    X(32, 256, 64, 1, 4, 2, 0)   \
+    X(64, 128, 64, 2, 2, 3, 0)   \
+    X(64, 256, 64, 2, 2, 2, 0)
 
 #define RAMP_CONFIG_GROUP1(X) \
-    X(64, 256, 64, 2, 4, 3, false)   \
-    X(128, 128, 64, 2, 2, 3, false)  \
-    X(128, 128, 64, 2, 4, 3, false)  \
-    X(128, 256, 64, 2, 4, 3, false)
+    X(64, 256, 64, 2, 4, 3, 0)   \
+    X(128, 128, 64, 2, 2, 3, 0)  \
+    X(128, 128, 64, 2, 4, 3, 0)  \
+    X(128, 256, 64, 2, 4, 3, 0)
 
 #define RAMP_CONFIG_GROUP2(X) \
-    X(128, 256, 64, 2, 4, 2, false)  \
-    X(128, 256, 32, 2, 4, 4, false)  \
-    X(256, 128, 64, 4, 2, 3, false)  \
-    X(256, 128, 64, 4, 2, 2, false)
+    X(128, 256, 64, 2, 4, 2, 0)  \
+    X(128, 256, 32, 2, 4, 4, 0)  \
+    X(256, 128, 64, 4, 2, 3, 0)  \
+    X(256, 128, 64, 4, 2, 2, 0)
 
 // prefill-sized token blocks: large register tiles, one workgroup per compute unit
 #define RAMP_CONFIG_GROUP3(X) \
-    X(256, 256, 64, 2, 4, 2, false)  \
-    X(256, 256, 32, 2, 4, 4, false)  \
-    X(256, 256, 32, 2, 4, 3, false)  \
-    X(256, 256, 64, 2, 2, 2, false) \
-    X(256, 256, 64, 2, 2, 2, true)  \
-    X(128, 256, 64, 2, 2, 3, true)  \
-    X(128, 128, 64, 2, 2, 3, true)
+    X(256, 256, 64, 2, 4, 2, 0)  \
+    X(256, 256, 32, 2, 4, 4, 0)  \
+    X(256, 256, 32, 2, 4, 3, 0)  \
+    X(256, 256, 64, 2, 2, 2, 0) \
+    X(256, 256, 64, 2, 2, 2, 1)  \
+    X(128, 256, 64, 2, 2, 3, 1)  \
+    X(128, 128, 64, 2, 2, 3, 1)
 
 #define RAMP_CONFIG_GROUP4(X) \
-    X(256, 256, 64, 2, 4, 2, true)  \
-    X(128, 256, 64, 2, 4, 3, true)  \
-    X(128, 256, 64, 2, 4, 2, true)  \
-    X(256, 128, 64, 4, 2, 3, true)
+    X(256, 256, 64, 2, 4, 2, 1)  \
+    X(128, 256, 64, 2, 4, 3, 1)  \
+    X(128, 256, 64, 2, 4, 2, 1)  \
+    X(256, 128, 64, 4, 2, 3, 1)
 
 #define RAMP_CONFIG_GROUP5(X) \
-    X(64, 256, 64, 2, 4, 3, true)   \
-    X(128, 128, 64, 2, 4, 3, true)  \
-    X(64, 128, 64, 2, 2, 3, true)   \
-    X(32, 128, 64, 1, 4, 3, true)
+    X(64, 256, 64, 2, 4, 3, 1)   \
+    X(128, 128, 64, 2, 4, 3, 1)  \
+    X(64, 128, 64, 2, 2, 3, 1)   \
+    X(32, 128, 64, 1, 4, 3, 1)
 
 // two independent 4-wavefront workgroups per compute unit (72 KB of LDS each)
 #define RAMP_CONFIG_GROUP6(X) \
-    X(128, 256, 32, 2, 2, 3, false) \
-    X(256, 128, 32, 2, 2, 3, false) \
-    X(128, 256, 32, 1, 4, 3, false) \
-    X(128, 128, 32, 2, 2, 4, false) \
-    X(128, 128, 32, 2, 2, 3, false) \
-    X(64, 256, 32, 1, 4, 3, false)
+    X(128, 256, 32, 2, 2, 3, 0) \
+    X(256, 128, 32, 2, 2, 3, 0) \
+    X(128, 256, 32, 1, 4, 3, 0) \
+    X(128, 128, 32, 2, 2, 4, 0) \
+    X(128, 128, 32, 2, 2, 3, 0) \
+    X(64, 256, 32, 1, 4, 3, 0)
+
+#define RAMP_CONFIG_GROUP7(X) \
+    X(256, 256, 32, 2, 4, 4, 2) \
+    X(256, 256, 32, 2, 4, 3, 2) \
+    X(256, 256, 64, 2, 4, 2, 2) \
+    X(128, 256, 32, 2, 4, 4, 2) \
+    X(128, 256, 64, 2, 4, 3, 2) \
+    X(256, 128, 32, 4, 2, 4, 2)
 
 // Weight-streaming family (moe_stream.h): X(bm, FBW, WF, WK, U) ->
 // bn = WF*FBW*16 weight rows per tile, WF*WK wavefronts, K split WK ways inside the workgroup,

@@ -13,6 +13,7 @@ void register_group3(KernelInfo *, int *);
 void register_group4(KernelInfo *, int *);
 void register_group5(KernelInfo *, int *);
 void register_group6(KernelInfo *, int *);
+void register_group7(KernelInfo *, int *);
 void register_stream_group0(KernelInfo *, int *);
 void register_stream_group1(KernelInfo *, int *);
 
@@ -32,6 +33,7 @@ void init_registry()
         register_group4(g_kernels, &g_num_kernels);
         register_group5(g_kernels, &g_num_kernels);
         register_group6(g_kernels, &g_num_kernels);
+        register_group7(g_kernels, &g_num_kernels);
         register_stream_group0(g_kernels, &g_num_kernels);
         register_stream_group1(g_kernels, &g_num_kernels);
     });

@@ -5,7 +5,7 @@
 namespace ramp {
 void register_group2(KernelInfo *out, int *n)
 {
-#define X(BM, BN, BK, WM, WN, NS, PIPE) out[(*n)++] = make_info<BM, BN, BK, WM, WN, NS, PIPE>();
+#define X(BM, BN, BK, WM, WN, NS, LOOP) out[(*n)++] = make_info<BM, BN, BK, WM, WN, NS, LOOP>();
     RAMP_CONFIG_GROUP2(X)
 #undef X
 }

@@ -1,0 +1,12 @@
+// Instantiates one group of the tile family; see config_list.h and moe_gemm.h.
+#include "config_list.h"
+#include "moe_gemm.h"
+
+namespace ramp {
+void register_group7(KernelInfo *out, int *n)
+{
+#define X(BM, BN, BK, WM, WN, NS, LOOP) out[(*n)++] = make_info<BM, BN, BK, WM, WN, NS, LOOP>();
+    RAMP_CONFIG_GROUP7(X)
+#undef X
+}
+}  // namespace ramp

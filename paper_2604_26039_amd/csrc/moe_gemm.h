@@ -167,7 +167,7 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE, bool PIPE>
+template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int LOOP>
 __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE>::MIN_WAVES_PER_SIMD)) void moe_gemm_kernel(
     GemmArgs a)
 {
@@ -303,13 +303,13 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
     };
 
     const int KT = K / BK;
-    if constexpr (PIPE) {
+    if constexpr (LOOP == 1) {
         // Register-pipelined main loop for one wavefront per SIMD: two register sets of operand
         // fragments; while the MFMAs of k-step g run on one set, the ds_reads of k-step g+1 fill
         // the other.  All NSTAGE buffers are kept full: at the last k-step of slice kt every
         // wavefront already holds its last fragments of that slice in registers, so after one
         // barrier the buffer is handed to the loads of slice kt+NSTAGE.
-        static_assert(!PIPE || KS % 2 == 0, "register sets alternate per k-step: bk must be a multiple of 64");
+        static_assert(LOOP != 1 || KS % 2 == 0, "register sets alternate per k-step: bk must be a multiple of 64");
         bf16x8 fx[2][NB], fw[2][NACC];
         auto read_frags = [&](int set, int buf, int ks) {
             const uint16_t *xs = &lds[buf * TT::BUF_ELEMS + lane * 8];
@@ -375,6 +375,76 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
             }
             buf_cur = buf_next;
         }
+    } else if constexpr (LOOP == 2) {
+        // Ping-pong main loop for 8 wavefronts = two groups of four (one wavefront of each group per
+        // SIMD).  A slice is handled in two phases separated by workgroup barriers: M (issue the loads
+        // of a later slice, read every operand fragment of the current slice into registers) and C (its
+        // MFMAs, registers only).  Group 1 starts one barrier late, so while one group multiplies the
+        // other does its memory phase on the same SIMDs and the matrix pipe never waits for LDS.
+        static_assert(LOOP != 2 || NWAVE == 8, "ping-pong needs two groups of four wavefronts");
+        const int group = wave >> 2;
+        bf16x8 fx[KS][NB], fw[KS][NACC];
+        auto read_all = [&](int buf) {
+            const uint16_t *xs = &lds[buf * TT::BUF_ELEMS + lane * 8];
+            const uint16_t *ws = xs + TT::X_FRAGS * kFragElems;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                for (int i = 0; i < NACC; ++i) {
+                    int rb;
+                    if (STAGE == 1) rb = (i < FB) ? (wn * FB + i) : (TT::RB / 2 + wn * FB + (i - FB));
+                    else rb = wn * FB + i;
+                    fw[ks][i] = *reinterpret_cast<const bf16x8 *>(ws + (rb * KS + ks) * kFragElems);
+                }
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + ((wm * NB + nb) * KS + ks) * kFragElems);
+            }
+        };
+        auto mfma_all = [&]() {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    if (nb < nb_valid) {
+#pragma unroll
+                        for (int i = 0; i < NACC; ++i)
+                            acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][i], fx[ks][nb], acc[i][nb], 0, 0, 0);
+                    }
+                }
+        };
+        auto wait_landed = [&](int later) {  // `later` younger slices may stay in flight
+            if (NSTAGE >= 4 && later >= 2) wait_vmcnt<(NSTAGE >= 4 ? 2 : 0) * SLOTS>();
+            else if (NSTAGE >= 3 && later >= 1) wait_vmcnt<(NSTAGE >= 3 ? 1 : 0) * SLOTS>();
+            else wait_vmcnt<0>();
+        };
+        auto phase_barrier = [&]() {
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+#pragma unroll
+        for (int s = 0; s < NSTAGE - 1; ++s)
+            if (s < KT) issue_slice(s);
+        wait_landed(min(NSTAGE - 2, KT - 1));  // slice 0 is in LDS
+        phase_barrier();
+        if (group == 1) phase_barrier();       // stagger
+        int buf_cur = 0, buf_issue = NSTAGE - 1;
+        for (int kt = 0; kt < KT; ++kt) {
+            // ---- M phase: the buffer of slice kt-1 is free (both groups read it before the last barrier)
+            if (kt + NSTAGE - 1 < KT) issue_slice(buf_issue);
+            read_all(buf_cur);
+            // this wavefront's part of slice kt+1 has to be in LDS before the barrier that lets group 0 read it
+            if (kt + 1 < KT) wait_landed(min(NSTAGE - 2, KT - 2 - kt));
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): fragments in registers, buffer no longer read
+            phase_barrier();
+            // ---- C phase
+            mfma_all();
+            phase_barrier();
+            buf_cur = (buf_cur + 1 == NSTAGE) ? 0 : buf_cur + 1;
+            buf_issue = (buf_issue + 1 == NSTAGE) ? 0 : buf_issue + 1;
+        }
+        if (group == 0) phase_barrier();       // both groups execute the same number of barriers
     } else {
     // prologue: slices 0 .. NSTAGE-2 in flight
 #pragma unroll
@@ -418,7 +488,7 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, bool PIPE>
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int LOOP>
 void launch_gemm(int stage, const GemmArgs &a, hipStream_t stream)
 {
     if (a.n_tiles <= 0 || a.m_tiles_cap <= 0) return;
@@ -431,24 +501,25 @@ void launch_gemm(int stage, const GemmArgs &a, hipStream_t stream)
     const int rounds = (a.m_tiles_cap + per_round - 1) / per_round;
     const dim3 grid((unsigned)rounds * (unsigned)per_round * (unsigned)a.n_tiles), block(WM * WN * 64);
     if (stage == 1)
-        hipLaunchKernelGGL((moe_gemm_kernel<1, BM, BN, BK, WM, WN, NSTAGE, PIPE>), grid, block, 0, stream, g);
+        hipLaunchKernelGGL((moe_gemm_kernel<1, BM, BN, BK, WM, WN, NSTAGE, LOOP>), grid, block, 0, stream, g);
     else
-        hipLaunchKernelGGL((moe_gemm_kernel<2, BM, BN, BK, WM, WN, NSTAGE, PIPE>), grid, block, 0, stream, g);
+        hipLaunchKernelGGL((moe_gemm_kernel<2, BM, BN, BK, WM, WN, NSTAGE, LOOP>), grid, block, 0, stream, g);
 }
 
-constexpr int kModePipe = 0x200;  // config.mode bit: register-pipelined main loop
+constexpr int kModePipe = 0x200;      // config.mode bit: register-pipelined main loop
+constexpr int kModePingPong = 0x400;  // config.mode bit: two wavefront groups alternate memory and MFMA phases
 
-template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, bool PIPE>
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int LOOP>
 KernelInfo make_info()
 {
     using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
     KernelInfo ki;
-    ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | (PIPE ? kModePipe : 0)};
+    ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | (LOOP == 1 ? kModePipe : 0) | (LOOP == 2 ? kModePingPong : 0)};
     ki.wm = WM;
     ki.wn = WN;
     ki.lds_bytes = TT::LDS_BYTES;
     ki.acc_regs = TT::ACC_REGS;
-    ki.launch = &launch_gemm<BM, BN, BK, WM, WN, NSTAGE, PIPE>;
+    ki.launch = &launch_gemm<BM, BN, BK, WM, WN, NSTAGE, LOOP>;
     return ki;
 }
 
