@@ -55,13 +55,14 @@
     X(128, 128, 32, 2, 2, 3, 0) \
     X(64, 256, 32, 1, 4, 3, 0)
 
+// Ping-pong family (moe_pingpong.h): X(bm, bn, bk, WM, WN, NSTAGE), always 8 wavefronts.
 #define RAMP_CONFIG_GROUP7(X) \
-    X(256, 256, 32, 2, 4, 4, 2) \
-    X(256, 256, 32, 2, 4, 3, 2) \
-    X(256, 256, 64, 2, 4, 2, 2) \
-    X(128, 256, 32, 2, 4, 4, 2) \
-    X(128, 256, 64, 2, 4, 3, 2) \
-    X(256, 128, 32, 4, 2, 4, 2)
+    X(256, 256, 32, 2, 4, 4) \
+    X(256, 256, 32, 2, 4, 3) \
+    X(256, 256, 64, 2, 4, 2) \
+    X(128, 256, 32, 2, 4, 4) \
+    X(128, 256, 64, 2, 4, 3) \
+    X(256, 128, 32, 4, 2, 4)
 
 // Weight-streaming family (moe_stream.h): X(bm, FBW, WF, WK, U) ->
 // bn = WF*FBW*16 weight rows per tile, WF*WK wavefronts, K split WK ways inside the workgroup,

@@ -139,7 +139,7 @@ Workspace workspace_layout(const ramp_shape &s, const ramp_config &c)
     w.meta = take(16);
     w.align_ws_bytes = ramp_align_workspace_bytes(s.T, s.k, s.E);
     w.align_ws = take(w.align_ws_bytes);
-    w.a_buf = take(w.cap * (size_t)s.I * 2);
+    w.a_buf = take(align_up(w.cap, 16) * (size_t)s.I * 2);  // fragment-major: whole blocks of 16 slots
     w.y_buf = take((size_t)s.T * s.k * s.H * 4);
     w.total = off;
     return w;
@@ -182,7 +182,7 @@ bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s)
     if ((2 * s.I) % c.bn || s.H % c.bn) return false;  // whole feature tiles in both projections
     // 32-bit element offsets inside the kernels
     const size_t cap = ramp_align_capacity(s.T, s.k, s.E, c.bm);
-    if (cap * (size_t)s.I >= (1ull << 32) || (size_t)s.T * s.H >= (1ull << 32)) return false;
+    if ((cap + 16) * (size_t)s.I >= (1ull << 32) || (size_t)s.T * s.H >= (1ull << 32)) return false;
     if (2ull * s.I * s.H >= (1ull << 32)) return false;
     return true;
 }

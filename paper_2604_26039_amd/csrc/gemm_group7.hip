@@ -1,11 +1,11 @@
-// Instantiates one group of the tile family; see config_list.h and moe_gemm.h.
+// Instantiates the ping-pong group of the tile family; see config_list.h and moe_pingpong.h.
 #include "config_list.h"
-#include "moe_gemm.h"
+#include "moe_pingpong.h"
 
 namespace ramp {
 void register_group7(KernelInfo *out, int *n)
 {
-#define X(BM, BN, BK, WM, WN, NS, LOOP) out[(*n)++] = make_info<BM, BN, BK, WM, WN, NS, LOOP>();
+#define X(BM, BN, BK, WM, WN, NS) out[(*n)++] = make_pingpong_info<BM, BN, BK, WM, WN, NS>();
     RAMP_CONFIG_GROUP7(X)
 #undef X
 }

@@ -130,11 +130,16 @@ __device__ __forceinline__ void store_token_row(const GemmArgs &a, const floatx4
                 make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
         return;
     }
-    uint16_t *base = (STAGE == 1) ? a.a_out : reinterpret_cast<uint16_t *>(a.y_out);
+    // stage 1 writes the activation in the fragment-major layout that stage 2 loads (row_elem is the slot);
+    // 8 features aligned to 8 are contiguous in both layouts
+    auto dst = [&](int feature) -> uint16_t * {
+        if (STAGE == 1) return a.a_out + act_elem((uint32_t)row_elem, (uint32_t)feature, (uint32_t)a.F >> 5);
+        return reinterpret_cast<uint16_t *>(a.y_out) + row_elem + feature;
+    };
     // row blocks rb0.. are consecutive; pairs (even, odd) inside a group of kPermBlocks are 8 adjacent features
     int i = 0;
     if ((rb0 & 1) && FB > 0) {
-        store_bf16x4(base + row_elem + packed_row_feature(rb0, q * 4), v[0]);
+        store_bf16x4(dst(packed_row_feature(rb0, q * 4)), v[0]);
         i = 1;
     }
 #pragma unroll
@@ -144,9 +149,9 @@ __device__ __forceinline__ void store_token_row(const GemmArgs &a, const floatx4
             if (j + 1 < FB) {
                 float w8[8] = {v[j][0], v[j][1], v[j][2], v[j][3], v[j + 1 < FB ? j + 1 : j][0], v[j + 1 < FB ? j + 1 : j][1],
                                v[j + 1 < FB ? j + 1 : j][2], v[j + 1 < FB ? j + 1 : j][3]};
-                store_bf16x8(base + row_elem + packed_row_feature(rb0 + j, q * 4), w8);
+                store_bf16x8(dst(packed_row_feature(rb0 + j, q * 4)), w8);
             } else {
-                store_bf16x4(base + row_elem + packed_row_feature(rb0 + j, q * 4), v[j]);
+                store_bf16x4(dst(packed_row_feature(rb0 + j, q * 4)), v[j]);
             }
         }
     }
@@ -167,6 +172,32 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
+// Workgroup -> tile.  Workgroups are handed to the 8 XCDs round robin (id % 8), each XCD has
+// its own 4 MB L2 and runs 32 workgroups of the large tiles at a time.  Consecutive workgroups of
+// one XCD therefore take a block of group_m M-tiles x all N-tiles: the token slices are shared
+// by the N-tiles and the weight slices by the M-tiles of the same expert while they are
+// still in that XCD's L2 (the XCD-aware analogue of the GROUP_M swizzle, Sec. 4.1 Eq. 4).
+__device__ __forceinline__ void tile_of_workgroup(const GemmArgs &a, int &n_tile, int &m_tile)
+{
+    const int xcd = blockIdx.x & 7, s = blockIdx.x >> 3;
+    const int per_group = a.group_m * a.n_tiles;
+    const int gi = s / per_group, r = s - gi * per_group;
+    n_tile = r / a.group_m;
+    m_tile = (gi * 8 + xcd) * a.group_m + (r - n_tile * a.group_m);
+}
+
+// Picks group_m for the launch and returns the (overlaunched) grid size that tile_of_workgroup expects.
+inline unsigned xcd_grid(GemmArgs &g)
+{
+    // 32 workgroups of an XCD run together: group_m M-tiles x n_tiles N-tiles of them share operands
+    g.group_m = 32 / g.n_tiles;
+    if (g.group_m < 1) g.group_m = 1;
+    if (g.group_m > 8) g.group_m = 8;
+    const int per_round = 8 * g.group_m;  // M-tiles handed out per round over the 8 XCDs
+    const int rounds = (g.m_tiles_cap + per_round - 1) / per_round;
+    return (unsigned)rounds * (unsigned)per_round * (unsigned)g.n_tiles;
+}
+
 template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE, int LOOP>
 __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE>::MIN_WAVES_PER_SIMD)) void moe_gemm_kernel(
     GemmArgs a)
@@ -179,19 +210,8 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
 
     __shared__ __attribute__((aligned(1024))) uint16_t lds[NSTAGE * TT::BUF_ELEMS];
 
-    // Workgroup -> tile.  Workgroups are handed to the 8 XCDs round robin (id % 8), each XCD has
-    // its own 4 MB L2 and runs 32 workgroups of this size at a time.  Consecutive workgroups of
-    // one XCD therefore take a block of group_m M-tiles x all N-tiles: the token slices are shared
-    // by the N-tiles and the weight slices by the M-tiles of the same expert while they are
-    // still in that XCD's L2 (the XCD-aware analogue of the GROUP_M swizzle, Sec. 4.1 Eq. 4).
     int n_tile, m_tile;
-    {
-        const int xcd = blockIdx.x & 7, s = blockIdx.x >> 3;
-        const int per_group = a.group_m * a.n_tiles;
-        const int gi = s / per_group, r = s - gi * per_group;
-        n_tile = r / a.group_m;
-        m_tile = (gi * 8 + xcd) * a.group_m + (r - n_tile * a.group_m);
-    }
+    tile_of_workgroup(a, n_tile, m_tile);
     if (m_tile >= a.meta[1]) return;  // overlaunched grid: surplus workgroups leave at once
 
     const int lane = threadIdx.x & 63;
@@ -215,15 +235,16 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
             int tr = nb * 16 + r16;
             if (tr >= BM) tr = BM - 1;
             const int slot = m_tile * BM + tr;
-            size_t row;
             if (STAGE == 1) {
                 const int pair = a.sorted[slot];
-                row = (pair < a.P) ? (size_t)(pair / a.topk) : 0;
+                const size_t row = (pair < a.P) ? (size_t)(pair / a.topk) : 0;
+                gptr[s] = a.act + row * (size_t)K + (size_t)(ks * 32 + q * 8);
+                gstep[s] = BK;
             } else {
-                row = (size_t)slot;
+                // fragment-major activation written by stage 1: a k-step of 16 slots is one 1 KB line
+                gptr[s] = a.act + act_elem((uint32_t)slot, (uint32_t)(ks * 32 + q * 8), (uint32_t)KST);
+                gstep[s] = KS * kFragElems;
             }
-            gptr[s] = a.act + row * (size_t)K + (size_t)(ks * 32 + q * 8);
-            gstep[s] = BK;
         } else {
             const int widx = idx - TT::X_FRAGS;
             const int rb = widx / KS, ks = widx % KS;
@@ -249,6 +270,12 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
     auto issue_slice = [&](int buf) {
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
+#ifdef RAMP_ABL_NOLOADX
+            if (wave + s * NWAVE < TT::X_FRAGS) continue;
+#endif
+#ifdef RAMP_ABL_NOLOADW
+            if (wave + s * NWAVE >= TT::X_FRAGS) continue;
+#endif
             load_to_lds_16B(gptr[s], &lds[buf * TT::BUF_ELEMS + (wave + s * NWAVE) * kFragElems]);
             gptr[s] += gstep[s];
         }
@@ -375,76 +402,6 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
             }
             buf_cur = buf_next;
         }
-    } else if constexpr (LOOP == 2) {
-        // Ping-pong main loop for 8 wavefronts = two groups of four (one wavefront of each group per
-        // SIMD).  A slice is handled in two phases separated by workgroup barriers: M (issue the loads
-        // of a later slice, read every operand fragment of the current slice into registers) and C (its
-        // MFMAs, registers only).  Group 1 starts one barrier late, so while one group multiplies the
-        // other does its memory phase on the same SIMDs and the matrix pipe never waits for LDS.
-        static_assert(LOOP != 2 || NWAVE == 8, "ping-pong needs two groups of four wavefronts");
-        const int group = wave >> 2;
-        bf16x8 fx[KS][NB], fw[KS][NACC];
-        auto read_all = [&](int buf) {
-            const uint16_t *xs = &lds[buf * TT::BUF_ELEMS + lane * 8];
-            const uint16_t *ws = xs + TT::X_FRAGS * kFragElems;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-                for (int i = 0; i < NACC; ++i) {
-                    int rb;
-                    if (STAGE == 1) rb = (i < FB) ? (wn * FB + i) : (TT::RB / 2 + wn * FB + (i - FB));
-                    else rb = wn * FB + i;
-                    fw[ks][i] = *reinterpret_cast<const bf16x8 *>(ws + (rb * KS + ks) * kFragElems);
-                }
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + ((wm * NB + nb) * KS + ks) * kFragElems);
-            }
-        };
-        auto mfma_all = [&]() {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    if (nb < nb_valid) {
-#pragma unroll
-                        for (int i = 0; i < NACC; ++i)
-                            acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][i], fx[ks][nb], acc[i][nb], 0, 0, 0);
-                    }
-                }
-        };
-        auto wait_landed = [&](int later) {  // `later` younger slices may stay in flight
-            if (NSTAGE >= 4 && later >= 2) wait_vmcnt<(NSTAGE >= 4 ? 2 : 0) * SLOTS>();
-            else if (NSTAGE >= 3 && later >= 1) wait_vmcnt<(NSTAGE >= 3 ? 1 : 0) * SLOTS>();
-            else wait_vmcnt<0>();
-        };
-        auto phase_barrier = [&]() {
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-        };
-#pragma unroll
-        for (int s = 0; s < NSTAGE - 1; ++s)
-            if (s < KT) issue_slice(s);
-        wait_landed(min(NSTAGE - 2, KT - 1));  // slice 0 is in LDS
-        phase_barrier();
-        if (group == 1) phase_barrier();       // stagger
-        int buf_cur = 0, buf_issue = NSTAGE - 1;
-        for (int kt = 0; kt < KT; ++kt) {
-            // ---- M phase: the buffer of slice kt-1 is free (both groups read it before the last barrier)
-            if (kt + NSTAGE - 1 < KT) issue_slice(buf_issue);
-            read_all(buf_cur);
-            // this wavefront's part of slice kt+1 has to be in LDS before the barrier that lets group 0 read it
-            if (kt + 1 < KT) wait_landed(min(NSTAGE - 2, KT - 2 - kt));
-            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): fragments in registers, buffer no longer read
-            phase_barrier();
-            // ---- C phase
-            mfma_all();
-            phase_barrier();
-            buf_cur = (buf_cur + 1 == NSTAGE) ? 0 : buf_cur + 1;
-            buf_issue = (buf_issue + 1 == NSTAGE) ? 0 : buf_issue + 1;
-        }
-        if (group == 0) phase_barrier();       // both groups execute the same number of barriers
     } else {
     // prologue: slices 0 .. NSTAGE-2 in flight
 #pragma unroll
@@ -479,7 +436,7 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
         const int slot = m_tile * BM + tr;
         const int rb0 = f0 / 16 + wn * FB;
         if (STAGE == 1) {
-            store_token_row<1, FB>(a, &acc[0][nb], &acc[FB][nb], NB, (size_t)slot * a.F, rb0, q, 1.0f);
+            store_token_row<1, FB>(a, &acc[0][nb], &acc[FB][nb], NB, (size_t)slot, rb0, q, 1.0f);
         } else {
             const int pair = out_pair[nb];
             if (pair >= a.P) continue;
@@ -493,13 +450,7 @@ void launch_gemm(int stage, const GemmArgs &a, hipStream_t stream)
 {
     if (a.n_tiles <= 0 || a.m_tiles_cap <= 0) return;
     GemmArgs g = a;
-    // 32 workgroups of an XCD run together: group_m M-tiles x n_tiles N-tiles of them share operands
-    g.group_m = 32 / a.n_tiles;
-    if (g.group_m < 1) g.group_m = 1;
-    if (g.group_m > 8) g.group_m = 8;
-    const int per_round = 8 * g.group_m;  // M-tiles handed out per round over the 8 XCDs
-    const int rounds = (a.m_tiles_cap + per_round - 1) / per_round;
-    const dim3 grid((unsigned)rounds * (unsigned)per_round * (unsigned)a.n_tiles), block(WM * WN * 64);
+    const dim3 grid(xcd_grid(g)), block(WM * WN * 64);
     if (stage == 1)
         hipLaunchKernelGGL((moe_gemm_kernel<1, BM, BN, BK, WM, WN, NSTAGE, LOOP>), grid, block, 0, stream, g);
     else
@@ -507,14 +458,14 @@ void launch_gemm(int stage, const GemmArgs &a, hipStream_t stream)
 }
 
 constexpr int kModePipe = 0x200;      // config.mode bit: register-pipelined main loop
-constexpr int kModePingPong = 0x400;  // config.mode bit: two wavefront groups alternate memory and MFMA phases
+constexpr int kModePingPong = 0x400;  // config.mode bit: ping-pong kernel (moe_pingpong.h)
 
 template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int LOOP>
 KernelInfo make_info()
 {
     using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
     KernelInfo ki;
-    ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | (LOOP == 1 ? kModePipe : 0) | (LOOP == 2 ? kModePingPong : 0)};
+    ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | (LOOP == 1 ? kModePipe : 0)};
     ki.wm = WM;
     ki.wn = WN;
     ki.lds_bytes = TT::LDS_BYTES;

@@ -1,0 +1,319 @@
+// Ping-pong variant of the LDS-staged expert projections for the large tiles (256 or 128 token rows,
+// 8 wavefronts): same tile decomposition and epilogues as moe_gemm_kernel, different main loop and
+// different token staging.
+//
+// Main loop.  The 8 wavefronts form two groups of four, one wavefront of each group per SIMD.  A
+// k-slice is handled in two phases separated by workgroup barriers: M (issue the LDS-direct loads of
+// later slices, read every operand fragment of the current slice into registers) and C (its MFMAs,
+// registers only).  Group 1 runs one barrier behind group 0, so while one group multiplies the other
+// does its memory phase on the same SIMDs and the matrix pipe does not wait for LDS.
+//
+// Token staging in the up-projection.  The token rows are gathered (row = pair / k of X, 2*H bytes
+// apart), so every row touched by a load instruction is another page for the address translation in
+// the vector memory path, and that, not bytes, is what the gather costs: 16 rows x 64 B per
+// instruction (one MFMA fragment) runs at a third of the rate of a contiguous 1 KB load.  Here a load
+// instruction takes 8 rows x 128 B (64 k-values per row), which halves the row visits; the 128-byte row
+// pieces land in LDS row-major in 1 KB blocks of 8 rows, with the 16-byte chunk index XOR-ed with
+// (row/2)%8 on the global side so that the ds_read_b128 operand reads (16 rows x one chunk) spread
+// over all banks.  One such token super-slice feeds 64/bk k-slices; weights keep one slice per load
+// batch.  The down-projection reads the fragment-major activation written by the up-projection, where
+// a token fragment is one contiguous 1 KB line, and stages it like the weights.
+#pragma once
+
+#include <type_traits>
+
+#include "moe_gemm.h"
+
+namespace ramp {
+
+template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+struct PingPongTraits {
+    using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
+    static constexpr bool ROWX = (STAGE == 1);           // gathered rows, 128-byte pieces
+    static constexpr int XK = ROWX ? 64 : BK;            // k-values of one token load batch ("super-slice")
+    static constexpr int XS = XK / BK;                   // k-slices fed by one super-slice
+    static constexpr int NX = (XS == 2) ? 2 : NSTAGE;    // token ring depth in super-slices
+    static constexpr int X_BYTES = BM * XK * 2;
+    static constexpr int W_BYTES = TT::W_FRAGS * kFragElems * 2;
+    static constexpr int TSLOTS = X_BYTES / 1024 / TT::NWAVE;  // token load instructions per wavefront per super-slice
+    static constexpr int WSLOTS = TT::W_FRAGS / TT::NWAVE;     // weight load instructions per wavefront per slice
+    static constexpr int LDS_BYTES = NX * X_BYTES + NSTAGE * W_BYTES;
+    static_assert(TT::NWAVE == 8, "ping-pong needs two groups of four wavefronts");
+    static_assert(BK == 32 || BK == 64, "bk 32 or 64");
+    static_assert(BM % 16 == 0 && (X_BYTES / 1024) % TT::NWAVE == 0, "token loads must split evenly");
+    static_assert(TT::W_FRAGS % TT::NWAVE == 0, "weight loads must split evenly");
+    static_assert(NSTAGE >= 3 || XS == 1, "a two-slice token batch needs three weight stages");
+    static_assert(LDS_BYTES <= kLdsBytesPerCU, "tile does not fit in LDS");
+};
+
+// Wait until at most n vector-memory operations of this wavefront are outstanding (n wave-uniform).
+__device__ __forceinline__ void wait_vmcnt_upto(int n)
+{
+    switch (n) {
+    case 0: wait_vmcnt<0>(); break;
+    case 1: wait_vmcnt<1>(); break;
+    case 2: wait_vmcnt<2>(); break;
+    case 3: wait_vmcnt<3>(); break;
+    case 4: wait_vmcnt<4>(); break;
+    case 5: wait_vmcnt<5>(); break;
+    case 6: wait_vmcnt<6>(); break;
+    case 7: wait_vmcnt<7>(); break;
+    case 8: wait_vmcnt<8>(); break;
+    case 9: wait_vmcnt<9>(); break;
+    case 10: wait_vmcnt<10>(); break;
+    case 11: wait_vmcnt<11>(); break;
+    case 12: wait_vmcnt<12>(); break;
+    case 13: wait_vmcnt<13>(); break;
+    case 14: wait_vmcnt<14>(); break;
+    case 15: wait_vmcnt<15>(); break;
+    default: wait_vmcnt<16>(); break;  // n >= 16: waiting for more than asked is always safe
+    }
+}
+
+template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+__global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
+{
+    using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
+    using PT = PingPongTraits<STAGE, BM, BN, BK, WM, WN, NSTAGE>;
+    constexpr int KS = TT::KS, NB = TT::NB, NWAVE = TT::NWAVE;
+    constexpr int FB = (STAGE == 1) ? TT::FB1 : TT::FB2;
+    constexpr int NACC = (STAGE == 1) ? 2 * FB : FB;
+    constexpr int FEAT_PER_TILE = (STAGE == 1) ? BN / 2 : BN;
+    constexpr int XS = PT::XS, NX = PT::NX, TSLOTS = PT::TSLOTS, WSLOTS = PT::WSLOTS;
+
+    __shared__ __attribute__((aligned(1024))) char lds[PT::LDS_BYTES];
+    char *const lds_x = lds;
+    char *const lds_w = lds + NX * PT::X_BYTES;
+
+    int n_tile, m_tile;
+    tile_of_workgroup(a, n_tile, m_tile);
+    if (m_tile >= a.meta[1]) return;  // overlaunched grid: surplus workgroups leave at once
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int group = wave >> 2;
+    const int e = a.tile_expert[m_tile];
+    const int K = a.K, KST = K / 32;
+    const int f0 = n_tile * FEAT_PER_TILE;
+    const uint16_t *wexp = a.wpacked + (size_t)e * a.expert_stride;
+    const int r16 = lane & 15, q = lane >> 4;
+
+    // ---- global element offsets of this lane's loads ----
+    uint32_t xoff[TSLOTS], woff[WSLOTS];
+#pragma unroll
+    for (int t = 0; t < TSLOTS; ++t) {
+        const int blk = wave + t * NWAVE;  // 1 KB block of the super-slice buffer
+        if (PT::ROWX) {
+            const int tr = blk * 8 + (lane >> 3);  // 8 rows per block, 8 lanes (128 B) per row
+            const int pair = a.sorted[m_tile * BM + tr];
+            const uint32_t row = (pair < a.P) ? (uint32_t)(pair / a.topk) : 0u;
+            xoff[t] = row * (uint32_t)K + (uint32_t)(((lane & 7) ^ ((tr >> 1) & 7)) * 8);
+        } else {
+            const int nb = blk / KS, ks = blk % KS;
+            xoff[t] = act_elem((uint32_t)(m_tile * BM + nb * 16 + r16), (uint32_t)(ks * 32 + q * 8), (uint32_t)KST);
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < WSLOTS; ++s) {
+        const int widx = wave + s * NWAVE;
+        const int rb = widx / KS, ks = widx % KS;
+        uint32_t base;
+        if (STAGE == 1) {
+            const int half = TT::RB / 2;
+            base = (rb < half) ? (uint32_t)(f0 / 16 + rb) * (uint32_t)KST * kFragElems
+                               : (uint32_t)a.up_offset + (uint32_t)(f0 / 16 + rb - half) * (uint32_t)KST * kFragElems;
+        } else {
+            base = (uint32_t)(f0 / 16 + rb) * (uint32_t)KST * kFragElems;
+        }
+        woff[s] = base + (uint32_t)ks * kFragElems + (uint32_t)lane * 8;
+    }
+    constexpr uint32_t XSTEP = PT::ROWX ? (uint32_t)PT::XK : (uint32_t)(KS * kFragElems);
+    constexpr uint32_t WSTEP = (uint32_t)(KS * kFragElems);
+
+    auto issue_x = [&](int xbuf) {
+#pragma unroll
+        for (int t = 0; t < TSLOTS; ++t) {
+            load_to_lds_16B(a.act + xoff[t], lds_x + xbuf * PT::X_BYTES + (wave + t * NWAVE) * 1024);
+            xoff[t] += XSTEP;
+        }
+    };
+    auto issue_w = [&](int wbuf) {
+#pragma unroll
+        for (int s = 0; s < WSLOTS; ++s) {
+            load_to_lds_16B(wexp + woff[s], lds_w + wbuf * PT::W_BYTES + (wave + s * NWAVE) * 1024);
+            woff[s] += WSTEP;
+        }
+    };
+
+    floatx4 acc[NACC][NB];
+#pragma unroll
+    for (int i = 0; i < NACC; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // token blocks of this wavefront that hold at least one real row (padding sits at the end of a tile)
+    int nb_valid = 0;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+        if (a.sorted[m_tile * BM + (wm * NB + nb) * 16] < a.P) nb_valid = nb + 1;
+    nb_valid = __builtin_amdgcn_readfirstlane(nb_valid);
+
+    int out_pair[NB];
+    float out_wgt[NB];
+    if (STAGE == 2) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int tr = (wm * NB + nb) * 16 + r16;
+            out_pair[nb] = (nb < nb_valid) ? a.sorted[m_tile * BM + tr] : a.P;
+            out_wgt[nb] = (out_pair[nb] < a.P) ? a.topk_w[out_pair[nb]] : 0.0f;
+        }
+    }
+
+    // ---- LDS read offsets of this lane's operand fragments ----
+    // tokens, row-major super-slice: row (wm*NB+nb)*16 + r16 sits in block row/8 at (row%8)*128, chunk c at (c ^ (row/2)%8)*16
+    const int xrow_off = (wm * NB * 16 + r16) / 8 * 1024 + (r16 & 7) * 128;
+    const int xsw = (r16 >> 1) & 7;
+    bf16x8 fx[KS][NB], fw[KS][NACC];
+    auto read_all = [&](int kk0, int xbuf, int wbuf) {  // kk0: 32-wide k-step of the slice inside its token batch
+        const char *xs = lds_x + xbuf * PT::X_BYTES;
+        const char *ws = lds_w + wbuf * PT::W_BYTES + lane * 16;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int i = 0; i < NACC; ++i) {
+                int rb;
+                if (STAGE == 1) rb = (i < FB) ? (wn * FB + i) : (TT::RB / 2 + wn * FB + (i - FB));
+                else rb = wn * FB + i;
+                fw[ks][i] = *reinterpret_cast<const bf16x8 *>(ws + (rb * KS + ks) * 1024);
+            }
+            if (PT::ROWX) {
+                const int kk = kk0 + ks;
+                const int coff = ((kk * 4 + q) ^ xsw) * 16;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + xrow_off + nb * 2048 + coff);
+            } else {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + ((wm * NB + nb) * KS + ks) * 1024 + lane * 16);
+            }
+        }
+    };
+    auto mfma_all = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                if (nb < nb_valid) {
+#pragma unroll
+                    for (int i = 0; i < NACC; ++i)
+                        acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][i], fx[ks][nb], acc[i][nb], 0, 0, 0);
+                }
+            }
+    };
+    auto phase_barrier = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    const int KT = K / BK;
+    // Loads are issued, and counted by vmcnt, in this order: prologue X(0) W(0) [X(1)] W(1) ..., then in the M
+    // phase of slice kt: the token batch that became free (if any), then weight slice kt+NSTAGE-1.
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s) {
+        if ((XS == 1 || s == 0) && s * XS < KT) issue_x(s);
+        if (s < KT) issue_w(s);
+    }
+    // token batch 0 and weight slice 0 have landed once only the loads issued after W(0) are outstanding
+    wait_vmcnt_upto(min(NSTAGE - 2, KT - 1) * (XS == 1 ? TSLOTS + WSLOTS : WSLOTS));
+    phase_barrier();
+    if (group == 1) phase_barrier();  // stagger
+    int wbuf_cur = 0, wbuf_issue = NSTAGE - 1;
+    auto slice = [&](int kt, auto steady_c) {
+        constexpr bool STEADY = decltype(steady_c)::value;
+        // ---- M phase: both groups have read slice kt-1 (its buffers are free).  Operand reads first, then the loads:
+        // the reads are what the barrier waits for, the loads only have to be issued.
+        const int par = (XS == 2) ? (kt & 1) : 0;  // position of the slice inside its token batch
+        const int xb = (kt / XS) % NX;
+        read_all(par * KS, xb, wbuf_cur);
+        bool x_issued = false;
+        if (par == 0) {
+            const int j = kt / XS + NX - 1;  // token batch that goes into the buffer freed last
+            if (STEADY || j * XS < KT) {
+                issue_x(j % NX);
+                x_issued = true;
+            }
+        }
+        if (STEADY || kt + NSTAGE - 1 < KT) issue_w(wbuf_issue);
+        // this wavefront's part of slice kt+1 has to be in LDS before the barrier after which the other group reads it
+        if (STEADY) {
+            if (XS == 1) wait_vmcnt<(NSTAGE - 2) * (TSLOTS + WSLOTS)>();
+            else if (par == 0) wait_vmcnt<(NSTAGE - 2) * WSLOTS + (XS == 2 ? TSLOTS : 0)>();
+            else wait_vmcnt<(NSTAGE - 2) * WSLOTS>();
+        } else if (kt + 1 < KT) {
+            const int later = min(NSTAGE - 2, KT - 2 - kt);  // younger weight slices that may stay in flight
+            if (XS == 1) wait_vmcnt_upto(later * (TSLOTS + WSLOTS));
+            else wait_vmcnt_upto(later * WSLOTS + (x_issued ? TSLOTS : 0));
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): fragments in registers, buffers no longer read
+        phase_barrier();
+        // ---- C phase
+        mfma_all();
+        phase_barrier();
+        wbuf_cur = (wbuf_cur + 1 == NSTAGE) ? 0 : wbuf_cur + 1;
+        wbuf_issue = (wbuf_issue + 1 == NSTAGE) ? 0 : wbuf_issue + 1;
+    };
+    // the bulk of the loop: every load of the turn exists and NSTAGE-2 younger weight slices stay in flight; then
+    // the last NSTAGE-1 slices with the conditions evaluated
+    int kt = 0;
+    for (; kt <= KT - NSTAGE; ++kt) slice(kt, std::integral_constant<bool, true>{});
+    for (; kt < KT; ++kt) slice(kt, std::integral_constant<bool, false>{});
+    if (group == 0) phase_barrier();  // both groups execute the same number of barriers
+
+    // ---- epilogue: lane holds features fblock*16 + 4*q + {0..3} of token r16 ----
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        if (nb >= nb_valid) continue;
+        const int slot = m_tile * BM + (wm * NB + nb) * 16 + r16;
+        const int rb0 = f0 / 16 + wn * FB;
+        if (STAGE == 1) {
+            store_token_row<1, FB>(a, &acc[0][nb], &acc[FB][nb], NB, (size_t)slot, rb0, q, 1.0f);
+        } else {
+            const int pair = out_pair[nb];
+            if (pair >= a.P) continue;
+            store_token_row<2, FB>(a, &acc[0][nb], &acc[0][nb], NB, (size_t)pair * a.F, rb0, q, out_wgt[nb]);
+        }
+    }
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+void launch_pingpong(int stage, const GemmArgs &a, hipStream_t stream)
+{
+    if (a.n_tiles <= 0 || a.m_tiles_cap <= 0) return;
+    GemmArgs g = a;
+    const dim3 grid(xcd_grid(g)), block(512);
+    if (stage == 1)
+        hipLaunchKernelGGL((moe_pingpong_kernel<1, BM, BN, BK, WM, WN, NSTAGE>), grid, block, 0, stream, g);
+    else
+        hipLaunchKernelGGL((moe_pingpong_kernel<2, BM, BN, BK, WM, WN, NSTAGE>), grid, block, 0, stream, g);
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE>
+KernelInfo make_pingpong_info()
+{
+    using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
+    constexpr int l1 = PingPongTraits<1, BM, BN, BK, WM, WN, NSTAGE>::LDS_BYTES;
+    constexpr int l2 = PingPongTraits<2, BM, BN, BK, WM, WN, NSTAGE>::LDS_BYTES;
+    KernelInfo ki;
+    ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | kModePingPong};
+    ki.wm = WM;
+    ki.wn = WN;
+    ki.lds_bytes = l1 > l2 ? l1 : l2;
+    ki.acc_regs = TT::ACC_REGS;
+    ki.launch = &launch_pingpong<BM, BN, BK, WM, WN, NSTAGE>;
+    return ki;
+}
+
+}  // namespace ramp

@@ -70,10 +70,8 @@ __global__ __launch_bounds__(WF *WK * 64) void moe_stream_kernel(GemmArgs a)
         const int slot = m_tile * BM + tr;
         const int pair = a.sorted[slot];
         pair_of[nb] = live ? pair : a.P;
-        uint32_t row;
-        if (STAGE == 1) row = (pair < a.P) ? (uint32_t)(pair / a.topk) : 0u;
-        else row = (uint32_t)slot;
-        xoff[nb] = row * (uint32_t)K + (uint32_t)(q * 8);
+        if (STAGE == 1) xoff[nb] = ((pair < a.P) ? (uint32_t)(pair / a.topk) : 0u) * (uint32_t)K + (uint32_t)(q * 8);
+        else xoff[nb] = act_elem((uint32_t)slot, (uint32_t)(q * 8), (uint32_t)KST);  // fragment-major, written by stage 1
     }
     // weight row-block offsets (elements) at k-step 0
     uint32_t woff[FBW];
@@ -107,7 +105,7 @@ __global__ __launch_bounds__(WF *WK * 64) void moe_stream_kernel(GemmArgs a)
             if (ks >= ks_end) ks = ks_end - 1;  // tail: re-read the last step, its product is skipped
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-                b.x[u][nb] = *reinterpret_cast<const bf16x8 *>(a.act + xoff[nb] + (size_t)ks * 32);
+                b.x[u][nb] = *reinterpret_cast<const bf16x8 *>(a.act + xoff[nb] + (size_t)ks * (STAGE == 1 ? 32 : kFragElems));
 #pragma unroll
             for (int i = 0; i < FBW; ++i)
                 b.w[u][i] = *reinterpret_cast<const bf16x8 *>(wexp + woff[i] + (size_t)ks * kFragElems);
@@ -166,7 +164,7 @@ __global__ __launch_bounds__(WF *WK * 64) void moe_stream_kernel(GemmArgs a)
         if (tr >= BM) continue;
         const int slot = m_tile * BM + tr;
         if (STAGE == 1) {
-            store_token_row<1, FPW>(a, &acc[0][nb], &acc[FPW][nb], NB, (size_t)slot * a.F, f0 / 16, q, 1.0f);
+            store_token_row<1, FPW>(a, &acc[0][nb], &acc[FPW][nb], NB, (size_t)slot, f0 / 16, q, 1.0f);
         } else {
             const int pair = pair_of[nb];
             if (pair >= a.P) continue;

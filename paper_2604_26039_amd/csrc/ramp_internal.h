@@ -51,6 +51,16 @@ __host__ __device__ inline int packed_row_feature(int rb, int r)
 {
     return (rb / kPermBlocks) * (16 * kPermBlocks) + (r >> 2) * (4 * kPermBlocks) + (rb % kPermBlocks) * 4 + (r & 3);
 }
+// Element offset of (slot, feature) in the intermediate activation A = SiLU(G)*U.  A is private to the
+// library, so the up-projection writes it in the order the down-projection consumes it: blocks of 16
+// slots x 32 features stored as the 64-lane register image of one MFMA token operand (lane =
+// 16*(feature/8 % 4) + slot % 16, 8 features per lane), k-steps of a slot block contiguous.  A k-step of
+// 16 slots is then one contiguous 1 KB line, like a weight fragment.  kst = I / 32.
+__host__ __device__ inline uint32_t act_elem(uint32_t slot, uint32_t feature, uint32_t kst)
+{
+    return ((slot >> 4) * kst + (feature >> 5)) * (uint32_t)kFragElems + ((((feature >> 3) & 3u) << 4) + (slot & 15u)) * 8u +
+           (feature & 7u);
+}
 struct PackedLayout {
     size_t w1_expert_elems;  // gate then up: 2 * I * H
     size_t up_offset_elems;  // I * H
