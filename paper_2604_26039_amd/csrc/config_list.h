@@ -59,9 +59,8 @@
 #define RAMP_CONFIG_GROUP7(X) \
     X(256, 256, 32, 2, 4, 4) \
     X(256, 256, 32, 2, 4, 3) \
-    X(256, 256, 64, 2, 4, 2) \
     X(128, 256, 32, 2, 4, 4) \
-    X(128, 256, 64, 2, 4, 3) \
+    X(128, 256, 32, 2, 4, 3) \
     X(256, 128, 32, 4, 2, 4)
 
 // Weight-streaming family (moe_stream.h): X(bm, FBW, WF, WK, U) ->

@@ -184,6 +184,8 @@ bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s)
     const size_t cap = ramp_align_capacity(s.T, s.k, s.E, c.bm);
     if ((cap + 16) * (size_t)s.I >= (1ull << 32) || (size_t)s.T * s.H >= (1ull << 32)) return false;
     if (2ull * s.I * s.H >= (1ull << 32)) return false;
+    // the ping-pong kernel keeps stages-1 slices in flight across tile boundaries: a tile must be at least that long
+    if ((c.mode & kModePingPong) && (s.H / c.bk < c.stages || s.I / c.bk < c.stages)) return false;
     return true;
 }
 int occupancy_estimate(const KernelInfo &ki)
@@ -351,7 +353,7 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
 
     const PackedLayout L = packed_layout(s);
     const uint16_t *packed = static_cast<const uint16_t *>(packed_weights);
-    GemmArgs g;
+    GemmArgs g = {};
     g.sorted = sorted;
     g.tile_expert = tile_expert;
     g.meta = meta;

@@ -65,7 +65,11 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
 
 // SiLU(x) = x / (1 + e^-x) with the hardware exp2 and reciprocal (1 ulp each; the result is rounded to
 // bf16 right after, which is 2^16 times coarser).
+#ifdef RAMP_ABL_NOSILU
+__device__ __forceinline__ float silu_f32(float x) { return x; }
+#else
 __device__ __forceinline__ float silu_f32(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+#endif
 
 // Four consecutive features of one weighted per-pair output row: fp32, or bf16 for large batches.
 __device__ __forceinline__ void store_pair_row(const GemmArgs &a, size_t elem, float v0, float v1, float v2, float v3)
@@ -177,13 +181,18 @@ __device__ __forceinline__ void wait_vmcnt()
 // one XCD therefore take a block of group_m M-tiles x all N-tiles: the token slices are shared
 // by the N-tiles and the weight slices by the M-tiles of the same expert while they are
 // still in that XCD's L2 (the XCD-aware analogue of the GROUP_M swizzle, Sec. 4.1 Eq. 4).
-__device__ __forceinline__ void tile_of_workgroup(const GemmArgs &a, int &n_tile, int &m_tile)
+__device__ __forceinline__ void tile_of_id(const GemmArgs &a, int id, int &n_tile, int &m_tile)
 {
-    const int xcd = blockIdx.x & 7, s = blockIdx.x >> 3;
+    const int xcd = id & 7, s = id >> 3;
     const int per_group = a.group_m * a.n_tiles;
     const int gi = s / per_group, r = s - gi * per_group;
     n_tile = r / a.group_m;
     m_tile = (gi * 8 + xcd) * a.group_m + (r - n_tile * a.group_m);
+}
+
+__device__ __forceinline__ void tile_of_workgroup(const GemmArgs &a, int &n_tile, int &m_tile)
+{
+    tile_of_id(a, (int)blockIdx.x, n_tile, m_tile);
 }
 
 // Picks group_m for the launch and returns the (overlaunched) grid size that tile_of_workgroup expects.
@@ -457,8 +466,6 @@ void launch_gemm(int stage, const GemmArgs &a, hipStream_t stream)
         hipLaunchKernelGGL((moe_gemm_kernel<2, BM, BN, BK, WM, WN, NSTAGE, LOOP>), grid, block, 0, stream, g);
 }
 
-constexpr int kModePipe = 0x200;      // config.mode bit: register-pipelined main loop
-constexpr int kModePingPong = 0x400;  // config.mode bit: ping-pong kernel (moe_pingpong.h)
 
 template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int LOOP>
 KernelInfo make_info()

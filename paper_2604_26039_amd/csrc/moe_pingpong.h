@@ -37,7 +37,9 @@ struct PingPongTraits {
     static constexpr int W_BYTES = TT::W_FRAGS * kFragElems * 2;
     static constexpr int TSLOTS = X_BYTES / 1024 / TT::NWAVE;  // token load instructions per wavefront per super-slice
     static constexpr int WSLOTS = TT::W_FRAGS / TT::NWAVE;     // weight load instructions per wavefront per slice
-    static constexpr int LDS_BYTES = NX * X_BYTES + NSTAGE * W_BYTES;
+    static constexpr int RING_BYTES = NX * X_BYTES + NSTAGE * W_BYTES;
+    static constexpr int STG_BYTES = (STAGE == 2) ? 4096 * TT::NWAVE : 0;  // per-wavefront staging of bf16 output rows
+    static constexpr int LDS_BYTES = RING_BYTES + STG_BYTES;
     static_assert(TT::NWAVE == 8, "ping-pong needs two groups of four wavefronts");
     static_assert(BK == 32 || BK == 64, "bk 32 or 64");
     static_assert(BM % 16 == 0 && (X_BYTES / 1024) % TT::NWAVE == 0, "token loads must split evenly");
@@ -84,52 +86,67 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     __shared__ __attribute__((aligned(1024))) char lds[PT::LDS_BYTES];
     char *const lds_x = lds;
     char *const lds_w = lds + NX * PT::X_BYTES;
-
-    int n_tile, m_tile;
-    tile_of_workgroup(a, n_tile, m_tile);
-    if (m_tile >= a.meta[1]) return;  // overlaunched grid: surplus workgroups leave at once
+    char *const lds_stage = lds + PT::RING_BYTES;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int group = wave >> 2;
-    const int e = a.tile_expert[m_tile];
-    const int K = a.K, KST = K / 32;
-    const int f0 = n_tile * FEAT_PER_TILE;
-    const uint16_t *wexp = a.wpacked + (size_t)e * a.expert_stride;
+    const int K = a.K, KST = K / 32, KT = K / BK;
     const int r16 = lane & 15, q = lane >> 4;
+    const int m_tiles = a.meta[1];
 
-    // ---- global element offsets of this lane's loads ----
-    uint32_t xoff[TSLOTS], woff[WSLOTS];
-#pragma unroll
-    for (int t = 0; t < TSLOTS; ++t) {
-        const int blk = wave + t * NWAVE;  // 1 KB block of the super-slice buffer
-        if (PT::ROWX) {
-            const int tr = blk * 8 + (lane >> 3);  // 8 rows per block, 8 lanes (128 B) per row
-            const int pair = a.sorted[m_tile * BM + tr];
-            const uint32_t row = (pair < a.P) ? (uint32_t)(pair / a.topk) : 0u;
-            xoff[t] = row * (uint32_t)K + (uint32_t)(((lane & 7) ^ ((tr >> 1) & 7)) * 8);
-        } else {
-            const int nb = blk / KS, ks = blk % KS;
-            xoff[t] = act_elem((uint32_t)(m_tile * BM + nb * 16 + r16), (uint32_t)(ks * 32 + q * 8), (uint32_t)KST);
+    // Tiles of this workgroup: ids blockIdx.x, + gridDim.x, ... (gridDim.x is a multiple of 8, so every tile of a
+    // workgroup maps to its own XCD); ids past the real M-tiles of this call are skipped.
+    auto next_tile = [&](int id, int &n_tile, int &m_tile) -> int {
+        for (; id < a.total_tiles; id += (int)gridDim.x) {
+            tile_of_id(a, id, n_tile, m_tile);
+            if (m_tile < m_tiles) return id;
         }
-    }
+        return -1;
+    };
+
+    // ---- global element offsets of this lane's loads for k-slice 0 of a tile ----
+    auto tile_offsets = [&](int n_tile, int m_tile, uint32_t *xo, uint32_t *wo, const uint16_t *&wexp) {
+        const int e = a.tile_expert[m_tile];
+        wexp = a.wpacked + (size_t)e * a.expert_stride;
+        const int f0 = n_tile * FEAT_PER_TILE;
 #pragma unroll
-    for (int s = 0; s < WSLOTS; ++s) {
-        const int widx = wave + s * NWAVE;
-        const int rb = widx / KS, ks = widx % KS;
-        uint32_t base;
-        if (STAGE == 1) {
-            const int half = TT::RB / 2;
-            base = (rb < half) ? (uint32_t)(f0 / 16 + rb) * (uint32_t)KST * kFragElems
-                               : (uint32_t)a.up_offset + (uint32_t)(f0 / 16 + rb - half) * (uint32_t)KST * kFragElems;
-        } else {
-            base = (uint32_t)(f0 / 16 + rb) * (uint32_t)KST * kFragElems;
+        for (int t = 0; t < TSLOTS; ++t) {
+            const int blk = wave + t * NWAVE;  // 1 KB block of the token batch buffer
+            if (PT::ROWX) {
+                const int tr = blk * 8 + (lane >> 3);  // 8 rows per block, 8 lanes (128 B) per row
+                const int pair = a.sorted[m_tile * BM + tr];
+                const uint32_t row = (pair < a.P) ? (uint32_t)(pair / a.topk) : 0u;
+                xo[t] = row * (uint32_t)K + (uint32_t)(((lane & 7) ^ ((tr >> 1) & 7)) * 8);
+            } else {
+                const int nb = blk / KS, ks = blk % KS;
+                xo[t] = act_elem((uint32_t)(m_tile * BM + nb * 16 + r16), (uint32_t)(ks * 32 + q * 8), (uint32_t)KST);
+            }
         }
-        woff[s] = base + (uint32_t)ks * kFragElems + (uint32_t)lane * 8;
-    }
+#pragma unroll
+        for (int s = 0; s < WSLOTS; ++s) {
+            const int widx = wave + s * NWAVE;
+            const int rb = widx / KS, ks = widx % KS;
+            uint32_t base;
+            if (STAGE == 1) {
+                const int half = TT::RB / 2;
+                base = (rb < half) ? (uint32_t)(f0 / 16 + rb) * (uint32_t)KST * kFragElems
+                                   : (uint32_t)a.up_offset + (uint32_t)(f0 / 16 + rb - half) * (uint32_t)KST * kFragElems;
+            } else {
+                base = (uint32_t)(f0 / 16 + rb) * (uint32_t)KST * kFragElems;
+            }
+            wo[s] = base + (uint32_t)ks * kFragElems + (uint32_t)lane * 8;
+        }
+    };
     constexpr uint32_t XSTEP = PT::ROWX ? (uint32_t)PT::XK : (uint32_t)(KS * kFragElems);
     constexpr uint32_t WSTEP = (uint32_t)(KS * kFragElems);
+
+    // load stream state: offsets of the next slice to issue (they run ahead of the tile being multiplied)
+    uint32_t xoff[TSLOTS], woff[WSLOTS];
+    const uint16_t *wexp_x = nullptr, *wexp_w = nullptr;  // expert weights of the tile the weight loads belong to
+    uint32_t xoff_n[TSLOTS], woff_n[WSLOTS];               // first slice of the following tile
+    const uint16_t *wexp_n = nullptr;
 
     auto issue_x = [&](int xbuf) {
 #pragma unroll
@@ -141,37 +158,21 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     auto issue_w = [&](int wbuf) {
 #pragma unroll
         for (int s = 0; s < WSLOTS; ++s) {
-            load_to_lds_16B(wexp + woff[s], lds_w + wbuf * PT::W_BYTES + (wave + s * NWAVE) * 1024);
+            load_to_lds_16B(wexp_w + woff[s], lds_w + wbuf * PT::W_BYTES + (wave + s * NWAVE) * 1024);
             woff[s] += WSTEP;
         }
     };
 
     floatx4 acc[NACC][NB];
+    auto zero_acc = [&]() {
 #pragma unroll
-    for (int i = 0; i < NACC; ++i)
+        for (int i = 0; i < NACC; ++i)
 #pragma unroll
-        for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    // token blocks of this wavefront that hold at least one real row (padding sits at the end of a tile)
-    int nb_valid = 0;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-        if (a.sorted[m_tile * BM + (wm * NB + nb) * 16] < a.P) nb_valid = nb + 1;
-    nb_valid = __builtin_amdgcn_readfirstlane(nb_valid);
-
-    int out_pair[NB];
-    float out_wgt[NB];
-    if (STAGE == 2) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int tr = (wm * NB + nb) * 16 + r16;
-            out_pair[nb] = (nb < nb_valid) ? a.sorted[m_tile * BM + tr] : a.P;
-            out_wgt[nb] = (out_pair[nb] < a.P) ? a.topk_w[out_pair[nb]] : 0.0f;
-        }
-    }
+            for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    };
 
     // ---- LDS read offsets of this lane's operand fragments ----
-    // tokens, row-major super-slice: row (wm*NB+nb)*16 + r16 sits in block row/8 at (row%8)*128, chunk c at (c ^ (row/2)%8)*16
+    // tokens, row-major batch: row (wm*NB+nb)*16 + r16 sits in block row/8 at (row%8)*128, chunk c at (c ^ (row/2)%8)*16
     const int xrow_off = (wm * NB * 16 + r16) / 8 * 1024 + (r16 & 7) * 128;
     const int xsw = (r16 >> 1) & 7;
     bf16x8 fx[KS][NB], fw[KS][NACC];
@@ -200,6 +201,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             }
         }
     };
+    int nb_valid = 0;  // token blocks of this wavefront with at least one real row in the current tile
     auto mfma_all = [&]() {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
@@ -217,75 +219,173 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
+    auto count_valid = [&](int m_tile) {
+        int v = 0;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+            if (a.sorted[m_tile * BM + (wm * NB + nb) * 16] < a.P) v = nb + 1;
+        return __builtin_amdgcn_readfirstlane(v);
+    };
 
-    const int KT = K / BK;
-    // Loads are issued, and counted by vmcnt, in this order: prologue X(0) W(0) [X(1)] W(1) ..., then in the M
-    // phase of slice kt: the token batch that became free (if any), then weight slice kt+NSTAGE-1.
+    int n_tile, m_tile;
+    int id = next_tile((int)blockIdx.x, n_tile, m_tile);
+    if (id < 0) return;
+    tile_offsets(n_tile, m_tile, xoff, woff, wexp_w);
+    nb_valid = count_valid(m_tile);
+    zero_acc();
+
+    // The k-slices of all tiles of this workgroup form one stream: the loads run NSTAGE-1 slices ahead of the
+    // multiplication and simply continue with the first slices of the next tile while the current one finishes,
+    // so only the very first tile waits for a cold pipeline.  Loads are issued, and counted by vmcnt, in this
+    // order: prologue X(0) W(0) [X(1)] W(1) ..., then in the M phase of slice kt: the token batch whose buffer
+    // became free (if any), then weight slice kt+NSTAGE-1.
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s) {
-        if ((XS == 1 || s == 0) && s * XS < KT) issue_x(s);
-        if (s < KT) issue_w(s);
+        if (XS == 1 || s == 0) issue_x(s);
+        issue_w(s);
     }
     // token batch 0 and weight slice 0 have landed once only the loads issued after W(0) are outstanding
-    wait_vmcnt_upto(min(NSTAGE - 2, KT - 1) * (XS == 1 ? TSLOTS + WSLOTS : WSLOTS));
+    wait_vmcnt<(NSTAGE - 2) * (XS == 1 ? TSLOTS + WSLOTS : WSLOTS)>();
     phase_barrier();
     if (group == 1) phase_barrier();  // stagger
-    int wbuf_cur = 0, wbuf_issue = NSTAGE - 1;
-    auto slice = [&](int kt, auto steady_c) {
-        constexpr bool STEADY = decltype(steady_c)::value;
-        // ---- M phase: both groups have read slice kt-1 (its buffers are free).  Operand reads first, then the loads:
-        // the reads are what the barrier waits for, the loads only have to be issued.
-        const int par = (XS == 2) ? (kt & 1) : 0;  // position of the slice inside its token batch
-        const int xb = (kt / XS) % NX;
-        read_all(par * KS, xb, wbuf_cur);
-        bool x_issued = false;
-        if (par == 0) {
-            const int j = kt / XS + NX - 1;  // token batch that goes into the buffer freed last
-            if (STEADY || j * XS < KT) {
-                issue_x(j % NX);
-                x_issued = true;
+
+    int wbuf_cur = 0, wbuf_issue = NSTAGE - 1;  // weight ring: buffer of the slice being read / being loaded
+    int xbat_cur = 0;                           // token ring: batch being read (counts over all tiles)
+    while (true) {
+        // following tile of this workgroup (its first slices are loaded while this one finishes)
+        int n_next = 0, m_next = 0;
+        const int id_next = next_tile(id + (int)gridDim.x, n_next, m_next);
+        const bool has_next = id_next >= 0;
+        if (has_next) tile_offsets(n_next, m_next, xoff_n, woff_n, wexp_n);
+        // stage 2: destination pair and router weight of this lane's token rows
+        int out_pair[NB];
+        float out_wgt[NB];
+        if (STAGE == 2) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int tr = (wm * NB + nb) * 16 + r16;
+                out_pair[nb] = (nb < nb_valid) ? a.sorted[m_tile * BM + tr] : a.P;
+                out_wgt[nb] = (out_pair[nb] < a.P) ? a.topk_w[out_pair[nb]] : 0.0f;
             }
         }
-        if (STEADY || kt + NSTAGE - 1 < KT) issue_w(wbuf_issue);
-        // this wavefront's part of slice kt+1 has to be in LDS before the barrier after which the other group reads it
-        if (STEADY) {
-            if (XS == 1) wait_vmcnt<(NSTAGE - 2) * (TSLOTS + WSLOTS)>();
-            else if (par == 0) wait_vmcnt<(NSTAGE - 2) * WSLOTS + (XS == 2 ? TSLOTS : 0)>();
-            else wait_vmcnt<(NSTAGE - 2) * WSLOTS>();
-        } else if (kt + 1 < KT) {
-            const int later = min(NSTAGE - 2, KT - 2 - kt);  // younger weight slices that may stay in flight
-            if (XS == 1) wait_vmcnt_upto(later * (TSLOTS + WSLOTS));
-            else wait_vmcnt_upto(later * WSLOTS + (x_issued ? TSLOTS : 0));
-        }
-        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): fragments in registers, buffers no longer read
-        phase_barrier();
-        // ---- C phase
-        mfma_all();
-        phase_barrier();
-        wbuf_cur = (wbuf_cur + 1 == NSTAGE) ? 0 : wbuf_cur + 1;
-        wbuf_issue = (wbuf_issue + 1 == NSTAGE) ? 0 : wbuf_issue + 1;
-    };
-    // the bulk of the loop: every load of the turn exists and NSTAGE-2 younger weight slices stay in flight; then
-    // the last NSTAGE-1 slices with the conditions evaluated
-    int kt = 0;
-    for (; kt <= KT - NSTAGE; ++kt) slice(kt, std::integral_constant<bool, true>{});
-    for (; kt < KT; ++kt) slice(kt, std::integral_constant<bool, false>{});
-    if (group == 0) phase_barrier();  // both groups execute the same number of barriers
 
-    // ---- epilogue: lane holds features fblock*16 + 4*q + {0..3} of token r16 ----
+        auto slice = [&](int kt, auto steady_c) {
+            constexpr bool STEADY = decltype(steady_c)::value;
+            // ---- M phase: both groups have read slice kt-1 (its buffers are free).  Operand reads first, then the
+            // loads: the reads are what the barrier waits for, the loads only have to be issued.
+            const int par = (XS == 2) ? (kt & 1) : 0;  // position of the slice inside its token batch
+            read_all(par * KS, xbat_cur % NX, wbuf_cur);
+            // the load stream crosses into the next tile NSTAGE-1 slices (one token batch) before this one ends
+            if (kt == KT - NSTAGE + 1) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        if (nb >= nb_valid) continue;
-        const int slot = m_tile * BM + (wm * NB + nb) * 16 + r16;
-        const int rb0 = f0 / 16 + wn * FB;
-        if (STAGE == 1) {
-            store_token_row<1, FB>(a, &acc[0][nb], &acc[FB][nb], NB, (size_t)slot, rb0, q, 1.0f);
+                for (int s = 0; s < WSLOTS; ++s) woff[s] = woff_n[s];
+                wexp_w = wexp_n;
+            }
+            if (kt == KT - (NX - 1) * XS) {
+#pragma unroll
+                for (int t = 0; t < TSLOTS; ++t) xoff[t] = xoff_n[t];
+            }
+            bool x_issued = false;
+            if (par == 0 && (STEADY || kt + (NX - 1) * XS < KT)) {
+                issue_x((xbat_cur + NX - 1) % NX);  // into the buffer freed last
+                x_issued = true;
+            }
+            if (STEADY || kt + NSTAGE - 1 < KT) issue_w(wbuf_issue);
+            // this wavefront's part of the next slice has to be in LDS before the barrier after which the other group reads it
+            if (STEADY) {
+                if (XS == 1) wait_vmcnt<(NSTAGE - 2) * (TSLOTS + WSLOTS)>();
+                else if (par == 0) wait_vmcnt<(NSTAGE - 2) * WSLOTS + (XS == 2 ? TSLOTS : 0)>();
+                else wait_vmcnt<(NSTAGE - 2) * WSLOTS>();
+            } else if (kt + 1 < KT) {
+                const int later = min(NSTAGE - 2, KT - 2 - kt);  // younger weight slices that may stay in flight
+                if (XS == 1) wait_vmcnt_upto(later * (TSLOTS + WSLOTS));
+                else wait_vmcnt_upto(later * WSLOTS + (x_issued ? TSLOTS : 0));
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): fragments in registers, buffers no longer read
+            phase_barrier();
+            // ---- C phase
+            mfma_all();
+            phase_barrier();
+            wbuf_cur = (wbuf_cur + 1 == NSTAGE) ? 0 : wbuf_cur + 1;
+            wbuf_issue = (wbuf_issue + 1 == NSTAGE) ? 0 : wbuf_issue + 1;
+            if (par == XS - 1) ++xbat_cur;
+        };
+        // a tile that is followed by another keeps the load stream full to its end; the last tile of the
+        // workgroup drains it (conditions evaluated for its last NSTAGE-1 slices)
+        int kt = 0;
+        if (has_next) {
+            for (; kt < KT; ++kt) slice(kt, std::integral_constant<bool, true>{});
         } else {
-            const int pair = out_pair[nb];
-            if (pair >= a.P) continue;
-            store_token_row<2, FB>(a, &acc[0][nb], &acc[0][nb], NB, (size_t)pair * a.F, rb0, q, out_wgt[nb]);
+            for (; kt <= KT - NSTAGE; ++kt) slice(kt, std::integral_constant<bool, true>{});
+            for (; kt < KT; ++kt) slice(kt, std::integral_constant<bool, false>{});
         }
+
+        // ---- epilogue: lane holds features fblock*16 + 4*q + {0..3} of token r16.  It runs while the other group
+        // is in a C phase; the stores are not waited for here.
+        const int f0 = n_tile * FEAT_PER_TILE;
+#ifdef RAMP_ABL_NOSTORE
+        const bool abl_skip = acc[0][0][0] != 12345.678f;
+#else
+        const bool abl_skip = false;
+#endif
+        if (STAGE == 2 && a.y_bf16) {
+            // bf16 per-pair rows leave through LDS: a lane holds 16 consecutive features of one token, but a store
+            // instruction should cover whole 128-byte lines.  Per chunk of two token blocks the wavefront writes its
+            // 32 x 64 weighted results into its own 4 KB staging area (row-major, 16-byte chunk index XOR-ed with
+            // (row/2)%8 so writes and reads spread over all banks) and reads them back 8 rows x 128 B at a time.
+            static_assert(STAGE != 2 || (FB == 4 && NB % 2 == 0), "staged epilogue: 64 features per wavefront, token blocks in pairs");
+            char *stg = lds_stage + wave * 4096;
+            uint16_t *ybase = reinterpret_cast<uint16_t *>(a.y_out) + f0 + wn * (FB * 16) + (lane & 7) * 8;
+#pragma unroll
+            for (int c2 = 0; c2 < NB / 2; ++c2) {
+                if (2 * c2 >= nb_valid || abl_skip) continue;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int nb = 2 * c2 + h;
+                    const int row = h * 16 + r16;
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {  // row blocks (0,1) and (2,3): 8 features each pair
+                        float w8[8];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            w8[c] = out_wgt[nb] * acc[2 * half][nb][c];
+                            w8[4 + c] = out_wgt[nb] * acc[2 * half + 1][nb][c];
+                        }
+                        store_bf16x8(reinterpret_cast<uint16_t *>(stg + row * 128 + (((2 * q + half) ^ ((row >> 1) & 7)) * 16)), w8);
+                    }
+                }
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const int row = p * 8 + (lane >> 3);
+                    const int nb = 2 * c2 + (p >> 1);
+                    const int pair = __shfl(out_pair[nb], row & 15);
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * 128 + (((lane & 7) ^ ((row >> 1) & 7)) * 16));
+                    if (pair < a.P) *reinterpret_cast<uint4 *>(ybase + (size_t)pair * a.F) = v;
+                }
+            }
+        } else {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            if (nb >= nb_valid || abl_skip) continue;
+            const int slot = m_tile * BM + (wm * NB + nb) * 16 + r16;
+            const int rb0 = f0 / 16 + wn * FB;
+            if (STAGE == 1) {
+                store_token_row<1, FB>(a, &acc[0][nb], &acc[FB][nb], NB, (size_t)slot, rb0, q, 1.0f);
+            } else {
+                const int pair = out_pair[nb];
+                if (pair >= a.P) continue;
+                store_token_row<2, FB>(a, &acc[0][nb], &acc[0][nb], NB, (size_t)pair * a.F, rb0, q, out_wgt[nb]);
+            }
+        }
+        }
+        if (!has_next) break;
+        id = id_next;
+        n_tile = n_next;
+        m_tile = m_next;
+        nb_valid = count_valid(m_tile);
+        zero_acc();
     }
+    if (group == 0) phase_barrier();  // both groups execute the same number of barriers
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int NSTAGE>
@@ -293,7 +393,9 @@ void launch_pingpong(int stage, const GemmArgs &a, hipStream_t stream)
 {
     if (a.n_tiles <= 0 || a.m_tiles_cap <= 0) return;
     GemmArgs g = a;
-    const dim3 grid(xcd_grid(g)), block(512);
+    g.total_tiles = (int)xcd_grid(g);
+    // persistent: one workgroup per compute unit walks its share of the tiles (the count is a multiple of 8)
+    const dim3 grid(g.total_tiles < kNumCU ? g.total_tiles : kNumCU), block(512);
     if (stage == 1)
         hipLaunchKernelGGL((moe_pingpong_kernel<1, BM, BN, BK, WM, WN, NSTAGE>), grid, block, 0, stream, g);
     else

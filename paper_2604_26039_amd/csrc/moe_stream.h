@@ -184,7 +184,6 @@ void launch_stream(int stage, const GemmArgs &a, hipStream_t stream)
         hipLaunchKernelGGL((moe_stream_kernel<2, BM, FBW, WF, WK, U>), grid, block, 0, stream, a);
 }
 
-constexpr int kModeStream = 0x100;  // config.mode = kModeStream | WK
 
 template <int BM, int FBW, int WF, int WK, int U>
 KernelInfo make_stream_info()

@@ -46,7 +46,7 @@ constexpr int kFragElems = 512;
 // 4 consecutive features per row block it owns, consecutive row blocks continuing the run: a lane
 // that owns all 8 row blocks of a group stores 32 consecutive features (64 B of bf16) per token
 // instead of 8 separate 8-byte pieces.  Pure relabelling: the packing kernel and the epilogues agree.
-constexpr int kPermBlocks = 8;
+constexpr int kPermBlocks = 4;
 __host__ __device__ inline int packed_row_feature(int rb, int r)
 {
     return (rb / kPermBlocks) * (16 * kPermBlocks) + (r >> 2) * (4 * kPermBlocks) + (rb % kPermBlocks) * 4 + (r & 3);
@@ -90,7 +90,13 @@ struct GemmArgs {
     int n_tiles;                // feature tiles of this stage
     int m_tiles_cap;            // launched M-tiles (upper bound)
     int group_m;                // M-tiles per XCD block of the workgroup->tile map (set by the launcher)
+    int total_tiles;            // persistent kernels: tile ids to walk (set by the launcher)
 };
+
+// ramp_config.mode: bits 0-7 = WM-1 (token split of the wavefront grid), then the kernel family
+constexpr int kModeStream = 0x100;    // weight-streaming kernel (moe_stream.h); bits 0-7 = WK instead
+constexpr int kModePipe = 0x200;      // LDS-staged kernel with the register-pipelined main loop (moe_gemm.h)
+constexpr int kModePingPong = 0x400;  // persistent ping-pong kernel (moe_pingpong.h)
 
 struct KernelInfo {
     ramp_config cfg;
