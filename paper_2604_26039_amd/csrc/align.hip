@@ -59,7 +59,7 @@ __device__ void block_histogram(const int32_t *ids, int begin, int end, int E, i
 // From n_e (one expert per lane, 0 beyond E): slot offsets toff[0..E] in LDS, counts / meta /
 // tile_expert in global memory.  Called by all NT lanes; E <= NT.
 __device__ void block_scan_and_emit(int n_e, int E, int bm, int cap, int dropped_total, int *toff, int *wsum,
-                                    int32_t *counts, int32_t *meta, int32_t *tile_expert)
+                                    int32_t *counts, int32_t *meta, int32_t *tile_expert, int32_t *tile_rows)
 {
     const int e = threadIdx.x;
     int slots = (e < E) ? (n_e + bm - 1) / bm * bm : 0;
@@ -90,6 +90,15 @@ __device__ void block_scan_and_emit(int n_e, int E, int bm, int cap, int dropped
             owner = lo;
         }
         tile_expert[m] = owner;
+        // real rows of the tile (the rest of its bm slots is sentinel padding); optional, for the projection kernels
+        if (tile_rows) {
+            int rows = 0;
+            if (owner >= 0) {
+                rows = counts[owner] - (m * bm - toff[owner]);  // counts[] was written before the barrier above
+                rows = rows > bm ? bm : rows;
+            }
+            tile_rows[m] = rows;
+        }
     }
 }
 
@@ -157,8 +166,8 @@ size_t lds_ints(int E) { return (size_t)E + (E + 1) + NW + 1 + (size_t)NW * E; }
 
 // ---- single workgroup: everything in one launch ----
 __global__ __launch_bounds__(NT) void align_single_kernel(const int32_t *ids, int P, int E, int bm, int cap,
-                                                          int32_t *sorted, int32_t *tile_expert, int32_t *counts,
-                                                          int32_t *meta, int scatter)
+                                                          int32_t *sorted, int32_t *tile_expert, int32_t *tile_rows,
+                                                          int32_t *counts, int32_t *meta, int scatter)
 {
     extern __shared__ int lds[];
     int *hist, *toff, *wsum, *misc;
@@ -178,7 +187,7 @@ __global__ __launch_bounds__(NT) void align_single_kernel(const int32_t *ids, in
     }
     int n_e = ((int)threadIdx.x < E) ? hist[threadIdx.x] : 0;
     int dropped = misc[0];
-    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, counts, meta, tile_expert);
+    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, counts, meta, tile_expert, tile_rows);
     __syncthreads();
     int *cursor = hist;  // histogram no longer needed
     for (int x = threadIdx.x; x < E; x += NT) cursor[x] = toff[x];
@@ -209,8 +218,8 @@ __global__ __launch_bounds__(NT) void align_hist_kernel(const int32_t *ids, int 
 
 __global__ __launch_bounds__(NT) void align_scan_kernel(int B, int E, int bm, int cap, const int32_t *block_counts,
                                                         const int32_t *block_dropped, int32_t *block_base,
-                                                        int32_t *tile_expert, int32_t *counts, int32_t *meta,
-                                                        int scatter)
+                                                        int32_t *tile_expert, int32_t *tile_rows, int32_t *counts,
+                                                        int32_t *meta, int scatter)
 {
     extern __shared__ int lds[];
     int *toff = lds, *wsum = lds + E + 1;
@@ -227,7 +236,7 @@ __global__ __launch_bounds__(NT) void align_scan_kernel(int B, int E, int bm, in
     int dropped = 0;
 #pragma unroll 8
     for (int b = 0; b < B; ++b) dropped += block_dropped[b];
-    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, counts, meta, tile_expert);
+    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, counts, meta, tile_expert, tile_rows);
     __syncthreads();
     if (e < E) {
         int run = toff[e];
@@ -275,8 +284,8 @@ int allow_lds(Kernel kernel, size_t bytes)
 
 // scatter = 0: histogram only (sorted / tile_expert / meta untouched, may be NULL)
 static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
-                             int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream,
-                             int scatter)
+                             int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes,
+                             hipStream_t stream, int scatter)
 {
     if (T < 0 || k < 0 || E <= 0 || E > kAlignMaxE || bm < 1 || bm > 1024) {
         set_error("align: bad sizes T=%d k=%d E=%d bm=%d (need E<=%d, 1<=bm<=1024)", T, k, E, bm, kAlignMaxE);
@@ -297,7 +306,7 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
         size_t lds = lds_ints(E) * sizeof(int);
         if (int rc = allow_lds(align_single_kernel, lds)) return rc;
         hipLaunchKernelGGL(align_single_kernel, dim3(1), dim3(NT), lds, stream, ids, P, E, bm, cap, sorted,
-                           tile_expert, counts, meta, scatter);
+                           tile_expert, tile_rows, counts, meta, scatter);
         return check_launch("align_single_kernel");
     }
     const int B = num_blocks(P);
@@ -314,7 +323,7 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
     int rc = check_launch("align_hist_kernel");
     if (rc) return rc;
     hipLaunchKernelGGL(align_scan_kernel, dim3(1), dim3(NT), (E + 1 + NW) * sizeof(int), stream, B, E, bm, cap,
-                       block_counts, block_dropped, block_base, tile_expert, counts, meta, scatter);
+                       block_counts, block_dropped, block_base, tile_expert, tile_rows, counts, meta, scatter);
     rc = check_launch("align_scan_kernel");
     if (rc || !scatter) return rc;
     const size_t scatter_lds = ((size_t)E + (size_t)NW * E) * sizeof(int);
@@ -324,9 +333,9 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
 }
 
 int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
-                 int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream)
+                 int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream)
 {
-    return launch_align_impl(ids, T, k, E, bm, sorted, tile_expert, counts, meta, ws, ws_bytes, stream, 1);
+    return launch_align_impl(ids, T, k, E, bm, sorted, tile_expert, tile_rows, counts, meta, ws, ws_bytes, stream, 1);
 }
 
 }  // namespace ramp
@@ -351,7 +360,7 @@ extern "C" size_t ramp_align_workspace_bytes(int T, int k, int E)
 extern "C" int ramp_moe_histogram(const int32_t *topk_ids, int T, int k, int E, int32_t *expert_counts, void *ws,
                                   size_t ws_bytes, void *stream)
 {
-    return ramp::launch_align_impl(topk_ids, T, k, E, 1, nullptr, nullptr, expert_counts, nullptr, ws, ws_bytes,
+    return ramp::launch_align_impl(topk_ids, T, k, E, 1, nullptr, nullptr, nullptr, expert_counts, nullptr, ws, ws_bytes,
                                    static_cast<hipStream_t>(stream), 0);
 }
 
@@ -359,6 +368,6 @@ extern "C" int ramp_moe_align(const int32_t *topk_ids, int T, int k, int E, int 
                               int32_t *tile_expert, int32_t *expert_counts, int32_t *meta, void *ws, size_t ws_bytes,
                               void *stream)
 {
-    return ramp::launch_align(topk_ids, T, k, E, bm, sorted_pair_ids, tile_expert, expert_counts, meta, ws, ws_bytes,
+    return ramp::launch_align(topk_ids, T, k, E, bm, sorted_pair_ids, tile_expert, nullptr, expert_counts, meta, ws, ws_bytes,
                               static_cast<hipStream_t>(stream));
 }

@@ -119,7 +119,7 @@ struct ProbeScope {
 constexpr size_t kPairRowsBf16Elems = (size_t)8 << 20;
 
 struct Workspace {
-    size_t sorted, tile_expert, counts, meta, align_ws, a_buf, y_buf, total;
+    size_t sorted, tile_expert, tile_rows, counts, meta, align_ws, a_buf, y_buf, total;
     size_t cap, align_ws_bytes;
 };
 
@@ -135,6 +135,7 @@ Workspace workspace_layout(const ramp_shape &s, const ramp_config &c)
     };
     w.sorted = take(w.cap * 4);
     w.tile_expert = take((w.cap / (size_t)c.bm) * 4);
+    w.tile_rows = take((w.cap / (size_t)c.bm) * 4);
     w.counts = take((size_t)s.E * 4);
     w.meta = take(16);
     w.align_ws_bytes = ramp_align_workspace_bytes(s.T, s.k, s.E);
@@ -338,6 +339,7 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     char *base = static_cast<char *>(ws);
     int32_t *sorted = reinterpret_cast<int32_t *>(base + w.sorted);
     int32_t *tile_expert = reinterpret_cast<int32_t *>(base + w.tile_expert);
+    int32_t *tile_rows = reinterpret_cast<int32_t *>(base + w.tile_rows);
     int32_t *counts = reinterpret_cast<int32_t *>(base + w.counts);
     int32_t *meta = reinterpret_cast<int32_t *>(base + w.meta);
     uint16_t *a_buf = reinterpret_cast<uint16_t *>(base + w.a_buf);
@@ -346,7 +348,7 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     int rc;
     {
         ProbeScope probe(1, st);
-        rc = launch_align(topk_ids, s.T, s.k, s.E, cfg->bm, sorted, tile_expert, counts, meta, base + w.align_ws,
+        rc = launch_align(topk_ids, s.T, s.k, s.E, cfg->bm, sorted, tile_expert, tile_rows, counts, meta, base + w.align_ws,
                           w.align_ws_bytes, st);
     }
     if (rc) return rc;
@@ -356,6 +358,8 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     GemmArgs g = {};
     g.sorted = sorted;
     g.tile_expert = tile_expert;
+    g.tile_rows = tile_rows;
+    g.topk_magic = ((1ull << 40) + (unsigned long long)s.k - 1) / (unsigned long long)s.k;
     g.meta = meta;
     g.topk_w = topk_w;
     g.a_out = a_buf;

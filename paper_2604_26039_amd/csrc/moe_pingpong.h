@@ -107,19 +107,27 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     };
 
     // ---- global element offsets of this lane's loads for k-slice 0 of a tile ----
-    auto tile_offsets = [&](int n_tile, int m_tile, uint32_t *xo, uint32_t *wo, const uint16_t *&wexp) {
+    auto tile_offsets = [&](int n_tile, int m_tile, uint32_t *xo, uint32_t *wo, const uint16_t *&wexp, int &rows) {
+        rows = a.tile_rows[m_tile];  // real rows of the tile (they come first, the sentinel padding after them)
         const int e = a.tile_expert[m_tile];
         wexp = a.wpacked + (size_t)e * a.expert_stride;
         const int f0 = n_tile * FEAT_PER_TILE;
+        if (PT::ROWX) {
+            // all index loads first, then the arithmetic (token = pair / k by multiplication)
+            int pair[TSLOTS];
 #pragma unroll
-        for (int t = 0; t < TSLOTS; ++t) {
-            const int blk = wave + t * NWAVE;  // 1 KB block of the token batch buffer
-            if (PT::ROWX) {
-                const int tr = blk * 8 + (lane >> 3);  // 8 rows per block, 8 lanes (128 B) per row
-                const int pair = a.sorted[m_tile * BM + tr];
-                const uint32_t row = (pair < a.P) ? (uint32_t)(pair / a.topk) : 0u;
+            for (int t = 0; t < TSLOTS; ++t) pair[t] = a.sorted[m_tile * BM + (wave + t * NWAVE) * 8 + (lane >> 3)];
+#pragma unroll
+            for (int t = 0; t < TSLOTS; ++t) {
+                const int tr = (wave + t * NWAVE) * 8 + (lane >> 3);  // 8 rows per 1 KB block, 8 lanes (128 B) per row
+                const uint32_t p = (pair[t] < a.P) ? (uint32_t)pair[t] : 0u;
+                const uint32_t row = (uint32_t)(((unsigned long long)p * a.topk_magic) >> 40);
                 xo[t] = row * (uint32_t)K + (uint32_t)(((lane & 7) ^ ((tr >> 1) & 7)) * 8);
-            } else {
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < TSLOTS; ++t) {
+                const int blk = wave + t * NWAVE;
                 const int nb = blk / KS, ks = blk % KS;
                 xo[t] = act_elem((uint32_t)(m_tile * BM + nb * 16 + r16), (uint32_t)(ks * 32 + q * 8), (uint32_t)KST);
             }
@@ -147,11 +155,22 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     const uint16_t *wexp_x = nullptr, *wexp_w = nullptr;  // expert weights of the tile the weight loads belong to
     uint32_t xoff_n[TSLOTS], woff_n[WSLOTS];               // first slice of the following tile
     const uint16_t *wexp_n = nullptr;
+    // Token loads of all-padding row blocks are degenerate (a ragged last tile of an expert then costs little more
+    // than its weights): only the first txv of this wavefront's TSLOTS token loads per batch fetch rows.
+    int txv = TSLOTS, txv_n = TSLOTS;
+    auto token_loads = [&](int rows) {
+        const int blocks = PT::ROWX ? (rows + 7) / 8 : (rows + 15) / 16 * KS;  // 1 KB load blocks that hold real rows
+        int v = (blocks - wave + NWAVE - 1) / NWAVE;
+        return v < 0 ? 0 : (v > TSLOTS ? TSLOTS : v);
+    };
 
     auto issue_x = [&](int xbuf) {
 #pragma unroll
         for (int t = 0; t < TSLOTS; ++t) {
-            load_to_lds_16B(a.act + xoff[t], lds_x + xbuf * PT::X_BYTES + (wave + t * NWAVE) * 1024);
+            // a block of nothing but padding rows re-reads one 16-byte piece instead (one cache line request, and
+            // the load count that the vmcnt waits rely on stays the same)
+            const uint32_t off = (t < txv) ? xoff[t] : 0u;
+            load_to_lds_16B(a.act + off, lds_x + xbuf * PT::X_BYTES + (wave + t * NWAVE) * 1024);
             xoff[t] += XSTEP;
         }
     };
@@ -176,6 +195,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     const int xrow_off = (wm * NB * 16 + r16) / 8 * 1024 + (r16 & 7) * 128;
     const int xsw = (r16 >> 1) & 7;
     bf16x8 fx[KS][NB], fw[KS][NACC];
+    int nb_valid = 0;  // token blocks of this wavefront with at least one real row in the current tile
     auto read_all = [&](int kk0, int xbuf, int wbuf) {  // kk0: 32-wide k-step of the slice inside its token batch
         const char *xs = lds_x + xbuf * PT::X_BYTES;
         const char *ws = lds_w + wbuf * PT::W_BYTES + lane * 16;
@@ -201,13 +221,16 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             }
         }
     };
-    int nb_valid = 0;  // token blocks of this wavefront with at least one real row in the current tile
-    auto mfma_all = [&]() {
+    // FULL: every token block of the wavefront is real (no branches between the MFMAs); otherwise the products of
+    // all-padding blocks are skipped.  The operand reads stay unconditional: branches between them cost more than
+    // the reads they save.
+    auto mfma_all = [&](auto full_c) {
+        constexpr bool FULL = decltype(full_c)::value;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                if (nb < nb_valid) {
+                if (FULL || nb < nb_valid) {
 #pragma unroll
                     for (int i = 0; i < NACC; ++i)
                         acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][i], fx[ks][nb], acc[i][nb], 0, 0, 0);
@@ -219,19 +242,18 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto count_valid = [&](int m_tile) {
-        int v = 0;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-            if (a.sorted[m_tile * BM + (wm * NB + nb) * 16] < a.P) v = nb + 1;
-        return __builtin_amdgcn_readfirstlane(v);
+    auto blocks_valid = [&](int rows) {  // token blocks of this wavefront that hold at least one real row
+        const int v = (rows - wm * NB * 16 + 15) / 16;
+        return v < 0 ? 0 : (v > NB ? NB : v);
     };
 
     int n_tile, m_tile;
     int id = next_tile((int)blockIdx.x, n_tile, m_tile);
     if (id < 0) return;
-    tile_offsets(n_tile, m_tile, xoff, woff, wexp_w);
-    nb_valid = count_valid(m_tile);
+    int rows_cur = 0, rows_next = 0;
+    tile_offsets(n_tile, m_tile, xoff, woff, wexp_w, rows_cur);
+    nb_valid = blocks_valid(rows_cur);
+    txv = token_loads(rows_cur);
     zero_acc();
 
     // The k-slices of all tiles of this workgroup form one stream: the loads run NSTAGE-1 slices ahead of the
@@ -256,7 +278,10 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         int n_next = 0, m_next = 0;
         const int id_next = next_tile(id + (int)gridDim.x, n_next, m_next);
         const bool has_next = id_next >= 0;
-        if (has_next) tile_offsets(n_next, m_next, xoff_n, woff_n, wexp_n);
+        if (has_next) {
+            tile_offsets(n_next, m_next, xoff_n, woff_n, wexp_n, rows_next);
+            txv_n = token_loads(rows_next);
+        }
         // stage 2: destination pair and router weight of this lane's token rows
         int out_pair[NB];
         float out_wgt[NB];
@@ -269,7 +294,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             }
         }
 
-        auto slice = [&](int kt, auto steady_c) {
+        auto slice = [&](int kt, auto steady_c, auto full_c) {
             constexpr bool STEADY = decltype(steady_c)::value;
             // ---- M phase: both groups have read slice kt-1 (its buffers are free).  Operand reads first, then the
             // loads: the reads are what the barrier waits for, the loads only have to be issued.
@@ -284,6 +309,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             if (kt == KT - (NX - 1) * XS) {
 #pragma unroll
                 for (int t = 0; t < TSLOTS; ++t) xoff[t] = xoff_n[t];
+                txv = txv_n;
             }
             bool x_issued = false;
             if (par == 0 && (STEADY || kt + (NX - 1) * XS < KT)) {
@@ -304,7 +330,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): fragments in registers, buffers no longer read
             phase_barrier();
             // ---- C phase
-            mfma_all();
+            mfma_all(full_c);
             phase_barrier();
             wbuf_cur = (wbuf_cur + 1 == NSTAGE) ? 0 : wbuf_cur + 1;
             wbuf_issue = (wbuf_issue + 1 == NSTAGE) ? 0 : wbuf_issue + 1;
@@ -312,13 +338,16 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         };
         // a tile that is followed by another keeps the load stream full to its end; the last tile of the
         // workgroup drains it (conditions evaluated for its last NSTAGE-1 slices)
+        using True = std::integral_constant<bool, true>;
+        using False = std::integral_constant<bool, false>;
         int kt = 0;
-        if (has_next) {
-            for (; kt < KT; ++kt) slice(kt, std::integral_constant<bool, true>{});
+        const int kt_steady = has_next ? KT : KT - NSTAGE + 1;
+        if (nb_valid == NB) {
+            for (; kt < kt_steady; ++kt) slice(kt, True{}, True{});
         } else {
-            for (; kt <= KT - NSTAGE; ++kt) slice(kt, std::integral_constant<bool, true>{});
-            for (; kt < KT; ++kt) slice(kt, std::integral_constant<bool, false>{});
+            for (; kt < kt_steady; ++kt) slice(kt, True{}, False{});
         }
+        for (; kt < KT; ++kt) slice(kt, False{}, False{});
 
         // ---- epilogue: lane holds features fblock*16 + 4*q + {0..3} of token r16.  It runs while the other group
         // is in a C phase; the stores are not waited for here.
@@ -382,7 +411,8 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         id = id_next;
         n_tile = n_next;
         m_tile = m_next;
-        nb_valid = count_valid(m_tile);
+        rows_cur = rows_next;
+        nb_valid = blocks_valid(rows_cur);
         zero_acc();
     }
     if (group == 0) phase_barrier();  // both groups execute the same number of barriers

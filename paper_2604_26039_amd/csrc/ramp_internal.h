@@ -35,7 +35,7 @@ constexpr int kAlignSingleMaxP = 2048; // up to this many pairs one workgroup do
 constexpr int kAlignMaxE = 1024;
 
 int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
-                 int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream);
+                 int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream);
 
 // ---- packed weights ----
 // One fragment = 16 weight rows x 32 k-values = 512 bf16 = 1 KB, stored in the lane order
@@ -78,6 +78,8 @@ struct GemmArgs {
     size_t up_offset;           // stage 1: offset of the up rows inside an expert
     const int32_t *sorted;      // [cap]
     const int32_t *tile_expert; // [cap/bm]
+    const int32_t *tile_rows;   // [cap/bm] real rows per tile
+    unsigned long long topk_magic;  // ceil(2^40 / k): pair / k == (pair * topk_magic) >> 40 for pair < 2^30
     const int32_t *meta;        // [4]
     const float *topk_w;        // stage 2: [P]
     uint16_t *a_out;            // stage 1: A [cap,I]
