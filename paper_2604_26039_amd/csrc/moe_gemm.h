@@ -176,18 +176,22 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-// Workgroup -> tile.  Workgroups are handed to the 8 XCDs round robin (id % 8), each XCD has
-// its own 4 MB L2 and runs 32 workgroups of the large tiles at a time.  Consecutive workgroups of
-// one XCD therefore take a block of group_m M-tiles x all N-tiles: the token slices are shared
-// by the N-tiles and the weight slices by the M-tiles of the same expert while they are
-// still in that XCD's L2 (the XCD-aware analogue of the GROUP_M swizzle, Sec. 4.1 Eq. 4).
+// Workgroup -> tile.  Workgroups are handed to the 8 XCDs round robin (id % 8), each XCD has its own
+// 4 MB L2 and runs 32 workgroups of the large tiles at a time.  Consecutive workgroups of one XCD
+// therefore take a block of group_m M-tiles x group_n N-tiles: the token slices are shared by the
+// N-tiles of the block and the weight slices by its M-tiles (same expert, mostly) while they are
+// still in that XCD's L2 (the XCD-aware analogue of the GROUP_M swizzle, Sec. 4.1 Eq. 4).  Blocks
+// walk the N dimension first, then the next group of M-tiles.
 __device__ __forceinline__ void tile_of_id(const GemmArgs &a, int id, int &n_tile, int &m_tile)
 {
     const int xcd = id & 7, s = id >> 3;
-    const int per_group = a.group_m * a.n_tiles;
-    const int gi = s / per_group, r = s - gi * per_group;
-    n_tile = r / a.group_m;
-    m_tile = (gi * 8 + xcd) * a.group_m + (r - n_tile * a.group_m);
+    const int per_block = a.group_m * a.group_n;
+    const int sb = s / per_block, w = s - sb * per_block;
+    const int dn = w / a.group_m, dm = w - dn * a.group_m;
+    const int nbn = a.n_tiles / a.group_n;
+    const int mb = sb / nbn, nbi = sb - mb * nbn;
+    n_tile = nbi * a.group_n + dn;
+    m_tile = (mb * 8 + xcd) * a.group_m + dm;
 }
 
 __device__ __forceinline__ void tile_of_workgroup(const GemmArgs &a, int &n_tile, int &m_tile)
@@ -195,10 +199,15 @@ __device__ __forceinline__ void tile_of_workgroup(const GemmArgs &a, int &n_tile
     tile_of_id(a, (int)blockIdx.x, n_tile, m_tile);
 }
 
-// Picks group_m for the launch and returns the (overlaunched) grid size that tile_of_workgroup expects.
+// Picks the block shape for the launch and returns the (overlaunched) number of tile ids that tile_of_id expects.
 inline unsigned xcd_grid(GemmArgs &g)
 {
-    // 32 workgroups of an XCD run together: group_m M-tiles x n_tiles N-tiles of them share operands
+    // A block spans all N-tiles: the token rows of its few M-tiles (group_m * bm * K * 2 bytes) then stay in the
+    // 4 MB L2 across the whole walk over N, which matters more than sharing weight slices inside one XCD
+    // (measured: wider M groups with narrower N groups are up to 1.5x slower when K and the N extent are large);
+    // the 8 XCDs work on neighbouring M-tiles, i.e. mostly the same expert, and share its weights through the
+    // memory-side cache.
+    g.group_n = g.n_tiles;
     g.group_m = 32 / g.n_tiles;
     if (g.group_m < 1) g.group_m = 1;
     if (g.group_m > 8) g.group_m = 8;

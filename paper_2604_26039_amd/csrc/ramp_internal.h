@@ -91,7 +91,7 @@ struct GemmArgs {
     int topk;                   // k
     int n_tiles;                // feature tiles of this stage
     int m_tiles_cap;            // launched M-tiles (upper bound)
-    int group_m;                // M-tiles per XCD block of the workgroup->tile map (set by the launcher)
+    int group_m, group_n;       // M-tiles x N-tiles per XCD block of the workgroup->tile map (set by the launcher)
     int total_tiles;            // persistent kernels: tile ids to walk (set by the launcher)
 };
 
