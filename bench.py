@@ -276,7 +276,7 @@ def main():
     else:
         roof = dict(bound="hbm", achieved=k_bytes / k_us * 1e-3, peak=HBM_PEAK_TBS * 1e3, unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof.update(traffic=MEASURED_TRAFFIC_BYTES.get((args.model, T_head, str(beta_head))), kernel="moe_gemm_kernel<1> (up-projection + SwiGLU)", kernel_us=k_us, launches=probe_n,
+    roof.update(traffic=MEASURED_TRAFFIC_BYTES.get((args.model, T_head, str(beta_head))), kernel=("moe_pingpong_kernel<1>" if cfg_head.mode & 0x400 else "moe_stream_kernel<1>" if cfg_head.mode & 0x100 else "moe_gemm_kernel<1>") + " (up-projection + SwiGLU)", kernel_us=k_us, launches=probe_n,
                 algorithmic_flops=k_flops, algorithmic_bytes=k_bytes)
     t_hbm, t_mfma, nbytes, flops = tuner.roofline_lower_bound_us(s, T_head, p.counts, HBM_PEAK_TBS, MFMA_PEAK_PFLOPS)
     whole = dict(bound="hbm" if t_hbm >= t_mfma else "mfma", lower_bound_us=max(t_hbm, t_mfma),

@@ -136,30 +136,38 @@ int ramp_fused_moe_workspace_layout(const ramp_shape *shape, const ramp_config *
                                     size_t offsets[4]);
 
 /* ---- cost model (Eq. 6, Sec. 4.2) -----------------------------------------------------------
- * T_hat(c) = a + b*g/W + c*m + d*ln(g+1),  g = (sum_e ceil(n_e/bm_c)) * ntiles_c.
- * flags = 0 is the paper's model as printed: m = g, ordinary least squares.
+ * T_hat(c) = a + b*w + c*m + d*l,  g = (sum_e ceil(n_e/bm_c)) * ntiles_c.
+ * flags = 0 is the paper's model as printed: w = g/W, m = g, l = ln(g+1), ordinary least squares.
  * RAMP_CM_DISTINCT_TILES: the per-block memory-traffic term counts the distinct weight tiles
  *   m = u = #{e: n_e > 0} * ntiles_c instead of all blocks.  On this chip a weight tile that a
  *   second M-tile of the same expert re-reads comes out of L2 / the 256 MB last-level cache,
  *   so HBM traffic scales with u, not g.  It also makes the four columns independent.
  * RAMP_CM_RELATIVE: least squares on relative residuals (each profiling row scaled by
  *   1/t_i), because dispatch only needs the ratio between configurations and the profiled
- *   times span three decades. */
-enum { RAMP_CM_EQ6 = 0, RAMP_CM_RELATIVE = 1, RAMP_CM_DISTINCT_TILES = 2 };
+ *   times span three decades.
+ * RAMP_CM_WAVE_FLOOR: the wave term is w = max(g/W, 1): a grid that does not fill the chip still
+ *   takes the time of one wave of its blocks (the sub-wave regime of Sec. 4.1), which the kernels
+ *   here show as a plateau rather than a logarithm.
+ * RAMP_CM_PAIRS: the fourth term is l = P = sum_e n_e, the routed pairs, in place of ln(g+1) and
+ *   always fitted: gather, SwiGLU, per-pair rows and the combine cost time per pair whatever the
+ *   tiling, which g (padded tiles) does not separate from the padding. */
+enum { RAMP_CM_EQ6 = 0, RAMP_CM_RELATIVE = 1, RAMP_CM_DISTINCT_TILES = 2, RAMP_CM_WAVE_FLOOR = 4, RAMP_CM_PAIRS = 8 };
 
 /* Least-squares fit per configuration from profiling (Sec. 4.2 "Fitting").
  * grid, time_us (and distinct, required with RAMP_CM_DISTINCT_TILES, else may be NULL) are
- * host arrays [n_cfg, n_pts]; wave_cap host [n_cfg].
+ * host arrays [n_cfg, n_pts]; wave_cap host [n_cfg]; pairs (required with RAMP_CM_PAIRS, else may
+ * be NULL) host [n_pts], the routed pairs of each profiling point.
  * The log column is used only when the lower median of a configuration's profiling
  * grids is below its wave capacity.  With m = g the columns g/W and g are proportional:
  * the minimum-norm least-squares solution is returned, predictions do not depend on
  * that choice.  theta: host out [n_cfg,4] = a,b,c,d. */
 int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
-                        const int64_t *distinct, const double *time_us, int flags, float *theta);
+                        const int64_t *distinct, const int64_t *pairs, const double *time_us, int flags,
+                        float *theta);
 
 /* Evaluate the model for every configuration on one histogram (host [E]) and return the
  * lowest index with the smallest prediction in *best_idx (Sec. 4.2 "Runtime
- * dispatch").  flags: RAMP_CM_DISTINCT_TILES must match the fit.
+ * dispatch").  flags: the column choices (all but RAMP_CM_RELATIVE) must match the fit.
  * pred_us: optional host out [n_cfg] (fp64 evaluation). */
 int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
                            const int32_t *wave_cap, const float *theta,

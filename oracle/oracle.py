@@ -211,26 +211,35 @@ def predict(theta4, g: int, wave_cap: int) -> float:
     return float(_load().oracle_predict(_ptr(th, ctypes.c_float), int(g), int(wave_cap)))
 
 
-def select(bm, ntiles, wave_cap, theta, counts, distinct_tiles: bool = False):
-    """Evaluate Eq. 6 for all configs on one histogram.  Returns (argmin, predictions).
-    distinct_tiles: the per-block traffic term uses (#active experts * ntiles) instead of g."""
+def select(bm, ntiles, wave_cap, theta, counts, distinct_tiles: bool = False, wave_floor: bool = False,
+           pairs_term: bool = False):
+    """Evaluate the cost model for all configs on one histogram.  Returns (argmin, predictions).
+    Default: Eq. 6 as printed.  distinct_tiles: the traffic term uses (#active experts * ntiles)
+    instead of g; wave_floor: the wave term is max(g/W, 1); pairs_term: the fourth term is the number
+    of routed pairs instead of ln(g+1)."""
     bm, ntiles, wave_cap, counts = _i32(bm), _i32(ntiles), _i32(wave_cap), _i32(counts)
     theta = np.ascontiguousarray(theta, dtype=np.float32).reshape(-1, 4)
     n = bm.size
     assert ntiles.size == n and wave_cap.size == n and theta.shape[0] == n
     pred = np.empty(n, np.float64)
+    options = (1 if distinct_tiles else 0) | (2 if wave_floor else 0) | (4 if pairs_term else 0)
     best = _load().oracle_select(n, _ptr(bm, ctypes.c_int32), _ptr(ntiles, ctypes.c_int32),
                                  _ptr(wave_cap, ctypes.c_int32), _ptr(theta, ctypes.c_float),
-                                 _ptr(counts, ctypes.c_int32), counts.size, int(distinct_tiles),
+                                 _ptr(counts, ctypes.c_int32), counts.size, options,
                                  _ptr(pred, ctypes.c_double))
     return int(best), pred
 
 
-def design_matrix(g, wave_cap: int, distinct=None) -> np.ndarray:
-    """Rows [1, g/W, m, ln(g+1)] of Eq. 6; m = g as printed, or the distinct-weight-tile count."""
+def design_matrix(g, wave_cap: int, distinct=None, wave_floor: bool = False, pairs=None) -> np.ndarray:
+    """Rows [1, w, m, l].  As printed (Eq. 6): w = g/W, m = g, l = ln(g+1).  distinct: m = the
+    distinct-weight-tile count; wave_floor: w = max(g/W, 1); pairs: l = routed pairs of each point."""
     g = np.asarray(g, dtype=np.float64)
     m = g if distinct is None else np.asarray(distinct, dtype=np.float64)
-    return np.stack([np.ones_like(g), g / float(wave_cap), m, np.log(g + 1.0)], axis=1)
+    w = g / float(wave_cap)
+    if wave_floor:
+        w = np.maximum(w, 1.0)
+    last = np.log(g + 1.0) if pairs is None else np.asarray(pairs, dtype=np.float64)
+    return np.stack([np.ones_like(g), w, m, last], axis=1)
 
 
 def lower_median(v) -> float:
@@ -238,12 +247,15 @@ def lower_median(v) -> float:
     return float(s[(s.size - 1) // 2])
 
 
-def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4, distinct=None, relative: bool = False):
+def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4, distinct=None, relative: bool = False,
+                   wave_floor: bool = False, pairs=None):
     """Sec. 4.2 "Fitting" for ONE configuration.
 
-    distinct / relative are the two documented departures from the printed recipe that the
-    GPU library also offers: the traffic column holds the number of distinct weight tiles
-    instead of g, and the residuals are relative (every row divided by its measured time).
+    distinct / relative / wave_floor / pairs are the documented departures from the printed recipe
+    that the GPU library also offers: the traffic column holds the number of distinct weight tiles
+    instead of g, the residuals are relative (every row divided by its measured time), the wave
+    column is max(g/W, 1), and the fourth column is the routed-pair count (then always fitted)
+    instead of the logarithm.
 
     g: profiling grids, t_us: measured times.  The log column is used only if
     the (lower) median profiling grid is below wave_cap.  Solves the literal
@@ -253,8 +265,8 @@ def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4, distinct=None, rela
     """
     g = np.asarray(g, dtype=np.float64)
     t = np.asarray(t_us, dtype=np.float64)
-    X = design_matrix(g, wave_cap, distinct)
-    use_log = (n_terms >= 4) and (lower_median(g) < wave_cap)
+    X = design_matrix(g, wave_cap, distinct, wave_floor, pairs)
+    use_log = (n_terms >= 4) and (pairs is not None or lower_median(g) < wave_cap)
     cols = [0, 1, 2] + ([3] if use_log else [])
     if n_terms == 2:
         cols = [0, 2]

@@ -204,14 +204,27 @@ int oracle_moe(const uint16_t *X, const int32_t *ids, const float *w,
 /* T_hat = a + b*g/W + c*m + d*ln(g+1), evaluated left to right in fp64.
  * m = g is Eq. 6 as printed; m = number of distinct weight tiles is the cache-aware
  * reading of the per-block traffic term (see oracle.py). */
-double oracle_predict2(const float *theta4, int64_t g, int64_t m, int wave_cap)
+/* General form of the four-term model: t = a + b*w + c*m + d*l.
+ * As printed (Eq. 6): w = g/W, m = g, l = ln(g+1).  Options (bit mask) of the variants the
+ * GPU library also offers: 1: m is supplied by the caller (distinct weight tiles);
+ * 2: w = max(g/W, 1); 4: l = pairs (routed pairs) instead of the logarithm. */
+double oracle_predict_opt(const float *theta4, int64_t g, int64_t m, int64_t pairs, int wave_cap, int options)
 {
     double gd = (double)g;
+    double w = gd / (double)wave_cap;
+    if ((options & 2) && w < 1.0) w = 1.0;
+    double traffic = (options & 1) ? (double)m : gd;
+    double last = (options & 4) ? (double)pairs : log(gd + 1.0);
     double t = (double)theta4[0];
-    t = t + (double)theta4[1] * (gd / (double)wave_cap);
-    t = t + (double)theta4[2] * (double)m;
-    t = t + (double)theta4[3] * log(gd + 1.0);
+    t = t + (double)theta4[1] * w;
+    t = t + (double)theta4[2] * traffic;
+    t = t + (double)theta4[3] * last;
     return t;
+}
+
+double oracle_predict2(const float *theta4, int64_t g, int64_t m, int wave_cap)
+{
+    return oracle_predict_opt(theta4, g, m, 0, wave_cap, 1);
 }
 
 double oracle_predict(const float *theta4, int64_t g, int wave_cap)
@@ -225,18 +238,18 @@ double oracle_predict(const float *theta4, int64_t g, int wave_cap)
  * n_cfg <= 0).  pred (optional) receives all predictions.
  */
 int oracle_select(int n_cfg, const int32_t *bm, const int32_t *ntiles, const int32_t *wave_cap,
-                  const float *theta /*[n_cfg,4]*/, const int32_t *counts, int E, int distinct_tiles,
+                  const float *theta /*[n_cfg,4]*/, const int32_t *counts, int E, int options,
                   double *pred)
 {
     int best = -1;
     double best_t = 0.0;
-    int64_t active = 0;
+    int64_t active = 0, pairs = 0;
     for (int e = 0; e < E; ++e)
-        if (counts[e] > 0) ++active;
+        if (counts[e] > 0) { ++active; pairs += counts[e]; }
     for (int c = 0; c < n_cfg; ++c) {
         int64_t g = oracle_grid(counts, E, bm[c], ntiles[c]);
-        int64_t m = distinct_tiles ? active * ntiles[c] : g;
-        double t = oracle_predict2(theta + 4 * (size_t)c, g, m, wave_cap[c]);
+        int64_t m = active * ntiles[c];
+        double t = oracle_predict_opt(theta + 4 * (size_t)c, g, m, pairs, wave_cap[c], options);
         if (pred) pred[c] = t;
         if (best < 0 || t < best_t) { best = c; best_t = t; }
     }

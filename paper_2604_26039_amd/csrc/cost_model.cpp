@@ -1,9 +1,12 @@
 // Four-term wave cost model (paper Eq. 6, Sec. 4.2): least-squares fit per configuration
 // and the runtime argmin over configurations.  Host code only.
 //
-//   T_hat(c) = a + b * g/W + c * m + d * ln(g + 1),   g = (sum_e ceil(n_e / bm_c)) * ntiles_c
+//   T_hat(c) = a + b * w + c * m + d * l,   g = (sum_e ceil(n_e / bm_c)) * ntiles_c
+//   w = g/W as printed, or max(g/W, 1) (RAMP_CM_WAVE_FLOOR: a grid below one wave still costs one wave);
 //   m = g as printed, or the number of distinct weight tiles (active experts * ntiles_c) when the
-//   per-block traffic term is made cache aware (RAMP_CM_DISTINCT_TILES).
+//   per-block traffic term is made cache aware (RAMP_CM_DISTINCT_TILES);
+//   l = ln(g + 1) as printed (used only in the sub-wave case), or the number of routed pairs
+//   (RAMP_CM_PAIRS: the work that does not depend on the tiling).
 //
 // The columns g/W and g of the design matrix are proportional for a fixed configuration, so
 // the literal four-column system is rank deficient.  The fit returns the minimum-norm
@@ -80,13 +83,18 @@ void lstsq_min_norm(std::vector<double> A, int n, int m, const double *t, double
 
 }  // namespace
 
+static const int kAllFlags = RAMP_CM_RELATIVE | RAMP_CM_DISTINCT_TILES | RAMP_CM_WAVE_FLOOR | RAMP_CM_PAIRS;
+
 extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
-                                   const int64_t *distinct, const double *time_us, int flags, float *theta)
+                                   const int64_t *distinct, const int64_t *pairs, const double *time_us, int flags,
+                                   float *theta)
 {
     const bool use_distinct = (flags & RAMP_CM_DISTINCT_TILES) != 0;
     const bool relative = (flags & RAMP_CM_RELATIVE) != 0;
+    const bool wave_floor = (flags & RAMP_CM_WAVE_FLOOR) != 0;
+    const bool use_pairs = (flags & RAMP_CM_PAIRS) != 0;
     if (n_cfg < 0 || n_pts <= 0 || !wave_cap || !grid || !time_us || !theta || (use_distinct && !distinct) ||
-        (flags & ~(RAMP_CM_RELATIVE | RAMP_CM_DISTINCT_TILES))) {
+        (use_pairs && !pairs) || (flags & ~kAllFlags)) {
         ramp::set_error("cost_model_fit: bad argument");
         return RAMP_EINVAL;
     }
@@ -101,8 +109,9 @@ extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts
         }
         for (int i = 0; i < n_pts; ++i) sorted_g[i] = (double)g[i];
         std::sort(sorted_g.begin(), sorted_g.end());
-        const bool use_log = sorted_g[(n_pts - 1) / 2] < W;  // lower median in the sub-wave region
-        const int m = use_log ? 4 : 3;
+        // fourth column: the log term only when the lower median grid is in the sub-wave region; the pair count always
+        const bool use_fourth = use_pairs || sorted_g[(n_pts - 1) / 2] < W;
+        const int m = use_fourth ? 4 : 3;
         for (int i = 0; i < n_pts; ++i) {
             const double gi = (double)g[i];
             const double mi = use_distinct ? (double)distinct[(size_t)c * n_pts + i] : gi;
@@ -115,9 +124,10 @@ extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts
                 scale = 1.0 / t[i];
             }
             A[0 * (size_t)n_pts + i] = 1.0 * scale;
-            A[1 * (size_t)n_pts + i] = gi / W * scale;
+            const double wi = gi / W;
+            A[1 * (size_t)n_pts + i] = ((wave_floor && wi < 1.0) ? 1.0 : wi) * scale;
             A[2 * (size_t)n_pts + i] = mi * scale;
-            A[3 * (size_t)n_pts + i] = std::log(gi + 1.0) * scale;
+            A[3 * (size_t)n_pts + i] = (use_pairs ? (double)pairs[i] : std::log(gi + 1.0)) * scale;
             rhs[i] = t[i] * scale;
         }
         double x[4] = {0, 0, 0, 0};
@@ -132,13 +142,18 @@ extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs,
                                       int flags, int *best_idx, double *pred_us)
 {
     if (E <= 0 || n_cfg <= 0 || !cfgs || !ntiles || !wave_cap || !theta || !expert_counts || !best_idx ||
-        (flags & ~(RAMP_CM_RELATIVE | RAMP_CM_DISTINCT_TILES))) {
+        (flags & ~kAllFlags)) {
         ramp::set_error("cost_model_select: bad argument");
         return RAMP_EINVAL;
     }
     const bool use_distinct = (flags & RAMP_CM_DISTINCT_TILES) != 0;
-    int64_t active = 0;
-    for (int e = 0; e < E; ++e) active += expert_counts[e] > 0 ? 1 : 0;
+    const bool wave_floor = (flags & RAMP_CM_WAVE_FLOOR) != 0;
+    const bool use_pairs = (flags & RAMP_CM_PAIRS) != 0;
+    int64_t active = 0, pairs = 0;
+    for (int e = 0; e < E; ++e) {
+        active += expert_counts[e] > 0 ? 1 : 0;
+        pairs += expert_counts[e] > 0 ? expert_counts[e] : 0;
+    }
     int best = -1;
     double best_t = 0.0;
     // M-tiles depend only on bm; configurations usually share a handful of bm values
@@ -162,10 +177,11 @@ extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs,
         const double g = (double)(last_mt * (int64_t)ntiles[c]);
         const float *th = theta + (size_t)c * 4;
         double t = (double)th[0];
-        t = t + (double)th[1] * (g / (double)wave_cap[c]);
+        const double w = g / (double)wave_cap[c];
+        t = t + (double)th[1] * ((wave_floor && w < 1.0) ? 1.0 : w);
         const double m = use_distinct ? (double)(active * (int64_t)ntiles[c]) : g;
         t = t + (double)th[2] * m;
-        t = t + (double)th[3] * std::log(g + 1.0);
+        t = t + (double)th[3] * (use_pairs ? (double)pairs : std::log(g + 1.0));
         if (pred_us) pred_us[c] = t;
         if (best < 0 || t < best_t) {
             best = c;

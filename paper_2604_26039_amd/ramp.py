@@ -18,7 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libramp.so")
 
 OK, EINVAL, ENOSPC, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
-CM_EQ6, CM_RELATIVE, CM_DISTINCT_TILES = 0, 1, 2
+CM_EQ6, CM_RELATIVE, CM_DISTINCT_TILES, CM_WAVE_FLOOR, CM_PAIRS = 0, 1, 2, 4, 8
 
 
 class Shape(ctypes.Structure):
@@ -86,7 +86,7 @@ def lib() -> ctypes.CDLL:
         L.ramp_fused_moe.restype = ci
         L.ramp_fused_moe.argtypes = [sp, cp, vp, i32p, f32p, vp, vp, vp, sz, vp]
         L.ramp_cost_model_fit.restype = ci
-        L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp, ci, vp]
+        L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp, vp, ci, vp]
         L.ramp_cost_model_select.restype = ci
         L.ramp_cost_model_select.argtypes = [ci, ci, cp, vp, vp, vp, vp, ci, ctypes.POINTER(ci), vp]
         L.ramp_probe_enable.restype = ci
@@ -232,8 +232,9 @@ def copy_bytes(dst: torch.Tensor, src: torch.Tensor, nbytes: int, stream=None):
 
 # ----------------------------------------------------------------------------- cost model (host)
 
-def cost_model_fit(wave_cap: Sequence[int], grid, time_us, distinct=None, flags: int = CM_EQ6) -> np.ndarray:
-    """grid, time_us (and distinct with CM_DISTINCT_TILES): [n_cfg, n_pts].  Returns theta float32 [n_cfg, 4]."""
+def cost_model_fit(wave_cap: Sequence[int], grid, time_us, distinct=None, pairs=None, flags: int = CM_EQ6) -> np.ndarray:
+    """grid, time_us (and distinct with CM_DISTINCT_TILES): [n_cfg, n_pts]; pairs (with CM_PAIRS): [n_pts].
+    Returns theta float32 [n_cfg, 4]."""
     grid = _np(grid, np.int64)
     time_us = _np(time_us, np.float64)
     n_cfg, n_pts = grid.shape
@@ -241,11 +242,15 @@ def cost_model_fit(wave_cap: Sequence[int], grid, time_us, distinct=None, flags:
     if distinct is not None:
         distinct = _np(distinct, np.int64)
         assert distinct.shape == (n_cfg, n_pts)
+    if pairs is not None:
+        pairs = _np(pairs, np.int64)
+        assert pairs.shape == (n_pts,)
     wc = _np(wave_cap, np.int32)
     assert wc.size == n_cfg
     theta = np.zeros((n_cfg, 4), np.float32)
     _check(lib().ramp_cost_model_fit(n_cfg, wc.ctypes.data, n_pts, grid.ctypes.data,
-                                     distinct.ctypes.data if distinct is not None else None, time_us.ctypes.data,
+                                     distinct.ctypes.data if distinct is not None else None,
+                                     pairs.ctypes.data if pairs is not None else None, time_us.ctypes.data,
                                      flags, theta.ctypes.data))
     return theta
 

@@ -161,7 +161,7 @@ def profile(layers: LayerSet, fam: Family, points: Sequence[Point], log=None, **
 
 # The dispatch model used on this chip: Eq. 6 with the traffic term on distinct weight tiles,
 # fitted on relative residuals.  EQ6 (= 0) is the model exactly as printed.
-MI355X_MODEL = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES
+MI355X_MODEL = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES | ramp.CM_WAVE_FLOOR | ramp.CM_PAIRS
 
 
 def distinct_tiles(fam: Family, counts_list: Sequence[np.ndarray]) -> np.ndarray:
@@ -172,7 +172,10 @@ def distinct_tiles(fam: Family, counts_list: Sequence[np.ndarray]) -> np.ndarray
 
 def fit(fam: Family, grid: np.ndarray, t_us: np.ndarray, counts_list=None, flags: int = ramp.CM_EQ6) -> np.ndarray:
     distinct = distinct_tiles(fam, counts_list) if (flags & ramp.CM_DISTINCT_TILES) else None
-    return ramp.cost_model_fit(fam.wave_cap, grid, t_us, distinct=distinct, flags=flags)
+    pairs = None
+    if flags & ramp.CM_PAIRS:
+        pairs = np.array([int(np.asarray(c).sum()) for c in counts_list], np.int64)
+    return ramp.cost_model_fit(fam.wave_cap, grid, t_us, distinct=distinct, pairs=pairs, flags=flags)
 
 
 def select(fam: Family, theta: np.ndarray, counts: np.ndarray, flags: int = ramp.CM_EQ6) -> int:

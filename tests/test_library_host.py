@@ -162,3 +162,36 @@ def test_adapted_model_fit_and_select_match_oracle():
         ramp.cost_model_fit(wc, g, t, distinct=None, flags=flags)   # distinct tiles required
     with pytest.raises(ramp.RampError):
         ramp.cost_model_fit(wc, g, -t, distinct=u, flags=flags)     # relative fit needs positive times
+
+
+def test_mi355x_model_fit_and_select_match_oracle():
+    """All four variant flags together (relative fit, distinct tiles, wave floor, pair-count term)."""
+    rng = np.random.default_rng(6)
+    sh = shape_of("olmoe", 256)
+    cfgs = ramp.configs(sh)
+    n = len(cfgs)
+    nt = np.array([ramp.config_ntiles(sh, c) for c in cfgs])
+    wc = np.array([ramp.config_wave_capacity(c) for c in cfgs])
+    bm = [c.bm for c in cfgs]
+    hists = [synth.histogram_subset(int(T), sh.k, sh.E, b, seed=i) for i, (T, b) in
+             enumerate((T, b) for T in (1, 8, 45, 300, 2000) for b in (1.0, 0.7, 0.4, 0.25, 0.12))]
+    g = np.array([[oracle.grid(h, bm[c], int(nt[c])) for h in hists] for c in range(n)], np.int64)
+    act = np.array([int((h > 0).sum()) for h in hists])
+    P = np.array([int(h.sum()) for h in hists], np.int64)
+    u = nt[:, None] * act[None, :]
+    t = 9 + 6 * np.maximum(g / wc[:, None], 1) + 0.3 * u + 2e-3 * P[None, :] + rng.normal(0, 0.2, g.shape)
+    flags = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES | ramp.CM_WAVE_FLOOR | ramp.CM_PAIRS
+    theta = ramp.cost_model_fit(wc, g, t, distinct=u, pairs=P, flags=flags)
+    for c in range(0, n, 3):
+        th_o, used = oracle.fit_cost_model(g[c], t[c], int(wc[c]), distinct=u[c], relative=True, wave_floor=True, pairs=P)
+        X = oracle.design_matrix(g[c], int(wc[c]), u[c], wave_floor=True, pairs=P)
+        po, pl = X @ th_o, X @ theta[c].astype(np.float64)
+        assert used and np.abs(po - pl).max() <= 5e-5 * np.abs(po).max()
+    for h in hists[::3]:
+        best, pred = ramp.cost_model_select(sh.E, cfgs, nt, wc, theta, h, want_pred=True, flags=flags)
+        b_o, p_o = oracle.select(bm, nt, wc, theta, h, distinct_tiles=True, wave_floor=True, pairs_term=True)
+        assert best == b_o and (pred == p_o).all()
+    with pytest.raises(ramp.RampError):
+        ramp.cost_model_fit(wc, g, t, distinct=u, pairs=None, flags=flags)   # pair counts required
+    with pytest.raises(ramp.RampError):
+        ramp.cost_model_fit(wc, g, t, distinct=u, pairs=P, flags=flags | 64)  # unknown flag

@@ -242,3 +242,76 @@ def test_select_with_distinct_tiles_matches_brute_force():
         a, b, cc, d = (float(np.float32(v)) for v in theta[c])
         exp.append(a + b * (g / W[c]) + cc * (active * int(nt[c])) + d * math.log(g + 1.0))
     assert np.allclose(pred, exp, rtol=1e-14) and best == int(np.argmin(exp))
+
+
+# ----------------------------------------------------------------------------- wave floor and pair-count term
+
+def test_wave_floor_is_inactive_above_one_wave_and_collapses_below_it():
+    W = 256
+    rng = np.random.default_rng(11)
+    u = rng.integers(8, 400, 25).astype(float)
+    P = rng.integers(100, 40000, 25).astype(float)
+    # every grid at least one wave: max(g/W, 1) == g/W, so the fit must not change at all
+    g_hi = rng.integers(W, 40 * W, 25).astype(float)
+    t_hi = 5 + 0.7 * g_hi / W + 0.3 * u + 1e-3 * P + rng.normal(0, 0.05, 25)
+    th0, _ = oracle.fit_cost_model(g_hi, t_hi, W, distinct=u, pairs=P)
+    th1, _ = oracle.fit_cost_model(g_hi, t_hi, W, distinct=u, pairs=P, wave_floor=True)
+    assert np.array_equal(th0, th1)
+    # every grid below one wave: the wave column is the constant 1, i.e. a second intercept;
+    # predictions equal those of the model without a wave column (fitted here by the normal equations)
+    g_lo = rng.integers(1, W, 25).astype(float)
+    t_lo = 9 + 0.3 * u + 2e-3 * P + rng.normal(0, 0.05, 25)
+    th, _ = oracle.fit_cost_model(g_lo, t_lo, W, distinct=u, pairs=P, wave_floor=True)
+    X = oracle.design_matrix(g_lo, W, u, wave_floor=True, pairs=P)
+    assert (X[:, 1] == 1.0).all() and (X[:, 3] == P).all()
+    A = np.stack([np.ones(25), u, P], 1)
+    beta = np.linalg.solve(A.T @ A, A.T @ t_lo)
+    assert np.allclose(X @ th, A @ beta, rtol=1e-9)
+
+
+def test_pair_term_recovers_exact_synthetic_model_and_replaces_the_log():
+    W = 512
+    rng = np.random.default_rng(12)
+    g = rng.integers(10, 6000, 25).astype(float)          # both sides of one wave
+    u = rng.integers(8, 900, 25).astype(float)
+    P = rng.integers(8, 70000, 25).astype(float)
+    a, b, c, d = 11.0, 21.0, 0.25, 3.5e-3
+    t = a + b * np.maximum(g / W, 1.0) + c * u + d * P
+    theta, used = oracle.fit_cost_model(g, t, W, distinct=u, wave_floor=True, pairs=P)
+    assert used                                            # the pair column is always fitted
+    assert np.allclose(theta, [a, b, c, d], rtol=1e-7)
+    th_rel, _ = oracle.fit_cost_model(g, t, W, distinct=u, relative=True, wave_floor=True, pairs=P)
+    assert np.allclose(th_rel, [a, b, c, d], rtol=1e-7)
+    # median grid above one wave: as printed the log column would be dropped, the pair column is not
+    g_big = g + 4 * W
+    t_big = a + b * g_big / W + c * u + d * P
+    th_big, used_big = oracle.fit_cost_model(g_big, t_big, W, distinct=u, pairs=P)
+    assert used_big and np.allclose(th_big, [a, b, c, d], rtol=1e-7)
+    _, used_log = oracle.fit_cost_model(g_big, t_big, W, distinct=u)
+    assert not used_log
+
+
+def test_select_with_wave_floor_and_pairs_matches_brute_force():
+    rng = np.random.default_rng(13)
+    n = 12
+    bm = rng.choice([4, 16, 32, 64, 128, 256], n)
+    nt = rng.integers(8, 80, n)
+    W = rng.choice([256, 512, 1024], n)
+    theta = (np.abs(rng.normal(0, 1, (n, 4))) * [10, 5, 0.05, 1e-3]).astype(np.float32)
+    for trial in range(6):
+        counts = rng.integers(0, 10 ** (1 + trial % 3), 64) * (rng.random(64) < 0.4)
+        active, pairs = int((counts > 0).sum()), int(counts.sum())
+        best, pred = oracle.select(bm, nt, W, theta, counts, distinct_tiles=True, wave_floor=True, pairs_term=True)
+        exp = []
+        for c in range(n):
+            g = sum(-(-int(x) // int(bm[c])) for x in counts) * int(nt[c])
+            a, b, cc, d = (float(np.float32(v)) for v in theta[c])
+            exp.append(a + b * max(g / W[c], 1.0) + cc * (active * int(nt[c])) + d * pairs)
+        assert np.allclose(pred, exp, rtol=1e-14) and best == int(np.argmin(exp))
+    # each option alone
+    counts = rng.integers(0, 30, 64)
+    _, p_floor = oracle.select(bm, nt, W, theta, counts, wave_floor=True)
+    _, p_plain = oracle.select(bm, nt, W, theta, counts)
+    for c in range(n):
+        g = sum(-(-int(x) // int(bm[c])) for x in counts) * int(nt[c])
+        assert p_floor[c] - p_plain[c] == pytest.approx(float(theta[c, 1]) * (max(g / W[c], 1.0) - g / W[c]), abs=1e-9)
