@@ -59,7 +59,11 @@ typedef struct {
  *          bits 8.. = 0 for the LDS-staged path; 0x100 | WK selects the weight-streaming
  *          path for small token blocks (weights go from HBM straight into MFMA operand
  *          registers, the K reduction is split WK ways over the workgroup's wavefronts;
- *          bk is then the k-extent of one register load batch) */
+ *          bk is then the k-extent of one register load batch); 0x200 = LDS-staged path with
+ *          the register-pipelined main loop; 0x400 = persistent ping-pong kernel for the
+ *          large tiles (one workgroup per compute unit walks its share of the tiles, two
+ *          groups of four wavefronts alternate memory and MFMA phases).
+ *          Take configurations from ramp_get_config rather than composing mode words. */
 typedef struct {
     int32_t bm, bn, bk, waves, stages, mode;
 } ramp_config;
