@@ -126,6 +126,20 @@ def test_olmoe_small_every_config(olmoe_small, T, beta):
         assert np.linalg.norm(v - vals[0]) / np.linalg.norm(vals[0]) <= L2_TOL
 
 
+@pytest.mark.parametrize("H,I,E,k,T,beta", [(128, 128, 4, 2, 700, 1.0), (256, 128, 6, 3, 1500, 0.5), (128, 384, 3, 1, 2500, 1.0)])
+def test_smallest_dimensions_many_tiles(H, I, E, k, T, beta):
+    """Shortest legal reduction lengths (a tile is as long as the load pipeline is deep) with enough pairs
+    that the large-tile kernels walk several tiles per workgroup, full and ragged ones, on every configuration."""
+    shape = synth.Shape("edge", H, I, E, k)
+    L = Layer(shape, T, seed=H + I, x_std=1.5)
+    ids, w = synth.routing(T, shape, beta, seed=T)
+    ref = L.oracle_rows(ids, w)
+    cfgs = ramp.configs(L.rs)
+    assert any(c.mode & 0x400 for c in cfgs) and any(c.mode & 0x100 for c in cfgs)
+    for cfg in cfgs:
+        assert_close(L.run(cfg, ids, w), ref, f"H={H} I={I} {cfg}")
+
+
 def test_run_to_run_bit_identical(olmoe_small):
     L = olmoe_small
     ids, w = synth.routing(96, L.s, 0.2, seed=9)
