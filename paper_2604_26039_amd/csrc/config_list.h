@@ -85,3 +85,8 @@
     X(32, 4, 4, 1, 2)         \
     X(64, 2, 2, 4, 1)         \
     X(64, 4, 4, 1, 1)
+
+// deeper load batches (U = 4): more bytes in flight per wavefront for the smallest batches
+#define RAMP_STREAM_GROUP2(X) \
+    X(16, 2, 2, 4, 4)         \
+    X(16, 2, 2, 2, 4)

@@ -16,6 +16,7 @@ void register_group6(KernelInfo *, int *);
 void register_group7(KernelInfo *, int *);
 void register_stream_group0(KernelInfo *, int *);
 void register_stream_group1(KernelInfo *, int *);
+void register_stream_group2(KernelInfo *, int *);
 
 namespace {
 constexpr int kMaxKernels = 128;
@@ -36,6 +37,7 @@ void init_registry()
         register_group7(g_kernels, &g_num_kernels);
         register_stream_group0(g_kernels, &g_num_kernels);
         register_stream_group1(g_kernels, &g_num_kernels);
+        register_stream_group2(g_kernels, &g_num_kernels);
     });
 }
 
