@@ -124,8 +124,10 @@ int ramp_pack_weights(const ramp_shape *shape, const void *W_gate, const void *W
 /* ---- fused MoE layer (Sec. 2.2 phases 1-3, Sec. 4.3) --------------------------------------
  * out[t,:] = sum_j w[t,j] * ( SiLU(x_t W_gate[e_j]) * (x_t W_up[e_j]) ) W_down[e_j]
  * bf16 inputs, fp32 accumulation, one bf16 rounding of the activation between the
- * projections, fp32 per-pair rows summed in fixed j order (no atomics: results are
- * bit-identical from run to run), one final rounding to bf16.
+ * projections, one row per pair (already multiplied by its router weight; fp32, or bf16
+ * once T*k*H reaches 8 Mi elements, where these rows dominate the memory traffic) summed in
+ * fp32 in fixed j order (no atomics: results are bit-identical from run to run), one final
+ * rounding to bf16.  Requires H and I to be multiples of 128 and E <= 1024.
  * Runs align(bm) + both projections + combine on `stream`; the grid is an upper
  * bound with early exit (Sec. 4.3 "grid overlaunch"), so nothing is read back. */
 size_t ramp_fused_moe_workspace_bytes(const ramp_shape *shape, const ramp_config *cfg);
