@@ -59,7 +59,8 @@ __device__ void block_histogram(const int32_t *ids, int begin, int end, int E, i
 // From n_e (one expert per lane, 0 beyond E): slot offsets toff[0..E] in LDS, counts / meta /
 // tile_expert in global memory.  Called by all NT lanes; E <= NT.
 __device__ void block_scan_and_emit(int n_e, int E, int bm, int cap, int dropped_total, int *toff, int *wsum,
-                                    int32_t *counts, int32_t *meta, int32_t *tile_expert, int32_t *tile_rows)
+                                    int32_t *counts, int32_t *meta, int32_t *tile_expert, int32_t *tile_rows,
+                                    bool emit = true)
 {
     const int e = threadIdx.x;
     int slots = (e < E) ? (n_e + bm - 1) / bm * bm : 0;
@@ -67,16 +68,19 @@ __device__ void block_scan_and_emit(int n_e, int E, int bm, int cap, int dropped
     int off = block_exclusive_scan(slots, wsum, &p_pad);
     if (e < E) {
         toff[e] = off;
-        counts[e] = n_e;
+        if (emit) counts[e] = n_e;
     }
     if (e == 0) {
         toff[E] = p_pad;
-        meta[0] = p_pad;
-        meta[1] = p_pad / bm;
-        meta[2] = dropped_total;
-        meta[3] = 0;
+        if (emit) {
+            meta[0] = p_pad;
+            meta[1] = p_pad / bm;
+            meta[2] = dropped_total;
+            meta[3] = 0;
+        }
     }
     __syncthreads();
+    if (!emit) return;  // the other workgroups of a launch only need the offsets
     const int m_tiles = p_pad / bm, m_cap = cap / bm;
     for (int m = threadIdx.x; m < m_cap; m += NT) {
         int owner = -1;
@@ -248,14 +252,36 @@ __global__ __launch_bounds__(NT) void align_scan_kernel(int B, int E, int bm, in
     }
 }
 
-__global__ __launch_bounds__(NT) void align_scatter_kernel(const int32_t *ids, int P, int E, const int32_t *block_base,
-                                                           int32_t *sorted)
+// Scan + scatter in one launch: every workgroup sums the per-chunk histograms itself (B x E ints), scans the
+// experts, and scatters its own chunk; workgroup 0 also writes counts, meta and the per-tile arrays.
+__global__ __launch_bounds__(NT) void align_scan_scatter_kernel(const int32_t *ids, int P, int B, int E, int bm, int cap,
+                                                                const int32_t *block_counts,
+                                                                const int32_t *block_dropped, int32_t *sorted,
+                                                                int32_t *tile_expert, int32_t *tile_rows,
+                                                                int32_t *counts, int32_t *meta)
 {
     extern __shared__ int lds[];
-    int *cursor = lds;
-    unsigned *wcnt = reinterpret_cast<unsigned *>(lds + E);
-    for (int x = threadIdx.x; x < E; x += NT) cursor[x] = block_base[(size_t)blockIdx.x * E + x];
+    int *toff = lds, *wsum = toff + E + 1, *cursor = wsum + NW;
+    unsigned *wcnt = reinterpret_cast<unsigned *>(cursor + E);
+    const int e = threadIdx.x;
+    int n_e = 0, before = 0;
+    if (e < E) {
+#pragma unroll 8
+        for (int b = 0; b < B; ++b) {
+            const int c = block_counts[(size_t)b * E + e];
+            if (b < (int)blockIdx.x) before += c;
+            n_e += c;
+        }
+    }
     for (int x = threadIdx.x; x < NW * E; x += NT) wcnt[x] = 0;
+    int dropped = 0;
+    if (blockIdx.x == 0) {
+#pragma unroll 8
+        for (int b = 0; b < B; ++b) dropped += block_dropped[b];
+    }
+    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, counts, meta, tile_expert, tile_rows, blockIdx.x == 0);
+    __syncthreads();
+    if (e < E) cursor[e] = toff[e] + before;
     __syncthreads();
     const int begin = blockIdx.x * kAlignChunk;
     const int end = min(P, begin + kAlignChunk);
@@ -322,14 +348,16 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
                        block_counts, block_dropped, scatter);
     int rc = check_launch("align_hist_kernel");
     if (rc) return rc;
-    hipLaunchKernelGGL(align_scan_kernel, dim3(1), dim3(NT), (E + 1 + NW) * sizeof(int), stream, B, E, bm, cap,
-                       block_counts, block_dropped, block_base, tile_expert, tile_rows, counts, meta, scatter);
-    rc = check_launch("align_scan_kernel");
-    if (rc || !scatter) return rc;
-    const size_t scatter_lds = ((size_t)E + (size_t)NW * E) * sizeof(int);
-    if (int rc2 = allow_lds(align_scatter_kernel, scatter_lds)) return rc2;
-    hipLaunchKernelGGL(align_scatter_kernel, dim3(B), dim3(NT), scatter_lds, stream, ids, P, E, block_base, sorted);
-    return check_launch("align_scatter_kernel");
+    if (!scatter) {
+        hipLaunchKernelGGL(align_scan_kernel, dim3(1), dim3(NT), (E + 1 + NW) * sizeof(int), stream, B, E, bm, cap,
+                           block_counts, block_dropped, block_base, tile_expert, tile_rows, counts, meta, scatter);
+        return check_launch("align_scan_kernel");
+    }
+    const size_t scatter_lds = ((size_t)(E + 1) + NW + E + (size_t)NW * E) * sizeof(int);
+    if (int rc2 = allow_lds(align_scan_scatter_kernel, scatter_lds)) return rc2;
+    hipLaunchKernelGGL(align_scan_scatter_kernel, dim3(B), dim3(NT), scatter_lds, stream, ids, P, B, E, bm, cap,
+                       block_counts, block_dropped, sorted, tile_expert, tile_rows, counts, meta);
+    return check_launch("align_scan_scatter_kernel");
 }
 
 int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
