@@ -28,7 +28,7 @@ namespace ramp {
 
 template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
 struct PingPongTraits {
-    using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
+    using TT = TileTraits<BM, BN, BK, WM, WN, 2>;  // tile geometry only; the ring depths are defined here
     static constexpr bool ROWX = (STAGE == 1);           // gathered rows, 128-byte pieces
     static constexpr int XK = ROWX ? 64 : BK;            // k-values of one token load batch ("super-slice")
     static constexpr int XS = XK / BK;                   // k-slices fed by one super-slice
@@ -75,7 +75,7 @@ __device__ __forceinline__ void wait_vmcnt_upto(int n)
 template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
 __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
 {
-    using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
+    using TT = TileTraits<BM, BN, BK, WM, WN, 2>;  // tile geometry only; the ring depths are defined here
     using PT = PingPongTraits<STAGE, BM, BN, BK, WM, WN, NSTAGE>;
     constexpr int KS = TT::KS, NB = TT::NB, NWAVE = TT::NWAVE;
     constexpr int FB = (STAGE == 1) ? TT::FB1 : TT::FB2;
@@ -321,11 +321,13 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             if (STEADY) {
                 if (XS == 1) wait_vmcnt<(NSTAGE - 2) * (TSLOTS + WSLOTS)>();
                 else if (par == 0) wait_vmcnt<(NSTAGE - 2) * WSLOTS + (XS == 2 ? TSLOTS : 0)>();
-                else wait_vmcnt<(NSTAGE - 2) * WSLOTS>();
+                else wait_vmcnt<(NSTAGE - 2 < 2 ? NSTAGE - 2 : 2) * WSLOTS>();  // the token batch issued one phase ago is needed now:
+                                                                              // only the weight batches issued after it may remain
             } else if (kt + 1 < KT) {
                 const int later = min(NSTAGE - 2, KT - 2 - kt);  // younger weight slices that may stay in flight
                 if (XS == 1) wait_vmcnt_upto(later * (TSLOTS + WSLOTS));
-                else wait_vmcnt_upto(later * WSLOTS + (x_issued ? TSLOTS : 0));
+                else if (par == 0) wait_vmcnt_upto(later * WSLOTS + (x_issued ? TSLOTS : 0));
+                else wait_vmcnt_upto((later < 2 ? later : 2) * WSLOTS);
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): fragments in registers, buffers no longer read
             phase_barrier();
@@ -426,18 +428,20 @@ void launch_pingpong(int stage, const GemmArgs &a, hipStream_t stream)
     g.total_tiles = (int)xcd_grid(g);
     // persistent: one workgroup per compute unit walks its share of the tiles (the count is a multiple of 8)
     const dim3 grid(g.total_tiles < kNumCU ? g.total_tiles : kNumCU), block(512);
+    // the down-projection stages tokens and weights per slice and needs LDS for its output rows: at most 4 stages
+    constexpr int NS2 = NSTAGE > 4 ? 4 : NSTAGE;
     if (stage == 1)
         hipLaunchKernelGGL((moe_pingpong_kernel<1, BM, BN, BK, WM, WN, NSTAGE>), grid, block, 0, stream, g);
     else
-        hipLaunchKernelGGL((moe_pingpong_kernel<2, BM, BN, BK, WM, WN, NSTAGE>), grid, block, 0, stream, g);
+        hipLaunchKernelGGL((moe_pingpong_kernel<2, BM, BN, BK, WM, WN, NS2>), grid, block, 0, stream, g);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int NSTAGE>
 KernelInfo make_pingpong_info()
 {
-    using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
+    using TT = TileTraits<BM, BN, BK, WM, WN, 2>;  // tile geometry only; the ring depths are defined here
     constexpr int l1 = PingPongTraits<1, BM, BN, BK, WM, WN, NSTAGE>::LDS_BYTES;
-    constexpr int l2 = PingPongTraits<2, BM, BN, BK, WM, WN, NSTAGE>::LDS_BYTES;
+    constexpr int l2 = PingPongTraits<2, BM, BN, BK, WM, WN, (NSTAGE > 4 ? 4 : NSTAGE)>::LDS_BYTES;
     KernelInfo ki;
     ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | kModePingPong};
     ki.wm = WM;
