@@ -140,6 +140,25 @@ def test_smallest_dimensions_many_tiles(H, I, E, k, T, beta):
         assert_close(L.run(cfg, ids, w), ref, f"H={H} I={I} {cfg}")
 
 
+RANDOM_CASES = [  # H, I, E, k, T, beta: unusual tile counts (N-tiles 1, 3, 5, 6, 7, 10), few and many experts
+    (384, 128, 5, 2, 900, 1.0), (256, 640, 7, 3, 400, 0.5), (768, 384, 12, 4, 260, 0.3), (128, 896, 3, 2, 1300, 1.0),
+    (640, 256, 40, 6, 150, 0.2), (1280, 128, 9, 1, 2100, 1.0), (512, 768, 130, 5, 333, 0.1), (256, 256, 2, 2, 3000, 1.0),
+]
+
+
+@pytest.mark.parametrize("H,I,E,k,T,beta", RANDOM_CASES)
+def test_irregular_shapes_every_third_config(H, I, E, k, T, beta):
+    shape = synth.Shape("irregular", H, I, E, k)
+    L = Layer(shape, T, seed=H * 7 + I, x_std=1.0)
+    ids, w = synth.routing(T, shape, beta, seed=E * 100 + k)
+    ref = L.oracle_rows(ids, w)
+    cfgs = ramp.configs(L.rs)
+    picked = cfgs[(H // 128) % 3::3] + [c for c in cfgs if c.mode & 0x400]
+    assert picked
+    for cfg in picked:
+        assert_close(L.run(cfg, ids, w), ref, f"H={H} I={I} E={E} k={k} T={T} {cfg}")
+
+
 def test_run_to_run_bit_identical(olmoe_small):
     L = olmoe_small
     ids, w = synth.routing(96, L.s, 0.2, seed=9)
