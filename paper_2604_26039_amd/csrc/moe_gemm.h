@@ -65,11 +65,7 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
 
 // SiLU(x) = x / (1 + e^-x) with the hardware exp2 and reciprocal (1 ulp each; the result is rounded to
 // bf16 right after, which is 2^16 times coarser).
-#ifdef RAMP_ABL_NOSILU
-__device__ __forceinline__ float silu_f32(float x) { return x; }
-#else
 __device__ __forceinline__ float silu_f32(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
-#endif
 
 // Four consecutive features of one weighted per-pair output row: fp32, or bf16 for large batches.
 __device__ __forceinline__ void store_pair_row(const GemmArgs &a, size_t elem, float v0, float v1, float v2, float v3)
@@ -288,12 +284,6 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
     auto issue_slice = [&](int buf) {
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
-#ifdef RAMP_ABL_NOLOADX
-            if (wave + s * NWAVE < TT::X_FRAGS) continue;
-#endif
-#ifdef RAMP_ABL_NOLOADW
-            if (wave + s * NWAVE >= TT::X_FRAGS) continue;
-#endif
             load_to_lds_16B(gptr[s], &lds[buf * TT::BUF_ELEMS + (wave + s * NWAVE) * kFragElems]);
             gptr[s] += gstep[s];
         }
@@ -391,9 +381,6 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
         wait_for_next(min(NSTAGE - 1, KT - 1));
         __builtin_amdgcn_s_barrier();
         read_frags(0, 0, 0);
-#ifdef RAMP_ABL_NOLDS
-        read_frags(1, 0, 1);
-#endif
         int buf_cur = 0;
         for (int kt = 0; kt < KT; ++kt) {
             const int buf_next = (buf_cur + 1 == NSTAGE) ? 0 : buf_cur + 1;
@@ -401,20 +388,14 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
             for (int ks = 0; ks < KS; ++ks) {
                 const int cur = ks & 1, nxt = cur ^ 1;
                 if (ks + 1 < KS) {
-#ifndef RAMP_ABL_NOLDS
                     read_frags(nxt, buf_cur, ks + 1);
-#endif
                 } else if (kt + 1 < KT) {
                     // every fragment of slice kt is in registers by now (requested one k-step ago)
                     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): no LDS read of this buffer pending
                     wait_for_next(min(NSTAGE - 2, KT - 2 - kt));
                     __builtin_amdgcn_s_barrier();
-#ifndef RAMP_ABL_NOLOAD
                     if (kt + NSTAGE < KT) issue_slice(buf_cur);
-#endif
-#ifndef RAMP_ABL_NOLDS
                     read_frags(nxt, buf_next, 0);
-#endif
                 }
                 mfma_step(cur);
             }
@@ -444,9 +425,6 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
     }
 
     // ---- epilogue: lane holds features f = fblock*16 + 4*q + {0..3} of token n = r16 ----
-#ifdef RAMP_ABL_NOSTORE
-    if (acc[0][0][0] != 12345.678f) return;
-#endif
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int tr = (wm * NB + nb) * 16 + r16;

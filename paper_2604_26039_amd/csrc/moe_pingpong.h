@@ -354,11 +354,6 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         // ---- epilogue: lane holds features fblock*16 + 4*q + {0..3} of token r16.  It runs while the other group
         // is in a C phase; the stores are not waited for here.
         const int f0 = n_tile * FEAT_PER_TILE;
-#ifdef RAMP_ABL_NOSTORE
-        const bool abl_skip = acc[0][0][0] != 12345.678f;
-#else
-        const bool abl_skip = false;
-#endif
         if (STAGE == 2 && a.y_bf16) {
             // bf16 per-pair rows leave through LDS: a lane holds 16 consecutive features of one token, but a store
             // instruction should cover whole 128-byte lines.  Per chunk of two token blocks the wavefront writes its
@@ -369,7 +364,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             uint16_t *ybase = reinterpret_cast<uint16_t *>(a.y_out) + f0 + wn * (FB * 16) + (lane & 7) * 8;
 #pragma unroll
             for (int c2 = 0; c2 < NB / 2; ++c2) {
-                if (2 * c2 >= nb_valid || abl_skip) continue;
+                if (2 * c2 >= nb_valid) continue;
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     const int nb = 2 * c2 + h;
@@ -397,7 +392,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         } else {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            if (nb >= nb_valid || abl_skip) continue;
+            if (nb >= nb_valid) continue;
             const int slot = m_tile * BM + (wm * NB + nb) * 16 + r16;
             const int rb0 = f0 / 16 + wn * FB;
             if (STAGE == 1) {
