@@ -33,7 +33,7 @@ MFMA_PEAK_PFLOPS = 2.5   # dense bf16
 # counter reads for the library's 1 GiB copy kernel: x2.000 and x1.000); the runs and their
 # per-kernel tables are kept as text under profiles/.  Keyed by (model, T, beta); other workloads
 # report null until they have been measured the same way.
-MEASURED_TRAFFIC_BYTES = {("olmoe", 4096, "1.0"): 1030.5e6 + 68.1e6}
+MEASURED_TRAFFIC_BYTES = {("olmoe", 4096, "1.0"): 1017.4e6 + 68.1e6}
 
 
 def log(*a):
