@@ -112,6 +112,7 @@ __device__ void block_scan_and_emit(int n_e, int E, int bm, int cap, int dropped
 __device__ void block_scatter_chunk(const int32_t *ids, int base, int P, int E, int *cursor, unsigned *wcnt,
                                     unsigned stamp, int32_t *sorted)
 {
+    const int ebits = 32 - __clz((E - 1) | 1);  // bits that tell the experts apart
     const int lane = lane_id(), wv = threadIdx.x >> 6;
     const int p = base + (int)threadIdx.x;
     int e = -1;
@@ -119,28 +120,27 @@ __device__ void block_scatter_chunk(const int32_t *ids, int base, int P, int E, 
         int v = ids[p];
         if (v >= 0 && v < E) e = v;
     }
-    int rank = 0;
-    bool pending = (e >= 0);
-    // One round per distinct expert in the wavefront: the first pending lane names its expert
-    // (scalar read, no cross-lane traffic), all pending lanes with that expert take their rank
-    // from the ballot and retire together.
-    while (__ballot(pending) != 0) {
-        if (pending) {
-            const int e0 = __builtin_amdgcn_readfirstlane(e);
-            const unsigned long long same = __ballot(e == e0);  // among the pending lanes
-            if (e == e0) {
-                rank = __popcll(same & ((1ull << lane) - 1ull));
-                if (rank == 0) wcnt[wv * E + e0] = (stamp << 8) | (unsigned)__popcll(same);
-                pending = false;
-            }
+    // Lanes of this wavefront with the same expert, without a loop over the distinct experts: one
+    // ballot per bit of the expert index, each lane keeping the side of the ballot its own bit is on.
+    const unsigned long long valid = __ballot(e >= 0);
+    unsigned long long same = valid;
+#pragma unroll
+    for (int b = 0; b < 10; ++b) {  // E <= 1024
+        if (b < ebits) {
+            const bool bit = (e >> b) & 1;
+            const unsigned long long m = __ballot(e >= 0 && bit);
+            same &= bit ? m : ~m;
         }
     }
+    const int rank = __popcll(same & ((1ull << lane) - 1ull));
+    if (e >= 0 && rank == 0) wcnt[wv * E + e] = (stamp << 8) | (unsigned)__popcll(same);
     __syncthreads();
     if (e >= 0) {
         int before = 0;
-        for (int w = 0; w < wv; ++w) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
             unsigned v = wcnt[w * E + e];
-            if ((v >> 8) == stamp) before += (int)(v & 0xffu);
+            if (w < wv && (v >> 8) == stamp) before += (int)(v & 0xffu);
         }
         sorted[cursor[e] + before + rank] = p;
     }
