@@ -221,7 +221,7 @@ def main():
 
     def step(i):
         t0s = time.perf_counter()
-        c = dispatcher.select(d_ids)            # histogram kernel, E counts to the host, Eq. 6 argmin
+        c = dispatcher.select(d_ids)            # histogram + Eq. 6 + argmin on the device, result polled in pinned memory
         t_select[0] += time.perf_counter() - t0s
         if fixed_cfg is not None:
             c = fixed_cfg
@@ -255,14 +255,37 @@ def main():
     cfg_head = fam.cfgs[chosen_log[-1]]
     # the layer alone with the dispatched configuration (no histogram / select), HIP events per call
     fused_us = tuner.time_config(layers, cfg_head, p, warmup=5, iters=args.iters)
-    # dispatch latency on an idle GPU: histogram launch + E-count copy + host sync + Eq. 6 argmin
+    # dispatch latency on an idle GPU, device-resident select (one enqueue, ticket polled in pinned host memory)
+    # next to the host-side select (histogram kernel, E-count copy, stream synchronisation, model on the host)
     torch.cuda.synchronize()
-    lat = []
-    for _ in range(50):
+
+    def idle_latency(fn):
+        lat = []
+        for _ in range(50):
+            t0s = time.perf_counter()
+            fn(d_ids)
+            lat.append(time.perf_counter() - t0s)
+        return float(np.median(lat)) * 1e6
+
+    dispatch_idle_us = idle_latency(dispatcher.select)
+    dispatch_host_idle_us = idle_latency(dispatcher.select_host)
+    if dispatcher.select(d_ids) != dispatcher.select_host(d_ids):
+        raise RuntimeError("device-resident select and host select disagree on the headline histogram")
+    # the same K steps with the selection taken off the critical path: every call enqueues its selection and
+    # launches with the choice of the latest finished one (the previous call's here)
+    async_us = None
+    if fixed_cfg is None:
+        def step_async(i):
+            c = dispatcher.select_async(d_ids)
+            ramp.fused_moe(rs, fam.cfgs[c], X, d_ids, d_w, layers.packed[i % layers.n_layers], out, ws)
+        for i in range(args.warmup):
+            step_async(i)
+        torch.cuda.synchronize()
         t0s = time.perf_counter()
-        dispatcher.select(d_ids)
-        lat.append(time.perf_counter() - t0s)
-    dispatch_idle_us = float(np.median(lat)) * 1e6
+        for i in range(args.steps):
+            step_async(i)
+        torch.cuda.synchronize()
+        async_us = (time.perf_counter() - t0s) / args.steps * 1e6
 
     # roofline of the dominant kernel (up-projection + SwiGLU): algorithmic flops / bytes per launch
     P = T_head * s.k
@@ -283,9 +306,11 @@ def main():
                  frac=max(t_hbm, t_mfma) / (ms_per_step * 1e3), tflops=flops / (ms_per_step * 1e3) * 1e-6,
                  gbs=nbytes / (ms_per_step * 1e3) * 1e-3, fused_layer_us=fused_us,
                  fused_layer_frac=max(t_hbm, t_mfma) / fused_us, dispatch_idle_us=dispatch_idle_us,
+                 dispatch_host_select_idle_us=dispatch_host_idle_us, async_dispatch_us_per_step=async_us,
                  paper_dispatch_us_h200=38.0)
     log(f"[bench] headline T={T_head} beta={beta_head}: {ms_per_step * 1e3:.1f} us/step (fused layer alone {fused_us:.1f} us, "
-        f"dispatch on an idle GPU {dispatch_idle_us:.1f} us), config {cfg_head}, "
+        f"dispatch on an idle GPU {dispatch_idle_us:.1f} us device-resident / {dispatch_host_idle_us:.1f} us host select, "
+        f"{async_us if async_us is None else round(async_us, 1)} us/step with asynchronous dispatch), config {cfg_head}, "
         f"dominant kernel {k_us:.1f} us = {roof['achieved']:.1f} {roof['unit']} ({100 * roof['frac']:.1f}% of peak)")
 
     # ------------------------------------------------------------------ CPU oracle baseline (bounded sample)

@@ -179,6 +179,42 @@ int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int3
                            const int32_t *wave_cap, const float *theta,
                            const int32_t *expert_counts, int flags, int *best_idx, double *pred_us);
 
+/* ---- device-resident dispatch (Sec. 4.4 steps 1-3 in one enqueue; Sec. 5 "dispatch overhead") ----
+ * ramp_cost_model_select needs the histogram on the host: a device-to-host copy and a stream
+ * synchronisation on every call.  ramp_select_device instead enqueues the histogram and one small
+ * kernel that evaluates the model for every configuration on the device (fp64, the operation order of
+ * ramp_cost_model_select, lowest index among equal predictions) and writes the outcome into a result
+ * block.  When that block is pinned host memory the host learns the choice by polling its first word
+ * (ramp_select_poll / ramp_select_wait): no copy, no stream synchronisation.  A caller that must not
+ * wait at all enqueues the selection of this call, launches the fused layer with the configuration the
+ * previous call's selection produced, and reads the new result later with ramp_select_poll.
+ *
+ * Table (device memory, built once on the host and copied by the caller):
+ *   ramp_select_table_build writes ramp_select_table_bytes(n_cfg) bytes: a 128-byte header
+ *   {int32 magic, n_cfg, n_bm, flags, bm[28]} (the distinct bm values) followed by n_cfg rows of 32
+ *   bytes {int32 bm_slot, ntiles, wave_cap, 0; float theta[4]}.  At most 28 distinct bm, n_cfg <= 1024.
+ * Result block (ramp_select_result_bytes(E, n_cfg) bytes, 8-byte aligned, written by the kernel):
+ *   uint64 ticket | int32 best | int32 n_cfg | double pred_us[n_cfg] | int32 expert_counts[E]
+ *   The ticket (the caller's, nonzero, different from what the block held before) is stored last
+ *   with system-scope release ordering: once it reads back, the rest of the block is complete.
+ * ws: ramp_align_workspace_bytes(T,k,E) bytes of device scratch (unused up to 2048 pairs).
+ * best_idx_dev: optional device int that also receives the index (for launches that test it on the
+ *   device).  Calls that share ws or a result block must be ordered by the caller. */
+size_t ramp_select_table_bytes(int n_cfg);
+int ramp_select_table_build(int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
+                            const int32_t *wave_cap, const float *theta /*host [n_cfg,4]*/, int flags,
+                            void *table /*host out*/, size_t table_bytes);
+size_t ramp_select_result_bytes(int E, int n_cfg);
+int ramp_select_device(const int32_t *topk_ids /*dev [T*k]*/, int T, int k, int E, int n_cfg,
+                       const void *table /*dev*/, void *result /*pinned host or dev*/,
+                       unsigned long long ticket, int32_t *best_idx_dev /*dev, may be NULL*/,
+                       void *ws /*dev*/, size_t ws_bytes, void *stream);
+/* Host side of the result block.  ramp_select_poll returns RAMP_OK and *best_idx once the block
+ * carries `ticket`, 1 if it does not yet (not an error).  ramp_select_wait spins on it for at most
+ * timeout_s seconds (then RAMP_EHIP).  Neither touches the HIP runtime. */
+int ramp_select_poll(const void *result_host, unsigned long long ticket, int *best_idx);
+int ramp_select_wait(const void *result_host, unsigned long long ticket, double timeout_s, int *best_idx);
+
 /* ---- measurement hooks --------------------------------------------------------------------------
  * ramp_probe_enable(stage): from now on every ramp_fused_moe call of this process records a
  * HIP event pair on its stream around one stage (1 = align, 2 = up-projection + SwiGLU,

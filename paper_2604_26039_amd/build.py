@@ -18,7 +18,7 @@ CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libramp.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ["align.hip", "pack.hip", "fused.hip", "gemm_group0.hip", "gemm_group1.hip", "gemm_group2.hip",
+SOURCES = ["align.hip", "select.hip", "pack.hip", "fused.hip", "gemm_group0.hip", "gemm_group1.hip", "gemm_group2.hip",
            "gemm_group3.hip", "gemm_group4.hip", "gemm_group5.hip", "gemm_group6.hip", "gemm_group7.hip", "stream_group0.hip", "stream_group1.hip", "stream_group2.hip", "cost_model.cpp"]
 HEADERS = ["ramp_internal.h", "moe_gemm.h", "moe_pingpong.h", "moe_stream.h", "config_list.h", os.path.join(ROOT, "include", "ramp.h")]
 

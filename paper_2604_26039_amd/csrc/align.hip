@@ -360,6 +360,23 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
     return check_launch("align_scan_scatter_kernel");
 }
 
+// Per-chunk histograms only (block_counts[B][E] at the start of ws), for the device-resident dispatch kernel.
+int launch_chunk_histograms(const int32_t *ids, int P, int E, void *ws, size_t ws_bytes, hipStream_t stream, int *B_out)
+{
+    const int B = num_blocks(P);
+    const size_t need = (size_t)(2 * (size_t)B * E + B) * sizeof(int32_t);
+    if (!ws || ws_bytes < need) {
+        set_error("select: workspace %zu < %zu bytes (size it with ramp_align_workspace_bytes)", ws_bytes, need);
+        return RAMP_ENOSPC;
+    }
+    int32_t *block_counts = static_cast<int32_t *>(ws);
+    int32_t *block_dropped = block_counts + 2 * (size_t)B * E;
+    hipLaunchKernelGGL(align_hist_kernel, dim3(B), dim3(NT), (E + 1) * sizeof(int), stream, ids, P, E, 0,
+                       static_cast<int32_t *>(nullptr), block_counts, block_dropped, 0);
+    *B_out = B;
+    return check_launch("align_hist_kernel");
+}
+
 int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
                  int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream)
 {

@@ -89,6 +89,18 @@ def lib() -> ctypes.CDLL:
         L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp, vp, ci, vp]
         L.ramp_cost_model_select.restype = ci
         L.ramp_cost_model_select.argtypes = [ci, ci, cp, vp, vp, vp, vp, ci, ctypes.POINTER(ci), vp]
+        L.ramp_select_table_bytes.restype = sz
+        L.ramp_select_table_bytes.argtypes = [ci]
+        L.ramp_select_table_build.restype = ci
+        L.ramp_select_table_build.argtypes = [ci, cp, vp, vp, vp, ci, vp, sz]
+        L.ramp_select_result_bytes.restype = sz
+        L.ramp_select_result_bytes.argtypes = [ci, ci]
+        L.ramp_select_device.restype = ci
+        L.ramp_select_device.argtypes = [i32p, ci, ci, ci, ci, vp, vp, ctypes.c_ulonglong, vp, vp, sz, vp]
+        L.ramp_select_poll.restype = ci
+        L.ramp_select_poll.argtypes = [vp, ctypes.c_ulonglong, ctypes.POINTER(ci)]
+        L.ramp_select_wait.restype = ci
+        L.ramp_select_wait.argtypes = [vp, ctypes.c_ulonglong, ctypes.c_double, ctypes.POINTER(ci)]
         L.ramp_probe_enable.restype = ci
         L.ramp_probe_enable.argtypes = [ci]
         L.ramp_probe_read.restype = ci
@@ -103,7 +115,8 @@ EXPORTS = [
     "ramp_last_error", "ramp_num_configs", "ramp_get_config", "ramp_config_ntiles", "ramp_config_wave_capacity",
     "ramp_align_capacity", "ramp_align_workspace_bytes", "ramp_moe_histogram", "ramp_moe_align", "ramp_pack_bytes",
     "ramp_pack_weights", "ramp_fused_moe_workspace_bytes", "ramp_fused_moe_workspace_layout", "ramp_fused_moe",
-    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_copy_bytes", "ramp_probe_enable", "ramp_probe_read",
+    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_select_table_bytes", "ramp_select_table_build",
+    "ramp_select_result_bytes", "ramp_select_device", "ramp_select_poll", "ramp_select_wait", "ramp_copy_bytes", "ramp_probe_enable", "ramp_probe_read",
 ]
 
 
@@ -268,3 +281,55 @@ def cost_model_select(E: int, cfgs: Sequence[Config], ntiles, wave_cap, theta, e
     _check(lib().ramp_cost_model_select(E, n, arr, nt.ctypes.data, wc.ctypes.data, th.ctypes.data, counts.ctypes.data,
                                         flags, ctypes.byref(best), pred.ctypes.data if want_pred else None))
     return (best.value, pred) if want_pred else best.value
+
+
+# ----------------------------------------------------------------------------- device-resident dispatch
+
+def select_table_build(cfgs: Sequence[Config], ntiles, wave_cap, theta, flags: int = CM_EQ6) -> np.ndarray:
+    """Host image (uint8) of the table ramp_select_device reads; copy it to the device once."""
+    n = len(cfgs)
+    arr = (Config * n)(*cfgs)
+    nt, wc = _np(ntiles, np.int32), _np(wave_cap, np.int32)
+    th = _np(theta, np.float32).reshape(n, 4)
+    table = np.zeros(lib().ramp_select_table_bytes(n), np.uint8)
+    _check(lib().ramp_select_table_build(n, arr, nt.ctypes.data, wc.ctypes.data, th.ctypes.data, flags,
+                                         table.ctypes.data, table.nbytes))
+    return table
+
+
+def select_result_bytes(E: int, n_cfg: int) -> int:
+    return lib().ramp_select_result_bytes(E, n_cfg)
+
+
+def select_device(topk_ids, T: int, k: int, E: int, n_cfg: int, table: torch.Tensor, result: torch.Tensor, ticket: int,
+                  ws: Optional[torch.Tensor], best_idx_dev: Optional[torch.Tensor] = None, stream=None):
+    """result: pinned host tensor (polled with select_poll / select_wait) or a device tensor."""
+    assert result.is_contiguous() and (result.is_cuda or result.is_pinned())
+    _check(lib().ramp_select_device(_dev(topk_ids), T, k, E, n_cfg, _dev(table), result.data_ptr(), ticket,
+                                    _dev(best_idx_dev), _dev(ws), ws.numel() * ws.element_size() if ws is not None else 0,
+                                    _stream(stream)))
+
+
+def select_poll(result: torch.Tensor, ticket: int) -> Optional[int]:
+    """Index chosen by the enqueue that carried `ticket`, or None while it has not finished."""
+    best = ctypes.c_int(-1)
+    rc = lib().ramp_select_poll(result.data_ptr(), ticket, ctypes.byref(best))
+    if rc < 0:
+        _check(rc)
+    return best.value if rc == 0 else None
+
+
+def select_wait(result: torch.Tensor, ticket: int, timeout_s: float = 10.0) -> int:
+    best = ctypes.c_int(-1)
+    _check(lib().ramp_select_wait(result.data_ptr(), ticket, timeout_s, ctypes.byref(best)))
+    return best.value
+
+
+def select_result_unpack(result: torch.Tensor, E: int, n_cfg: int):
+    """(ticket, best, pred_us [n_cfg] fp64, expert_counts [E]) from a host copy of a result block."""
+    raw = result.cpu().numpy().view(np.uint8)
+    ticket = int(raw[:8].view(np.uint64)[0])
+    best, n = (int(v) for v in raw[8:16].view(np.int32))
+    pred = raw[16:16 + 8 * n_cfg].view(np.float64).copy()
+    counts = raw[16 + 8 * n_cfg:16 + 8 * n_cfg + 4 * E].view(np.int32).copy()
+    return ticket, best, pred, counts

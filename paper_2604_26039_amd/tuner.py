@@ -183,15 +183,23 @@ def select(fam: Family, theta: np.ndarray, counts: np.ndarray, flags: int = ramp
 
 
 class Dispatcher:
-    """Runtime dispatch (Sec. 4.4): histogram kernel -> E counts to pinned host memory -> one
-    ramp_cost_model_select call.  All marshalling is done once here so a step costs two library
-    calls, one small device-to-host copy and one stream synchronisation."""
+    """Runtime dispatch (Sec. 4.4).  Three ways to get from the routing of a call to a configuration index:
+
+    select()        device-resident: one enqueue (histogram + model + argmin on the device), the result lands in
+                    pinned host memory and the host polls its ticket word.  No copy, no stream synchronisation.
+    select_async()  never waits: enqueues the selection for this call's routing and returns the choice of the
+                    latest selection that has already finished (the previous call's, in a steady stream of calls
+                    of one batch size; the first call waits once).
+    select_host()   histogram kernel -> E counts copied to pinned host memory -> stream synchronisation ->
+                    ramp_cost_model_select on the host.
+    All marshalling is done once here."""
 
     def __init__(self, fam: Family, theta: np.ndarray, flags: int, T: int, device="cuda:0"):
         import ctypes
         self.fam, self.flags, self.T = fam, flags, T
         s = fam.shape
         self.E, self.k = s.E, s.k
+        self.n_cfg = len(fam.cfgs)
         self._cfgs = (ramp.Config * len(fam.cfgs))(*fam.cfgs)
         self._nt = np.ascontiguousarray(fam.ntiles, np.int32)
         self._wc = np.ascontiguousarray(fam.wave_cap, np.int32)
@@ -203,12 +211,64 @@ class Dispatcher:
         self._best = ctypes.c_int(-1)
         self._best_ref = ctypes.byref(self._best)
         self._lib = ramp.lib()
+        # device-resident path: table on the device, two result blocks in pinned host memory used in turn
+        self.table = torch.from_numpy(ramp.select_table_build(fam.cfgs, fam.ntiles, fam.wave_cap, theta, flags)).to(device)
+        nbytes = ramp.select_result_bytes(self.E, self.n_cfg)
+        self.results = [torch.zeros(nbytes, dtype=torch.uint8).pin_memory() for _ in range(2)]
+        self._res_ptr = [r.data_ptr() for r in self.results]
+        self._table_ptr, self._ws_ptr, self._ws_bytes = self.table.data_ptr(), self.ws.data_ptr(), self.ws.numel()
+        self.ticket = 0
+        self.cached = None
+
+    def _enqueue(self, d_ids: torch.Tensor) -> int:
+        self.ticket += 1
+        rc = self._lib.ramp_select_device(d_ids.data_ptr(), self.T, self.k, self.E, self.n_cfg, self._table_ptr,
+                                          self._res_ptr[self.ticket & 1], self.ticket, None, self._ws_ptr,
+                                          self._ws_bytes, torch.cuda.current_stream().cuda_stream)
+        if rc != ramp.OK:
+            raise ramp.RampError(rc, ramp.last_error())
+        return self.ticket
 
     def select(self, d_ids: torch.Tensor) -> int:
+        t = self._enqueue(d_ids)
+        rc = self._lib.ramp_select_wait(self._res_ptr[t & 1], t, 10.0, self._best_ref)
+        if rc != ramp.OK:
+            raise ramp.RampError(rc, ramp.last_error())
+        self.cached = self._best.value
+        return self.cached
+
+    def select_async(self, d_ids: torch.Tensor) -> int:
+        prev = self.ticket
+        if prev and self._lib.ramp_select_poll(self._res_ptr[prev & 1], prev, self._best_ref) == 0:
+            self.cached = self._best.value
+        t = self._enqueue(d_ids)
+        if self.cached is None:  # nothing has finished yet (first call): wait once
+            rc = self._lib.ramp_select_wait(self._res_ptr[t & 1], t, 10.0, self._best_ref)
+            if rc != ramp.OK:
+                raise ramp.RampError(rc, ramp.last_error())
+            self.cached = self._best.value
+        return self.cached
+
+    def begin_step(self):
+        """Per-step cache (Sec. 4.4): the first select_step() of a step dispatches on its own routing, the later
+        layers of the step reuse that choice (this dispatcher serves one batch size, the cache key of the paper)."""
+        self._step_choice = None
+
+    def select_step(self, d_ids: torch.Tensor) -> int:
+        if getattr(self, "_step_choice", None) is None:
+            self._step_choice = self.select(d_ids)
+        return self._step_choice
+
+    def last_counts(self) -> np.ndarray:
+        """Expert histogram of the latest finished selection (from its result block)."""
+        t = self.ticket
+        return ramp.select_result_unpack(self.results[t & 1], self.E, self.n_cfg)[3]
+
+    def select_host(self, d_ids: torch.Tensor) -> int:
         stream = torch.cuda.current_stream()
         ramp.moe_histogram(d_ids, self.T, self.k, self.E, self.d_counts, self.ws, stream)
         self.h_counts.copy_(self.d_counts, non_blocking=True)
-        stream.synchronize()  # the path's one host sync
+        stream.synchronize()  # this path's one host sync
         rc = self._lib.ramp_cost_model_select(self.E, len(self.fam.cfgs), self._cfgs, self._nt.ctypes.data,
                                               self._wc.ctypes.data, self._theta.ctypes.data, self._h_ptr, self.flags,
                                               self._best_ref, None)

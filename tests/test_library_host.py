@@ -195,3 +195,40 @@ def test_mi355x_model_fit_and_select_match_oracle():
         ramp.cost_model_fit(wc, g, t, distinct=u, pairs=None, flags=flags)   # pair counts required
     with pytest.raises(ramp.RampError):
         ramp.cost_model_fit(wc, g, t, distinct=u, pairs=P, flags=flags | 64)  # unknown flag
+
+
+def test_select_table_layout_and_host_polling():
+    """Host pieces of the device-resident dispatch: the table image follows the documented layout and the
+    poll / wait calls read a result block without touching the GPU."""
+    sh = shape_of("olmoe", 256)
+    cfgs = ramp.configs(sh)
+    n = len(cfgs)
+    nt = np.array([ramp.config_ntiles(sh, c) for c in cfgs], np.int32)
+    wc = np.array([ramp.config_wave_capacity(c) for c in cfgs], np.int32)
+    theta = np.arange(4 * n, dtype=np.float32).reshape(n, 4)
+    table = ramp.select_table_build(cfgs, nt, wc, theta, flags=10)
+    assert table.nbytes == 128 + 32 * n == ramp.lib().ramp_select_table_bytes(n)
+    hdr = table[:128].view(np.int32)
+    assert hdr[1] == n and hdr[3] == 10
+    bms = list(hdr[4:4 + hdr[2]])
+    assert sorted(bms) == sorted({c.bm for c in cfgs}) and len(set(bms)) == len(bms)
+    rows = table[128:].reshape(n, 32)
+    ints = rows[:, :16].copy().view(np.int32).reshape(n, 4)
+    assert [bms[i] for i in ints[:, 0]] == [c.bm for c in cfgs]
+    assert np.array_equal(ints[:, 1], nt) and np.array_equal(ints[:, 2], wc)
+    assert np.array_equal(rows[:, 16:].copy().view(np.float32).reshape(n, 4), theta)
+    with pytest.raises(ramp.RampError):
+        ramp.select_table_build(cfgs, nt, np.zeros(n, np.int32), theta)   # wave capacity must be positive
+    # result block: ticket | best | n_cfg | pred | counts
+    nbytes = ramp.select_result_bytes(sh.E, n)
+    assert nbytes >= 16 + 8 * n + 4 * sh.E and nbytes % 64 == 0
+    import ctypes
+    block = np.zeros(nbytes, np.uint8)
+    best = ctypes.c_int(-1)
+    L = ramp.lib()
+    assert L.ramp_select_poll(block.ctypes.data, 5, ctypes.byref(best)) == 1      # not there yet
+    assert L.ramp_select_wait(block.ctypes.data, 5, 0.05, ctypes.byref(best)) == ramp.EHIP   # bounded wait
+    block[8:12] = np.array([23], np.int32).view(np.uint8)
+    block[:8] = np.array([5], np.uint64).view(np.uint8)
+    assert L.ramp_select_poll(block.ctypes.data, 5, ctypes.byref(best)) == 0 and best.value == 23
+    assert L.ramp_select_wait(block.ctypes.data, 5, 0.05, ctypes.byref(best)) == 0 and best.value == 23
