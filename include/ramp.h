@@ -194,10 +194,11 @@ int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int3
  *   {int32 magic, n_cfg, n_bm, flags, bm[28]} (the distinct bm values) followed by n_cfg rows of 32
  *   bytes {int32 bm_slot, ntiles, wave_cap, 0; float theta[4]}.  At most 28 distinct bm, n_cfg <= 1024.
  * Result block (ramp_select_result_bytes(E, n_cfg) bytes, 8-byte aligned, written by the kernel):
- *   uint64 ticket | int32 best | int32 n_cfg | double pred_us[n_cfg] | int32 expert_counts[E]
- *   The ticket (the caller's, nonzero, different from what the block held before) is stored last
- *   with system-scope release ordering: once it reads back, the rest of the block is complete.
- * ws: ramp_align_workspace_bytes(T,k,E) bytes of device scratch (unused up to 2048 pairs).
+ *   uint64 word = best << 32 | ticket | int32 n_cfg | int32 0 | double pred_us[n_cfg] | int32 expert_counts[E]
+ *   The word carries the caller's ticket (nonzero, different from what the block held before) and the
+ *   chosen index in one 64-bit store, made last with system-scope release ordering after a single fence:
+ *   once the ticket reads back, the index is there and the rest of the block is complete.
+ * ws: ramp_align_workspace_bytes(T,k,E) bytes of device scratch (unused up to 8192 pairs).
  * best_idx_dev: optional device int that also receives the index (for launches that test it on the
  *   device).  Calls that share ws or a result block must be ordered by the caller. */
 size_t ramp_select_table_bytes(int n_cfg);
@@ -207,13 +208,13 @@ int ramp_select_table_build(int n_cfg, const ramp_config *cfgs, const int32_t *n
 size_t ramp_select_result_bytes(int E, int n_cfg);
 int ramp_select_device(const int32_t *topk_ids /*dev [T*k]*/, int T, int k, int E, int n_cfg,
                        const void *table /*dev*/, void *result /*pinned host or dev*/,
-                       unsigned long long ticket, int32_t *best_idx_dev /*dev, may be NULL*/,
+                       uint32_t ticket, int32_t *best_idx_dev /*dev, may be NULL*/,
                        void *ws /*dev*/, size_t ws_bytes, void *stream);
 /* Host side of the result block.  ramp_select_poll returns RAMP_OK and *best_idx once the block
  * carries `ticket`, 1 if it does not yet (not an error).  ramp_select_wait spins on it for at most
  * timeout_s seconds (then RAMP_EHIP).  Neither touches the HIP runtime. */
-int ramp_select_poll(const void *result_host, unsigned long long ticket, int *best_idx);
-int ramp_select_wait(const void *result_host, unsigned long long ticket, double timeout_s, int *best_idx);
+int ramp_select_poll(const void *result_host, uint32_t ticket, int *best_idx);
+int ramp_select_wait(const void *result_host, uint32_t ticket, double timeout_s, int *best_idx);
 
 /* ---- measurement hooks --------------------------------------------------------------------------
  * ramp_probe_enable(stage): from now on every ramp_fused_moe call of this process records a

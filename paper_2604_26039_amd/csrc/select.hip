@@ -15,6 +15,7 @@ namespace {
 constexpr int NT = 1024;
 constexpr int NW = NT / kWave;
 constexpr int kMaxBm = 28;  // distinct bm values a table can hold
+constexpr int kSingleMaxP = 8192;  // up to this many pairs the select kernel makes the histogram itself
 
 // Table in device memory (built on the host by ramp_select_table_build).
 struct TableHeader {
@@ -28,16 +29,16 @@ struct TableRow {
 static_assert(sizeof(TableHeader) == 128 && sizeof(TableRow) == 32, "table layout is part of the ABI");
 constexpr int32_t kMagic = 0x52614d50;
 
-// Result block: ticket (written last) | best | n_cfg | pred_us[n_cfg] (fp64) | counts[E]
+// Result block: word = best << 32 | ticket (one 64-bit store, written last) | n_cfg | 0 | pred_us[n_cfg] (fp64) | counts[E]
 struct ResultHeader {
-    unsigned long long ticket;
-    int32_t best, n_cfg;
+    unsigned long long word;
+    int32_t n_cfg, reserved;
 };
 static_assert(sizeof(ResultHeader) == 16, "result layout is part of the ABI");
 
 __global__ __launch_bounds__(NT) void select_kernel(const int32_t *ids, int P, int B, const int32_t *block_counts, int E,
-                                                    const TableHeader *table, ResultHeader *res,
-                                                    unsigned long long ticket, int32_t *best_dev)
+                                                    const TableHeader *table, ResultHeader *res, uint32_t ticket,
+                                                    int32_t *best_dev)
 {
     __shared__ int hist[kAlignMaxE];
     __shared__ int mt[kMaxBm];
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(NT) void select_kernel(const int32_t *ids, int P, i
         }
         __syncthreads();
     }
-    if (tid < E) counts_out[tid] = n;
+    if (tid < E) hist[tid] = n;
     // ---- sums over the experts: M-tiles for every distinct bm, active experts, routed pairs
     if ((tid & ~63) < E) {  // wavefronts that hold experts
         for (int j = 0; j < n_bm + 2; ++j) {
@@ -84,7 +85,6 @@ __global__ __launch_bounds__(NT) void select_kernel(const int32_t *ids, int P, i
             if (lane == 0) atomicAdd(j < n_bm ? &mt[j] : &active_pairs[j - n_bm], v);
         }
     }
-    __threadfence_system();  // this lane's part of the result block is visible to the host before the ticket
     __syncthreads();
     if (tid >= kWave) return;
     // ---- the model for every configuration, and the lowest index with the smallest prediction
@@ -118,14 +118,18 @@ __global__ __launch_bounds__(NT) void select_kernel(const int32_t *ids, int P, i
             best_t = ot;
         }
     }
-    __threadfence_system();
+    // Only this wavefront writes the result block: payload, one system-scope fence (one round trip to host
+    // memory), then the word that carries the ticket.
+    for (int e = lane; e < E; e += kWave) counts_out[e] = hist[e];
     if (lane == 0) {
-        res->best = best;
         res->n_cfg = n_cfg;
+        res->reserved = 0;
         if (best_dev) *best_dev = best;
-        __threadfence_system();
-        __hip_atomic_store(&res->ticket, ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
+    __threadfence_system();
+    if (lane == 0)
+        __hip_atomic_store(&res->word, ((unsigned long long)(uint32_t)best << 32) | ticket, __ATOMIC_RELEASE,
+                           __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 }  // namespace
@@ -185,8 +189,8 @@ extern "C" size_t ramp_select_result_bytes(int E, int n_cfg)
 }
 
 extern "C" int ramp_select_device(const int32_t *topk_ids, int T, int k, int E, int n_cfg, const void *table,
-                                  void *result, unsigned long long ticket, int32_t *best_idx_dev, void *ws,
-                                  size_t ws_bytes, void *stream)
+                                  void *result, uint32_t ticket, int32_t *best_idx_dev, void *ws, size_t ws_bytes,
+                                  void *stream)
 {
     using namespace ramp;
     if (T < 0 || k < 0 || E <= 0 || E > kAlignMaxE || n_cfg <= 0 || n_cfg > 1024 || !table || !result || ticket == 0) {
@@ -201,7 +205,7 @@ extern "C" int ramp_select_device(const int32_t *topk_ids, int T, int k, int E, 
     const int P = (int)P64;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int B = 0;
-    if (P > kAlignSingleMaxP) {
+    if (P > kSingleMaxP) {
         if (int rc = launch_chunk_histograms(topk_ids, P, E, ws, ws_bytes, s, &B)) return rc;
     }
     hipLaunchKernelGGL(select_kernel, dim3(1), dim3(NT), 0, s, topk_ids, P, B, static_cast<const int32_t *>(ws), E,
@@ -210,19 +214,20 @@ extern "C" int ramp_select_device(const int32_t *topk_ids, int T, int k, int E, 
     return check_launch("select_kernel");
 }
 
-extern "C" int ramp_select_poll(const void *result_host, unsigned long long ticket, int *best_idx)
+extern "C" int ramp_select_poll(const void *result_host, uint32_t ticket, int *best_idx)
 {
     if (!result_host || !best_idx) {
         ramp::set_error("select_poll: NULL argument");
         return RAMP_EINVAL;
     }
     const ramp::ResultHeader *r = static_cast<const ramp::ResultHeader *>(result_host);
-    if (__atomic_load_n(&r->ticket, __ATOMIC_ACQUIRE) != ticket) return 1;
-    *best_idx = r->best;
+    const unsigned long long w = __atomic_load_n(&r->word, __ATOMIC_ACQUIRE);
+    if ((uint32_t)w != ticket) return 1;
+    *best_idx = (int32_t)(w >> 32);
     return RAMP_OK;
 }
 
-extern "C" int ramp_select_wait(const void *result_host, unsigned long long ticket, double timeout_s, int *best_idx)
+extern "C" int ramp_select_wait(const void *result_host, uint32_t ticket, double timeout_s, int *best_idx)
 {
     if (!result_host || !best_idx) {
         ramp::set_error("select_wait: NULL argument");
@@ -234,7 +239,7 @@ extern "C" int ramp_select_wait(const void *result_host, unsigned long long tick
         if (rc <= 0) return rc;
         if ((spin & 0x3ff) == 0 &&
             std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > timeout_s) {
-            ramp::set_error("select_wait: ticket %llu not reached within %.3f s", ticket, timeout_s);
+            ramp::set_error("select_wait: ticket %u not reached within %.3f s", ticket, timeout_s);
             return RAMP_EHIP;
         }
     }

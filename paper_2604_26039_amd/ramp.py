@@ -96,11 +96,11 @@ def lib() -> ctypes.CDLL:
         L.ramp_select_result_bytes.restype = sz
         L.ramp_select_result_bytes.argtypes = [ci, ci]
         L.ramp_select_device.restype = ci
-        L.ramp_select_device.argtypes = [i32p, ci, ci, ci, ci, vp, vp, ctypes.c_ulonglong, vp, vp, sz, vp]
+        L.ramp_select_device.argtypes = [i32p, ci, ci, ci, ci, vp, vp, ctypes.c_uint32, vp, vp, sz, vp]
         L.ramp_select_poll.restype = ci
-        L.ramp_select_poll.argtypes = [vp, ctypes.c_ulonglong, ctypes.POINTER(ci)]
+        L.ramp_select_poll.argtypes = [vp, ctypes.c_uint32, ctypes.POINTER(ci)]
         L.ramp_select_wait.restype = ci
-        L.ramp_select_wait.argtypes = [vp, ctypes.c_ulonglong, ctypes.c_double, ctypes.POINTER(ci)]
+        L.ramp_select_wait.argtypes = [vp, ctypes.c_uint32, ctypes.c_double, ctypes.POINTER(ci)]
         L.ramp_probe_enable.restype = ci
         L.ramp_probe_enable.argtypes = [ci]
         L.ramp_probe_read.restype = ci
@@ -328,8 +328,8 @@ def select_wait(result: torch.Tensor, ticket: int, timeout_s: float = 10.0) -> i
 def select_result_unpack(result: torch.Tensor, E: int, n_cfg: int):
     """(ticket, best, pred_us [n_cfg] fp64, expert_counts [E]) from a host copy of a result block."""
     raw = result.cpu().numpy().view(np.uint8)
-    ticket = int(raw[:8].view(np.uint64)[0])
-    best, n = (int(v) for v in raw[8:16].view(np.int32))
+    word = int(raw[:8].view(np.uint64)[0])
+    ticket, best = word & 0xFFFFFFFF, int(np.int32(word >> 32))
     pred = raw[16:16 + 8 * n_cfg].view(np.float64).copy()
     counts = raw[16 + 8 * n_cfg:16 + 8 * n_cfg + 4 * E].view(np.int32).copy()
     return ticket, best, pred, counts

@@ -221,7 +221,7 @@ class Dispatcher:
         self.cached = None
 
     def _enqueue(self, d_ids: torch.Tensor) -> int:
-        self.ticket += 1
+        self.ticket = self.ticket % 0xFFFFFFFF + 1  # 1 .. 2^32-1; 0 is what an unused result block holds
         rc = self._lib.ramp_select_device(d_ids.data_ptr(), self.T, self.k, self.E, self.n_cfg, self._table_ptr,
                                           self._res_ptr[self.ticket & 1], self.ticket, None, self._ws_ptr,
                                           self._ws_bytes, torch.cuda.current_stream().cuda_stream)

@@ -68,8 +68,9 @@ def oracle_select(fam, theta, counts, flags):
 
 
 CASES = [
-    ("tiny", 16, 0.2), ("olmoe", 1, 1.0), ("olmoe", 16, 0.5), ("olmoe", 256, 1.0),   # 2048 pairs: last single launch
-    ("olmoe", 257, 0.2),                                                              # first chunked size
+    ("tiny", 16, 0.2), ("olmoe", 1, 1.0), ("olmoe", 16, 0.5), ("olmoe", 256, 1.0), ("olmoe", 257, 0.2),
+    ("olmoe", 1024, 0.1),    # 8192 pairs: last size whose histogram the select kernel makes itself
+    ("olmoe", 1025, 1.0),    # first size that takes the chunked histogram launch
     ("olmoe", 4096, 1.0), ("olmoe", 4096, 0.1), ("qwen3", 8192, 0.08), ("qwen3", 32, 0.3),
     ("mixtral", 8192, "zipf1.2"), ("mixtral", 1, 1.0), ("dsv3", 8192, 0.1), ("dsv3", 64, 1.0), ("dsv3", 2048, 0.2),
 ]

@@ -219,7 +219,7 @@ def test_select_table_layout_and_host_polling():
     assert np.array_equal(rows[:, 16:].copy().view(np.float32).reshape(n, 4), theta)
     with pytest.raises(ramp.RampError):
         ramp.select_table_build(cfgs, nt, np.zeros(n, np.int32), theta)   # wave capacity must be positive
-    # result block: ticket | best | n_cfg | pred | counts
+    # result block: word (best << 32 | ticket) | n_cfg | 0 | pred | counts
     nbytes = ramp.select_result_bytes(sh.E, n)
     assert nbytes >= 16 + 8 * n + 4 * sh.E and nbytes % 64 == 0
     import ctypes
@@ -228,7 +228,6 @@ def test_select_table_layout_and_host_polling():
     L = ramp.lib()
     assert L.ramp_select_poll(block.ctypes.data, 5, ctypes.byref(best)) == 1      # not there yet
     assert L.ramp_select_wait(block.ctypes.data, 5, 0.05, ctypes.byref(best)) == ramp.EHIP   # bounded wait
-    block[8:12] = np.array([23], np.int32).view(np.uint8)
-    block[:8] = np.array([5], np.uint64).view(np.uint8)
+    block[:8] = np.array([(23 << 32) | 5], np.uint64).view(np.uint8)
     assert L.ramp_select_poll(block.ctypes.data, 5, ctypes.byref(best)) == 0 and best.value == 23
     assert L.ramp_select_wait(block.ctypes.data, 5, 0.05, ctypes.byref(best)) == 0 and best.value == 23
