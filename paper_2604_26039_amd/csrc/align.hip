@@ -56,13 +56,14 @@ __device__ void block_histogram(const int32_t *ids, int begin, int end, int E, i
     }
 }
 
-// From n_e (one expert per lane, 0 beyond E): slot offsets toff[0..E] in LDS, counts / meta /
-// tile_expert in global memory.  Called by all NT lanes; E <= NT.
+// From n_e (one expert per lane, 0 beyond E): slot offsets toff[0..E] and the counts nreal[0..E) in LDS,
+// counts / meta / tile_expert / tile_rows in global memory.  Called by all NT lanes; E <= NT.
 __device__ void block_scan_and_emit(int n_e, int E, int bm, int cap, int dropped_total, int *toff, int *wsum,
-                                    int32_t *counts, int32_t *meta, int32_t *tile_expert, int32_t *tile_rows,
-                                    bool emit = true)
+                                    int *nreal, int32_t *counts, int32_t *meta, int32_t *tile_expert,
+                                    int32_t *tile_rows, bool emit = true)
 {
     const int e = threadIdx.x;
+    if (e < E) nreal[e] = n_e;
     int slots = (e < E) ? (n_e + bm - 1) / bm * bm : 0;
     int p_pad;
     int off = block_exclusive_scan(slots, wsum, &p_pad);
@@ -98,7 +99,7 @@ __device__ void block_scan_and_emit(int n_e, int E, int bm, int cap, int dropped
         if (tile_rows) {
             int rows = 0;
             if (owner >= 0) {
-                rows = counts[owner] - (m * bm - toff[owner]);  // counts[] was written before the barrier above
+                rows = nreal[owner] - (m * bm - toff[owner]);
                 rows = rows > bm ? bm : rows;
             }
             tile_rows[m] = rows;
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(NT) void align_single_kernel(const int32_t *ids, in
     }
     int n_e = ((int)threadIdx.x < E) ? hist[threadIdx.x] : 0;
     int dropped = misc[0];
-    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, counts, meta, tile_expert, tile_rows);
+    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, hist, counts, meta, tile_expert, tile_rows);
     __syncthreads();
     int *cursor = hist;  // histogram no longer needed
     for (int x = threadIdx.x; x < E; x += NT) cursor[x] = toff[x];
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(NT) void align_scan_kernel(int B, int E, int bm, in
                                                         int32_t *meta, int scatter)
 {
     extern __shared__ int lds[];
-    int *toff = lds, *wsum = lds + E + 1;
+    int *toff = lds, *wsum = lds + E + 1, *nreal = wsum + NW;
     const int e = threadIdx.x;
     int n_e = 0;
     if (e < E) {
@@ -240,7 +241,7 @@ __global__ __launch_bounds__(NT) void align_scan_kernel(int B, int E, int bm, in
     int dropped = 0;
 #pragma unroll 8
     for (int b = 0; b < B; ++b) dropped += block_dropped[b];
-    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, counts, meta, tile_expert, tile_rows);
+    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, nreal, counts, meta, tile_expert, tile_rows);
     __syncthreads();
     if (e < E) {
         int run = toff[e];
@@ -279,7 +280,9 @@ __global__ __launch_bounds__(NT) void align_scan_scatter_kernel(const int32_t *i
 #pragma unroll 8
         for (int b = 0; b < B; ++b) dropped += block_dropped[b];
     }
-    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, counts, meta, tile_expert, tile_rows, blockIdx.x == 0);
+    // the cursor array holds the counts while workgroup 0 emits the per-tile arrays
+    block_scan_and_emit(n_e, E, bm, cap, dropped, toff, wsum, cursor, counts, meta, tile_expert, tile_rows,
+                        blockIdx.x == 0);
     __syncthreads();
     if (e < E) cursor[e] = toff[e] + before;
     __syncthreads();
@@ -349,7 +352,7 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
     int rc = check_launch("align_hist_kernel");
     if (rc) return rc;
     if (!scatter) {
-        hipLaunchKernelGGL(align_scan_kernel, dim3(1), dim3(NT), (E + 1 + NW) * sizeof(int), stream, B, E, bm, cap,
+        hipLaunchKernelGGL(align_scan_kernel, dim3(1), dim3(NT), (2 * E + 1 + NW) * sizeof(int), stream, B, E, bm, cap,
                            block_counts, block_dropped, block_base, tile_expert, tile_rows, counts, meta, scatter);
         return check_launch("align_scan_kernel");
     }
