@@ -179,6 +179,32 @@ int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int3
                            const int32_t *wave_cap, const float *theta,
                            const int32_t *expert_counts, int flags, int *best_idx, double *pred_us);
 
+/* ---- performance-region variables (Sec. 4.1: Eq. 2-5, Tab. 2) ------------------------------------
+ * The four quantities the paper uses to say which optimisation modes belong in a model's pool, for
+ * one configuration of this kernel (ttn -> bn, tile_k -> bk, N = 2I, K = H) and one grid (Eq. 1):
+ *   rho = N*K/(bn*bk)  MMA tile operations per block        lambda = ceil(N/bn)  N-tiles
+ *   kappa = K/bk       K-loop depth                         omega = grid/units   waves
+ * region: 0..5 = A1 A2 A3 B1 B2 B3 of Tab. 2 (row: rho >= rho_c; column: omega < 1, 1 <= omega <= 8,
+ * omega > 8).  group_m: lambda*kappa > l2_eff_bytes/(bn*bk*elem_bytes) (Eq. 4); split_k: kappa >=
+ * split_k_kappa and omega < split_k_omega; wide_tile: omega > 1.  Host only.
+ * thresholds == NULL takes this chip's: rho_c = RAMP_REGION_RHO_C, l2_eff_bytes =
+ * RAMP_REGION_L2_EFF_BYTES (three quarters of the 4 MB L2 of one XCD, the level at which workgroups
+ * share weight tiles), 2-byte elements, 256 units, the paper's 48 and 0.2 for split-K.  The paper's
+ * own H200 numbers are rho_c = 186, 45 MB, 1 byte, 132 units. */
+#define RAMP_REGION_RHO_C 16.0
+#define RAMP_REGION_L2_EFF_BYTES (3.0 * 1024 * 1024)
+typedef struct {
+    double rho_c, l2_eff_bytes;
+    int32_t elem_bytes, units;
+    double split_k_kappa, split_k_omega;
+} ramp_region_thresholds;
+typedef struct {
+    double rho, lambda, kappa, omega, group_m_threshold;
+    int32_t region, group_m, split_k, wide_tile;
+} ramp_region;
+int ramp_region_classify(const ramp_shape *shape, const ramp_config *cfg, long long grid,
+                         const ramp_region_thresholds *thresholds /*may be NULL*/, ramp_region *out);
+
 /* ---- device-resident dispatch (Sec. 4.4 steps 1-3 in one enqueue; Sec. 5 "dispatch overhead") ----
  * ramp_cost_model_select needs the histogram on the host: a device-to-host copy and a stream
  * synchronisation on every call.  ramp_select_device instead enqueues the histogram and one small

@@ -191,3 +191,34 @@ extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs,
     *best_idx = best;
     return RAMP_OK;
 }
+
+// ---- performance-region variables (Sec. 4.1, Eq. 2-5, Tab. 2) ----
+extern "C" int ramp_region_classify(const ramp_shape *shape, const ramp_config *cfg, long long grid,
+                                    const ramp_region_thresholds *thresholds, ramp_region *out)
+{
+    if (!shape || !cfg || !out || grid < 0 || cfg->bn <= 0 || cfg->bk <= 0 || shape->H <= 0 || shape->I <= 0) {
+        ramp::set_error("region_classify: bad argument");
+        return RAMP_EINVAL;
+    }
+    ramp_region_thresholds th = {RAMP_REGION_RHO_C, RAMP_REGION_L2_EFF_BYTES, 2, 256, 48.0, 0.2};
+    if (thresholds) th = *thresholds;
+    if (th.rho_c <= 0 || th.l2_eff_bytes <= 0 || th.elem_bytes <= 0 || th.units <= 0) {
+        ramp::set_error("region_classify: thresholds must be positive");
+        return RAMP_EINVAL;
+    }
+    const double N = 2.0 * shape->I, K = shape->H;  // the paper's N (gate and up side by side) and K of phase 1
+    ramp_region r;
+    r.rho = N * K / ((double)cfg->bn * cfg->bk);                       // Eq. 2
+    r.lambda = (double)((2ll * shape->I + cfg->bn - 1) / cfg->bn);     // Eq. 3
+    r.kappa = K / cfg->bk;                                             // Eq. 3
+    r.omega = (double)grid / th.units;                                 // Eq. 5
+    r.group_m_threshold = th.l2_eff_bytes / ((double)cfg->bn * cfg->bk * th.elem_bytes);  // Eq. 4, right-hand side
+    const int row = r.rho >= th.rho_c ? 1 : 0;
+    const int col = r.omega < 1.0 ? 0 : (r.omega <= 8.0 ? 1 : 2);
+    r.region = row * 3 + col;                                          // Tab. 2: A1 A2 A3 B1 B2 B3
+    r.group_m = r.lambda * r.kappa > r.group_m_threshold;
+    r.split_k = r.kappa >= th.split_k_kappa && r.omega < th.split_k_omega;
+    r.wide_tile = r.omega > 1.0;
+    *out = r;
+    return RAMP_OK;
+}

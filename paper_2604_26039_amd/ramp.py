@@ -38,6 +38,23 @@ class Config(ctypes.Structure):
         return f"Config(bm={self.bm}, bn={self.bn}, bk={self.bk}, waves={self.waves}, stages={self.stages}, mode={self.mode})"
 
 
+class RegionThresholds(ctypes.Structure):
+    _fields_ = [("rho_c", ctypes.c_double), ("l2_eff_bytes", ctypes.c_double), ("elem_bytes", ctypes.c_int32),
+                ("units", ctypes.c_int32), ("split_k_kappa", ctypes.c_double), ("split_k_omega", ctypes.c_double)]
+
+
+class Region(ctypes.Structure):
+    _fields_ = [("rho", ctypes.c_double), ("lam", ctypes.c_double), ("kappa", ctypes.c_double),
+                ("omega", ctypes.c_double), ("group_m_threshold", ctypes.c_double), ("region", ctypes.c_int32),
+                ("group_m", ctypes.c_int32), ("split_k", ctypes.c_int32), ("wide_tile", ctypes.c_int32)]
+
+    NAMES = ("A1", "A2", "A3", "B1", "B2", "B3")
+
+    @property
+    def name(self):
+        return self.NAMES[self.region]
+
+
 class RampError(RuntimeError):
     def __init__(self, status: int, msg: str):
         super().__init__(f"ramp status {status}: {msg}")
@@ -89,6 +106,8 @@ def lib() -> ctypes.CDLL:
         L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp, vp, ci, vp]
         L.ramp_cost_model_select.restype = ci
         L.ramp_cost_model_select.argtypes = [ci, ci, cp, vp, vp, vp, vp, ci, ctypes.POINTER(ci), vp]
+        L.ramp_region_classify.restype = ci
+        L.ramp_region_classify.argtypes = [sp, cp, ctypes.c_longlong, ctypes.POINTER(RegionThresholds), ctypes.POINTER(Region)]
         L.ramp_select_table_bytes.restype = sz
         L.ramp_select_table_bytes.argtypes = [ci]
         L.ramp_select_table_build.restype = ci
@@ -115,7 +134,7 @@ EXPORTS = [
     "ramp_last_error", "ramp_num_configs", "ramp_get_config", "ramp_config_ntiles", "ramp_config_wave_capacity",
     "ramp_align_capacity", "ramp_align_workspace_bytes", "ramp_moe_histogram", "ramp_moe_align", "ramp_pack_bytes",
     "ramp_pack_weights", "ramp_fused_moe_workspace_bytes", "ramp_fused_moe_workspace_layout", "ramp_fused_moe",
-    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_select_table_bytes", "ramp_select_table_build",
+    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_region_classify", "ramp_select_table_bytes", "ramp_select_table_build",
     "ramp_select_result_bytes", "ramp_select_device", "ramp_select_poll", "ramp_select_wait", "ramp_copy_bytes", "ramp_probe_enable", "ramp_probe_read",
 ]
 
@@ -333,3 +352,12 @@ def select_result_unpack(result: torch.Tensor, E: int, n_cfg: int):
     pred = raw[16:16 + 8 * n_cfg].view(np.float64).copy()
     counts = raw[16 + 8 * n_cfg:16 + 8 * n_cfg + 4 * E].view(np.int32).copy()
     return ticket, best, pred, counts
+
+
+# ----------------------------------------------------------------------------- performance regions (host)
+
+def region_classify(shape: Shape, cfg: Config, grid: int, thresholds: Optional[RegionThresholds] = None) -> Region:
+    out = Region()
+    _check(lib().ramp_region_classify(ctypes.byref(shape), ctypes.byref(cfg), int(grid),
+                                      ctypes.byref(thresholds) if thresholds is not None else None, ctypes.byref(out)))
+    return out

@@ -231,3 +231,39 @@ def test_select_table_layout_and_host_polling():
     block[:8] = np.array([(23 << 32) | 5], np.uint64).view(np.uint8)
     assert L.ramp_select_poll(block.ctypes.data, 5, ctypes.byref(best)) == 0 and best.value == 23
     assert L.ramp_select_wait(block.ctypes.data, 5, 0.05, ctypes.byref(best)) == 0 and best.value == 23
+
+
+def test_region_classify_matches_oracle_and_tab3():
+    """Eq. 2-5 / Tab. 2 calculators of the library against the oracle's (which are pinned to Tab. 3), with the
+    paper's H200 thresholds; Tab. 3's region letters and GROUP_M predictions (Sec. 4.1) come out."""
+    import os
+    golden = os.path.join(os.path.dirname(__file__), "golden", "tab3_regions.txt")
+    rows = [l.split() for l in open(golden) if l.strip() and not l.startswith("#")]
+    h200 = ramp.RegionThresholds(186.0, 45.0 * 2 ** 20, 1, 132, 48.0, 0.2)
+    letters = dict(olmoe="A", qwen3="A", dsv3_ep8="A", mixtral="B", dsv3_tp8="A", phi_moe="B", jamba="B", dbrx="B")
+    for model, N, K, rho, lam, kap in rows:
+        N, K = int(N), int(K)
+        sh = ramp.Shape(64, 2, 8, K, N // 2)
+        cfg = ramp.Config(64, 256, 128, 4, 3, 0)
+        for grid in (20, 131, 133, 1200):
+            r = ramp.region_classify(sh, cfg, grid, h200)
+            assert r.rho == oracle.rho(N, K, 256, 128) == float(rho)
+            assert r.lam == oracle.lam(N, 256) == int(lam)
+            assert r.kappa == oracle.kappa(K, 128) == float(kap)
+            assert r.omega == oracle.omega(grid, 132)
+            assert r.group_m_threshold == oracle.group_m_threshold(45.0 * 2 ** 20, 256, 128, 1) == 1440.0
+            assert r.name[0] == letters[model]
+            assert r.name[1] == ("1" if grid < 132 else "2" if grid <= 8 * 132 else "3")
+            assert bool(r.group_m) == (letters[model] == "B")          # Sec. 4.1: holds for all 8 models
+            assert bool(r.split_k) == (float(kap) >= 48 and grid / 132 < 0.2)
+            assert bool(r.wide_tile) == (grid > 132)
+    # this chip's defaults: 256 units, bf16 elements, 3 MB of one XCD's L2
+    sh = shape_of("mixtral", 64)
+    cfg = ramp.configs(sh)[0]
+    r = ramp.region_classify(sh, cfg, 512)
+    assert r.omega == 2.0 and r.group_m_threshold == 3.0 * 2 ** 20 / (cfg.bn * cfg.bk * 2)
+    assert r.rho == 2 * sh.I * sh.H / (cfg.bn * cfg.bk)
+    with pytest.raises(ramp.RampError):
+        ramp.region_classify(sh, cfg, -1)
+    with pytest.raises(ramp.RampError):
+        ramp.region_classify(sh, cfg, 10, ramp.RegionThresholds(0.0, 1.0, 1, 1, 48.0, 0.2))
