@@ -237,7 +237,8 @@ int ramp_select_device(const int32_t *topk_ids /*dev [T*k]*/, int T, int k, int 
                        uint32_t ticket, int32_t *best_idx_dev /*dev, may be NULL*/,
                        void *ws /*dev*/, size_t ws_bytes, void *stream);
 /* Host side of the result block.  ramp_select_poll returns RAMP_OK and *best_idx once the block
- * carries `ticket`, 1 if it does not yet (not an error).  ramp_select_wait spins on it for at most
+ * carries `ticket`, 1 if it does not yet (not an error), RAMP_EINVAL if the kernel found that the
+ * table was not one built for n_cfg configurations (it then evaluates nothing).  ramp_select_wait spins on it for at most
  * timeout_s seconds (then RAMP_EHIP).  Neither touches the HIP runtime. */
 int ramp_select_poll(const void *result_host, uint32_t ticket, int *best_idx);
 int ramp_select_wait(const void *result_host, uint32_t ticket, double timeout_s, int *best_idx);

@@ -37,14 +37,18 @@ struct ResultHeader {
 static_assert(sizeof(ResultHeader) == 16, "result layout is part of the ABI");
 
 __global__ __launch_bounds__(NT) void select_kernel(const int32_t *ids, int P, int B, const int32_t *block_counts, int E,
-                                                    const TableHeader *table, ResultHeader *res, uint32_t ticket,
-                                                    int32_t *best_dev)
+                                                    int n_cfg, const TableHeader *table, ResultHeader *res,
+                                                    uint32_t ticket, int32_t *best_dev)
 {
     __shared__ int hist[kAlignMaxE];
     __shared__ int mt[kMaxBm];
     __shared__ int active_pairs[2];
     const int tid = threadIdx.x, lane = tid & 63;
-    const int n_cfg = table->n_cfg, n_bm = table->n_bm, flags = table->flags;
+    // n_cfg is the caller's (the result block was sized with it); a table that is not one of
+    // ramp_select_table_build's for that many configurations yields best = -1 and no predictions
+    const bool table_ok = table->magic == kMagic && table->n_cfg == n_cfg && table->n_bm >= 1 && table->n_bm <= kMaxBm;
+    const int n_bm = table_ok ? table->n_bm : 0, flags = table->flags;
+    const int n_eval = table_ok ? n_cfg : 0;
     const TableRow *rows = reinterpret_cast<const TableRow *>(table + 1);
     double *pred = reinterpret_cast<double *>(res + 1);
     int32_t *counts_out = reinterpret_cast<int32_t *>(pred + n_cfg);
@@ -52,24 +56,19 @@ __global__ __launch_bounds__(NT) void select_kernel(const int32_t *ids, int P, i
     if (tid < kMaxBm) mt[tid] = 0;
     if (tid < 2) active_pairs[tid] = 0;
     // ---- histogram: own pass over the ids (small inputs), or the per-chunk histograms of align_hist_kernel
-    int n = 0;
+    if (tid < E) hist[tid] = 0;
+    __syncthreads();
     if (B == 0) {
-        if (tid < E) hist[tid] = 0;
-        __syncthreads();
         for (int p = tid; p < P; p += NT) {
             const int v = ids[p];
             if (v >= 0 && v < E) atomicAdd(&hist[v], 1);
         }
-        __syncthreads();
-        if (tid < E) n = hist[tid];
     } else {
-        if (tid < E) {
-#pragma unroll 8
-            for (int b = 0; b < B; ++b) n += block_counts[(size_t)b * E + tid];
-        }
-        __syncthreads();
+        // all lanes share the B x E chunk counts (coalesced; integer sums do not depend on the order)
+        for (int i = tid; i < B * E; i += NT) atomicAdd(&hist[i % E], block_counts[i]);
     }
-    if (tid < E) hist[tid] = n;
+    __syncthreads();
+    const int n = (tid < E) ? hist[tid] : 0;
     // ---- sums over the experts: M-tiles for every distinct bm, active experts, routed pairs
     if ((tid & ~63) < E) {  // wavefronts that hold experts
         for (int j = 0; j < n_bm + 2; ++j) {
@@ -94,7 +93,7 @@ __global__ __launch_bounds__(NT) void select_kernel(const int32_t *ids, int P, i
     const long long active = active_pairs[0], pairs = active_pairs[1];
     int best = -1;
     double best_t = 0.0;
-    for (int c = lane; c < n_cfg; c += kWave) {
+    for (int c = lane; c < n_eval; c += kWave) {
         const TableRow r = rows[c];
         const double g = (double)((long long)mt[r.bm_slot] * (long long)r.ntiles);
         double t = (double)r.theta[0];
@@ -126,9 +125,9 @@ __global__ __launch_bounds__(NT) void select_kernel(const int32_t *ids, int P, i
         res->reserved = 0;
         if (best_dev) *best_dev = best;
     }
-    __threadfence_system();
-    if (lane == 0)
-        __hip_atomic_store(&res->word, ((unsigned long long)(uint32_t)best << 32) | ticket, __ATOMIC_RELEASE,
+    __threadfence_system();  // every lane's payload stores are complete and visible to the host ...
+    if (lane == 0)           // ... before the word that announces them (the fence above is the release)
+        __hip_atomic_store(&res->word, ((unsigned long long)(uint32_t)best << 32) | ticket, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
@@ -209,7 +208,7 @@ extern "C" int ramp_select_device(const int32_t *topk_ids, int T, int k, int E, 
         if (int rc = launch_chunk_histograms(topk_ids, P, E, ws, ws_bytes, s, &B)) return rc;
     }
     hipLaunchKernelGGL(select_kernel, dim3(1), dim3(NT), 0, s, topk_ids, P, B, static_cast<const int32_t *>(ws), E,
-                       static_cast<const TableHeader *>(table), static_cast<ResultHeader *>(result), ticket,
+                       n_cfg, static_cast<const TableHeader *>(table), static_cast<ResultHeader *>(result), ticket,
                        best_idx_dev);
     return check_launch("select_kernel");
 }
@@ -224,6 +223,10 @@ extern "C" int ramp_select_poll(const void *result_host, uint32_t ticket, int *b
     const unsigned long long w = __atomic_load_n(&r->word, __ATOMIC_ACQUIRE);
     if ((uint32_t)w != ticket) return 1;
     *best_idx = (int32_t)(w >> 32);
+    if (*best_idx < 0) {
+        ramp::set_error("select: the kernel rejected its table (not built by ramp_select_table_build for this n_cfg)");
+        return RAMP_EINVAL;
+    }
     return RAMP_OK;
 }
 

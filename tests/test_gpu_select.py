@@ -171,3 +171,8 @@ def test_select_device_rejects_bad_arguments():
     with pytest.raises(ramp.RampError):
         ramp.select_device(ids, 4096, s.k, s.E, n, table, result, 1, ws)        # workspace too small for the chunked path
     assert ramp.select_poll(result, 1) is None                                   # nothing was enqueued
+    # a table for another configuration count is rejected by the kernel itself; nothing is evaluated
+    ramp.select_device(ids, 16, s.k, s.E, n - 1, table, result, 7, ws)
+    with pytest.raises(ramp.RampError):
+        ramp.select_wait(result, 7, timeout_s=20.0)
+    torch.cuda.synchronize()
