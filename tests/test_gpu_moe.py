@@ -159,6 +159,38 @@ def test_irregular_shapes_every_third_config(H, I, E, k, T, beta):
         assert_close(L.run(cfg, ids, w), ref, f"H={H} I={I} E={E} k={k} T={T} {cfg}")
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_randomized_shapes_sampled_rows(seed):
+    """Seeded random shapes (H, I multiples of 128; 1 to 257 experts; top-1 to top-8), batch sizes from one token to
+    a few thousand, four skews, some ids out of range; ten random configurations plus the ping-pong ones per case,
+    sampled token rows against the oracle."""
+    rng = np.random.default_rng(seed)
+    for case in range(25):
+        H, I = 128 * int(rng.integers(1, 9)), 128 * int(rng.integers(1, 9))
+        E = int(rng.choice([1, 2, 3, 5, 8, 17, 33, 64, 100, 257]))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        T = int(rng.choice([1, 2, 3, 15, 17, 63, 130, 255, 513, 1025, 2047, 3001]))
+        beta = float(rng.choice([1.0, 0.5, 0.2, 0.08]))
+        shape = synth.Shape("random", H, I, E, k)
+        L = Layer(shape, T, seed=1000 * seed + case, x_std=float(rng.choice([0.5, 1.0, 2.0])))
+        ids, w = synth.routing(T, shape, beta, seed=case)
+        if rng.random() < 0.3:
+            ids = ids.copy()
+            ids.reshape(-1)[rng.integers(0, ids.size, max(1, ids.size // 10))] = rng.choice([-1, E, E + 5])
+        rows = np.unique(rng.integers(0, T, min(T, 24)))
+        if not any(0 <= e < E for t in rows for e in ids[t]):
+            continue  # every sampled pair dropped: nothing to compare
+        ref = L.oracle_rows(ids, w, rows=rows)
+        if np.abs(ref).max() == 0:
+            continue
+        cfgs = ramp.configs(L.rs)
+        picked = [cfgs[i] for i in rng.choice(len(cfgs), min(len(cfgs), 10), replace=False)]
+        picked += [c for c in cfgs if c.mode & 0x400][:3]
+        sel = torch.from_numpy(rows).to(DEV)
+        for cfg in picked:
+            assert_close(L.run(cfg, ids, w)[sel], ref, f"seed={seed} case={case} H={H} I={I} E={E} k={k} T={T} beta={beta} {cfg}")
+
+
 def test_run_to_run_bit_identical(olmoe_small):
     L = olmoe_small
     ids, w = synth.routing(96, L.s, 0.2, seed=9)
