@@ -267,3 +267,14 @@ def test_region_classify_matches_oracle_and_tab3():
         ramp.region_classify(sh, cfg, -1)
     with pytest.raises(ramp.RampError):
         ramp.region_classify(sh, cfg, 10, ramp.RegionThresholds(0.0, 1.0, 1, 1, 48.0, 0.2))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a single-GPU benchmark: --gpus N > 1 (or a multi-rank launch) exits with a message, before
+    anything touches a GPU."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for extra_env, argv in (({}, ["--gpus", "2"]), ({"WORLD_SIZE": "4"}, [])):
+        env = dict(os.environ, **extra_env)
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py")] + argv, capture_output=True, text=True, env=env, timeout=60)
+        assert r.returncode == 2 and "single-GPU" in r.stderr and r.stdout.strip() == ""
