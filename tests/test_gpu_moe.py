@@ -191,6 +191,48 @@ def test_randomized_shapes_sampled_rows(seed):
             assert_close(L.run(cfg, ids, w)[sel], ref, f"seed={seed} case={case} H={H} I={I} E={E} k={k} T={T} beta={beta} {cfg}")
 
 
+def test_fused_layer_replays_from_a_hip_graph(olmoe_small):
+    """ramp_fused_moe only enqueues kernels on the caller's stream (no allocation, no memset node, no host
+    synchronisation), so it can be captured once and replayed: every replay, with new inputs written into the
+    captured buffers and eager work in between, is bit-identical to the eager call on the same inputs."""
+    L = olmoe_small
+    T = 96
+    rs = ramp.Shape(T, L.s.k, L.s.E, L.s.H, L.s.I)
+    cfgs = ramp.configs(rs)
+    picked = [cfgs[0]] + [c for c in cfgs if c.mode & 0x400][:1] + [c for c in cfgs if c.mode & 0x100][:1]
+    for cfg in picked:
+        d_ids = torch.zeros((T, L.s.k), dtype=torch.int32, device=DEV)
+        d_w = torch.zeros((T, L.s.k), dtype=torch.float32, device=DEV)
+        X = L.X[:T].clone()
+        out = torch.zeros((T, L.s.H), dtype=torch.bfloat16, device=DEV)
+        ws = torch.empty(ramp.fused_moe_workspace_bytes(rs, cfg), dtype=torch.uint8, device=DEV)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            ramp.fused_moe(rs, cfg, X, d_ids, d_w, L.packed, out, ws)       # warm-up outside the capture
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                ramp.fused_moe(rs, cfg, X, d_ids, d_w, L.packed, out, ws, stream=side)
+        torch.cuda.current_stream().wait_stream(side)
+        for rep, beta in enumerate((0.2, 1.0, 0.5)):
+            ids, w = synth.routing(T, L.s, beta, seed=40 + rep)
+            d_ids.copy_(torch.from_numpy(np.ascontiguousarray(ids, np.int32)))
+            d_w.copy_(torch.from_numpy(np.ascontiguousarray(w, np.float32)))
+            X.copy_(L.X[:T] * (1.0 + 0.25 * rep))
+            ws.fill_(0xFF)
+            out.fill_(777.0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = out.clone()
+            eager = torch.zeros_like(out)
+            ws2 = torch.full_like(ws, 0xFF)
+            ramp.fused_moe(rs, cfg, X, d_ids, d_w, L.packed, eager, ws2)    # the program's own eager work between replays
+            torch.cuda.synchronize()
+            assert torch.equal(got.view(torch.int16), eager.view(torch.int16)), f"replay {rep} {cfg}"
+
+
 def test_run_to_run_bit_identical(olmoe_small):
     L = olmoe_small
     ids, w = synth.routing(96, L.s, 0.2, seed=9)
