@@ -9,8 +9,9 @@
 //     a per-wavefront count table in LDS (wavefronts of lower index) and a running
 //     cursor (earlier chunks / earlier workgroups).
 // Up to kAlignSingleMaxP pairs one 1024-lane workgroup does histogram, scan and
-// scatter in a single launch; larger inputs take three launches
-// (per-workgroup histograms -> scan -> scatter).
+// scatter in a single launch; larger inputs take two launches (per-chunk
+// histograms, then a kernel in which every workgroup scans them and scatters
+// its chunk); the histogram-only entry point ends with a small scan kernel.
 #include "ramp_internal.h"
 
 namespace ramp {
