@@ -61,6 +61,7 @@ def main():
     ap.add_argument("--config", default=None,
                     help="bm,bn,bk,waves,stages,mode: skip profiling/fit and run the headline with this fixed "
                          "configuration (for profiler runs)")
+    ap.add_argument("--save-model", default=None, help="write the fitted cost-model table of this shape (JSON) here")
     ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out"))
     args = ap.parse_args()
 
@@ -119,6 +120,9 @@ def main():
     thetas = {name: tuner.fit(fam, g_fit, t_fit, counts_fit, flags) for name, flags in MODELS.items()}
     DISPATCH = "eq6_mi355x"
     theta, dispatch_flags = thetas[DISPATCH], MODELS[DISPATCH]
+    if args.save_model and fixed_cfg is None:
+        tuner.save_model(args.save_model, fam, theta, dispatch_flags,
+                         extra=dict(model=args.model, fit_T=fit_T, fit_betas=[str(b) for b in tuner.FIT_BETAS]))
 
     def predictions(name, counts):
         return ramp.cost_model_select(s.E, fam.cfgs, fam.ntiles, fam.wave_cap, thetas[name], counts, want_pred=True,

@@ -182,6 +182,40 @@ def select(fam: Family, theta: np.ndarray, counts: np.ndarray, flags: int = ramp
     return ramp.cost_model_select(fam.shape.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, counts, flags=flags)
 
 
+def save_model(path: str, fam: Family, theta: np.ndarray, flags: int, extra: dict = None) -> None:
+    """Writes the fitted table of one shape (Sec. 4.2: four numbers per configuration, a few KB) as JSON, keyed by
+    the configuration tuples so that a table is never applied to a different family."""
+    import json
+    s = fam.shape
+    doc = dict(shape=dict(k=s.k, E=s.E, H=s.H, I=s.I), flags=int(flags),
+               configs=[list(c.key()) for c in fam.cfgs], ntiles=[int(v) for v in fam.ntiles],
+               wave_cap=[int(v) for v in fam.wave_cap],
+               theta=[[float(v) for v in row] for row in np.asarray(theta, np.float32).reshape(len(fam.cfgs), 4)])
+    if extra:
+        doc["info"] = extra
+    with open(path, "w") as f:
+        json.dump(doc, f)
+
+
+def load_model(path: str, fam: Family):
+    """(theta float32 [n_cfg,4], flags) from save_model's file; raises if it was fitted for another shape,
+    family or tile accounting (then the shape has to be profiled again)."""
+    import json
+    with open(path) as f:
+        doc = json.load(f)
+    s = fam.shape
+    if doc["shape"] != dict(k=s.k, E=s.E, H=s.H, I=s.I):
+        raise ValueError(f"{path}: fitted for shape {doc['shape']}, not {dict(k=s.k, E=s.E, H=s.H, I=s.I)}")
+    if [tuple(c) for c in doc["configs"]] != [c.key() for c in fam.cfgs]:
+        raise ValueError(f"{path}: fitted for a different configuration family")
+    if list(doc["ntiles"]) != [int(v) for v in fam.ntiles] or list(doc["wave_cap"]) != [int(v) for v in fam.wave_cap]:
+        raise ValueError(f"{path}: tile counts or wave capacities differ from this build's")
+    theta = np.asarray(doc["theta"], np.float32).reshape(len(fam.cfgs), 4)
+    if not np.isfinite(theta).all():
+        raise ValueError(f"{path}: non-finite coefficients")
+    return theta, int(doc["flags"])
+
+
 class Dispatcher:
     """Runtime dispatch (Sec. 4.4).  Three ways to get from the routing of a call to a configuration index:
 

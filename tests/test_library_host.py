@@ -278,3 +278,22 @@ def test_bench_refuses_more_than_one_gpu():
         env = dict(os.environ, **extra_env)
         r = subprocess.run([sys.executable, os.path.join(root, "bench.py")] + argv, capture_output=True, text=True, env=env, timeout=60)
         assert r.returncode == 2 and "single-GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_fitted_table_round_trip(tmp_path):
+    """tuner.save_model / load_model: the table comes back bit for bit and is refused for another shape or family."""
+    from paper_2604_26039_amd import tuner
+    fam = tuner.Family.of(synth.SHAPES["olmoe"], 64)
+    rng = np.random.default_rng(3)
+    theta = rng.uniform(0.01, 50, (len(fam.cfgs), 4)).astype(np.float32)
+    path = str(tmp_path / "olmoe.json")
+    tuner.save_model(path, fam, theta, tuner.MI355X_MODEL, extra=dict(note="test"))
+    got, flags = tuner.load_model(path, fam)
+    assert got.dtype == np.float32 and np.array_equal(got, theta) and flags == tuner.MI355X_MODEL
+    assert os.path.getsize(path) < 64 * 1024
+    with pytest.raises(ValueError):
+        tuner.load_model(path, tuner.Family.of(synth.SHAPES["qwen3"], 64))
+    other = tuner.Family.of(synth.SHAPES["olmoe"], 64)
+    other.cfgs = other.cfgs[1:] + other.cfgs[:1]
+    with pytest.raises(ValueError):
+        tuner.load_model(path, other)
