@@ -112,3 +112,20 @@ def test_align_rejects_bad_arguments():
     with pytest.raises(ramp.RampError) as ei:
         ramp.moe_align(big, 8192, 8, 64, 16, buf, buf, buf, buf, None)  # multi-workgroup path needs a workspace
     assert ei.value.status == ramp.ENOSPC
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_align_randomized(seed):
+    """Seeded random sizes: 1 to 1024 experts, top-1 to top-16, bm including non powers of two, empty to 9000 tokens,
+    Dirichlet-skewed routing, some ids out of range."""
+    rng = np.random.default_rng(seed)
+    for _ in range(60):
+        E = int(rng.choice([1, 2, 7, 64, 100, 256, 777, 1024]))
+        k = int(rng.integers(1, 17))
+        T = int(rng.choice([0, 1, 2, 5, 100, 128, 129, 500, 1024, 3000, 9000]))
+        bm = int(rng.choice([1, 3, 4, 16, 33, 64, 128, 256, 1000]))
+        p = rng.dirichlet(np.full(E, 0.05 + 2 * rng.random())) if E > 1 else np.ones(1)
+        ids = rng.choice(E, size=(T, k), p=p).astype(np.int32)
+        if rng.random() < 0.3 and ids.size:
+            ids.reshape(-1)[rng.integers(0, ids.size, ids.size // 7 + 1)] = rng.choice([-3, E, E + 9])
+        check(ids, T, k, E, bm)
