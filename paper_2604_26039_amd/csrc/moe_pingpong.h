@@ -224,8 +224,8 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     // FULL: every token block of the wavefront is real (no branches between the MFMAs); otherwise the products of
     // all-padding blocks are skipped.  The operand reads stay unconditional: branches between them cost more than
     // the reads they save.
-    auto mfma_all = [&](auto full_c) {
-        constexpr bool FULL = decltype(full_c)::value;
+    auto mfma_all = [&](auto mode_c) {
+        constexpr bool FULL = decltype(mode_c)::value == 1;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -294,12 +294,16 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             }
         }
 
-        auto slice = [&](int kt, auto steady_c, auto full_c) {
+        // mode_c: 1 = every token block of the wavefront is real, 0 = some are, 2 = none (a ragged tile that ends
+        // in the other wavefront row): such a wavefront issues its loads and keeps the barriers but neither reads
+        // operands nor multiplies, which leaves the LDS bandwidth of the tile to the wavefronts that do
+        auto slice = [&](int kt, auto steady_c, auto mode_c) {
             constexpr bool STEADY = decltype(steady_c)::value;
+            constexpr int MODE = decltype(mode_c)::value;
             // ---- M phase: both groups have read slice kt-1 (its buffers are free).  Operand reads first, then the
             // loads: the reads are what the barrier waits for, the loads only have to be issued.
             const int par = (XS == 2) ? (kt & 1) : 0;  // position of the slice inside its token batch
-            read_all(par * KS, xbat_cur % NX, wbuf_cur);
+            if (MODE != 2) read_all(par * KS, xbat_cur % NX, wbuf_cur);
             // the load stream crosses into the next tile NSTAGE-1 slices (one token batch) before this one ends
             if (kt == KT - NSTAGE + 1) {
 #pragma unroll
@@ -332,7 +336,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): fragments in registers, buffers no longer read
             phase_barrier();
             // ---- C phase
-            mfma_all(full_c);
+            if (MODE != 2) mfma_all(mode_c);
             phase_barrier();
             wbuf_cur = (wbuf_cur + 1 == NSTAGE) ? 0 : wbuf_cur + 1;
             wbuf_issue = (wbuf_issue + 1 == NSTAGE) ? 0 : wbuf_issue + 1;
@@ -342,14 +346,21 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         // workgroup drains it (conditions evaluated for its last NSTAGE-1 slices)
         using True = std::integral_constant<bool, true>;
         using False = std::integral_constant<bool, false>;
+        using Some = std::integral_constant<int, 0>;
+        using Full = std::integral_constant<int, 1>;
+        using None = std::integral_constant<int, 2>;
         int kt = 0;
         const int kt_steady = has_next ? KT : KT - NSTAGE + 1;
         if (nb_valid == NB) {
-            for (; kt < kt_steady; ++kt) slice(kt, True{}, True{});
+            for (; kt < kt_steady; ++kt) slice(kt, True{}, Full{});
+            for (; kt < KT; ++kt) slice(kt, False{}, Some{});
+        } else if (nb_valid > 0) {
+            for (; kt < kt_steady; ++kt) slice(kt, True{}, Some{});
+            for (; kt < KT; ++kt) slice(kt, False{}, Some{});
         } else {
-            for (; kt < kt_steady; ++kt) slice(kt, True{}, False{});
+            for (; kt < kt_steady; ++kt) slice(kt, True{}, None{});
+            for (; kt < KT; ++kt) slice(kt, False{}, None{});
         }
-        for (; kt < KT; ++kt) slice(kt, False{}, False{});
 
         // ---- epilogue: lane holds features fblock*16 + 4*q + {0..3} of token r16.  It runs while the other group
         // is in a C phase; the stores are not waited for here.
