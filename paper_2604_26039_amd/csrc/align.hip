@@ -8,8 +8,8 @@
 //   - ranks inside an expert come from a wavefront ballot (lanes of lower index),
 //     a per-wavefront count table in LDS (wavefronts of lower index) and a running
 //     cursor (earlier chunks / earlier workgroups).
-// Up to kAlignSingleMaxP pairs one 1024-lane workgroup does histogram, scan and
-// scatter in a single launch; larger inputs take two launches (per-chunk
+// Up to 64 pairs a single wavefront does everything; up to kAlignSingleMaxP pairs one
+// 1024-lane workgroup does histogram, scan and scatter in a single launch; larger inputs take two launches (per-chunk
 // histograms, then a kernel in which every workgroup scans them and scatters
 // its chunk); the histogram-only entry point ends with a small scan kernel.
 #include "ramp_internal.h"
@@ -203,6 +203,89 @@ __global__ __launch_bounds__(NT) void align_single_kernel(const int32_t *ids, in
         block_scatter_chunk(ids, base, P, E, cursor, wcnt, stamp, sorted);
 }
 
+// ---- up to 64 pairs (decode-sized calls): one wavefront, one pair per lane, no workgroup-wide steps ----
+constexpr int kAlignTinyMaxP = 64;
+constexpr int kAlignTinyMaxCap = 4096;
+__global__ __launch_bounds__(kWave) void align_tiny_kernel(const int32_t *ids, int P, int E, int bm, int cap,
+                                                           int32_t *sorted, int32_t *tile_expert, int32_t *tile_rows,
+                                                           int32_t *counts, int32_t *meta)
+{
+    __shared__ int n_lds[kAlignMaxE];
+    __shared__ int toff[kAlignMaxE + 1];
+    const int lane = threadIdx.x;
+    for (int x = lane; x < E; x += kWave) n_lds[x] = 0;
+    for (int s = lane; s < cap; s += kWave) sorted[s] = P;
+    int e = -1;
+    if (lane < P) {
+        const int v = ids[lane];
+        if (v >= 0 && v < E) e = v;
+    }
+    const int dropped = __popcll(__ballot(lane < P && e < 0));
+    // lanes with the same expert: one ballot per bit of the expert index
+    const int ebits = 32 - __clz((E - 1) | 1);
+    unsigned long long same = __ballot(e >= 0);
+#pragma unroll
+    for (int b = 0; b < 10; ++b) {
+        if (b < ebits) {
+            const bool bit = (e >> b) & 1;
+            const unsigned long long m = __ballot(e >= 0 && bit);
+            same &= bit ? m : ~m;
+        }
+    }
+    const int rank = __popcll(same & ((1ull << lane) - 1ull));
+    __syncthreads();
+    if (e >= 0 && rank == 0) n_lds[e] = __popcll(same);
+    __syncthreads();
+    // exclusive scan of the padded slot counts: lane l owns experts [l*per, (l+1)*per)
+    const int per = (E + kWave - 1) / kWave;
+    int local = 0;
+    for (int i = 0; i < per; ++i) {
+        const int x = lane * per + i;
+        if (x < E) local += (n_lds[x] + bm - 1) / bm * bm;
+    }
+    int incl = local;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int up = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += up;
+    }
+    const int p_pad = __shfl(incl, kWave - 1, kWave);
+    int run = incl - local;
+    for (int i = 0; i < per; ++i) {
+        const int x = lane * per + i;
+        if (x < E) {
+            toff[x] = run;
+            run += (n_lds[x] + bm - 1) / bm * bm;
+        }
+    }
+    if (lane == 0) {
+        toff[E] = p_pad;
+        meta[0] = p_pad;
+        meta[1] = p_pad / bm;
+        meta[2] = dropped;
+        meta[3] = 0;
+    }
+    __syncthreads();
+    for (int x = lane; x < E; x += kWave) counts[x] = n_lds[x];
+    const int m_tiles = p_pad / bm, m_cap = cap / bm;
+    for (int m = lane; m < m_cap; m += kWave) {
+        int owner = -1, rows = 0;
+        if (m < m_tiles) {
+            int target = m * bm, lo = 0, hi = E - 1;  // first expert with toff[e+1] > m*bm (empty experts are skipped)
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (toff[mid + 1] > target) hi = mid; else lo = mid + 1;
+            }
+            owner = lo;
+            rows = n_lds[owner] - (target - toff[owner]);
+            rows = rows > bm ? bm : rows;
+        }
+        tile_expert[m] = owner;
+        if (tile_rows) tile_rows[m] = rows;
+    }
+    if (e >= 0) sorted[toff[e] + rank] = lane;  // after the sentinel fill of the same wavefront
+}
+
 // ---- several workgroups: histogram per chunk -> scan -> scatter ----
 __global__ __launch_bounds__(NT) void align_hist_kernel(const int32_t *ids, int P, int E, int cap, int32_t *sorted,
                                                         int32_t *block_counts, int32_t *block_dropped, int fill)
@@ -332,6 +415,11 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
         return RAMP_EINVAL;
     }
     const int cap = scatter ? (int)ramp_align_capacity(T, k, E, bm) : 0;
+    if (scatter && P <= kAlignTinyMaxP && cap <= kAlignTinyMaxCap) {
+        hipLaunchKernelGGL(align_tiny_kernel, dim3(1), dim3(kWave), 0, stream, ids, P, E, bm, cap, sorted, tile_expert,
+                           tile_rows, counts, meta);
+        return check_launch("align_tiny_kernel");
+    }
     if (P <= kAlignSingleMaxP) {
         size_t lds = lds_ints(E) * sizeof(int);
         if (int rc = allow_lds(align_single_kernel, lds)) return rc;

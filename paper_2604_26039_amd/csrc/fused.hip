@@ -59,9 +59,11 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
             const int id = row_ids[j];
             const bool live = id >= 0 && id < E;
             const size_t elem = ((size_t)t * k + j) * H + (size_t)c * 8;
+            // the row is read whether or not the pair is live (its address is always inside Y), so the loads do
+            // not wait for the ids; a dropped pair's row holds stale bytes and is replaced by zeros afterwards
             if (Y16) {
-                uint4 y = make_uint4(0, 0, 0, 0);
-                if (live) y = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(Y) + elem);
+                uint4 y = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(Y) + elem);
+                if (!live) y = make_uint4(0, 0, 0, 0);
                 const uint32_t w[4] = {y.x, y.y, y.z, y.w};
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -69,11 +71,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
                     s[2 * q + 1] += __builtin_bit_cast(float, w[q] & 0xffff0000u);
                 }
             } else {
-                float4 y0 = make_float4(0.f, 0.f, 0.f, 0.f), y1 = y0;
-                if (live) {
-                    y0 = *reinterpret_cast<const float4 *>(Y + elem);
-                    y1 = *reinterpret_cast<const float4 *>(Y + elem + 4);
-                }
+                float4 y0 = *reinterpret_cast<const float4 *>(Y + elem);
+                float4 y1 = *reinterpret_cast<const float4 *>(Y + elem + 4);
+                if (!live) y0 = y1 = make_float4(0.f, 0.f, 0.f, 0.f);
                 s[0] += y0.x; s[1] += y0.y; s[2] += y0.z; s[3] += y0.w;
                 s[4] += y1.x; s[5] += y1.y; s[6] += y1.z; s[7] += y1.w;
             }

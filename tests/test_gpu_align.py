@@ -41,7 +41,10 @@ def check(ids, T, k, E, bm):
 CASES = [
     # (shape, T, beta, bm)
     ("tiny", 16, 1.0, 4), ("tiny", 16, 0.2, 4), ("tiny", 16, 0.2, 16), ("tiny", 16, 1.0, 16),
-    ("olmoe", 1, 1.0, 16), ("olmoe", 16, 0.5, 16), ("olmoe", 64, 0.1, 32), ("olmoe", 256, 0.2, 64),
+    ("olmoe", 1, 1.0, 16), ("olmoe", 8, 1.0, 16),   # 8 and 64 pairs: the single-wavefront kernel
+    ("olmoe", 9, 0.5, 32),                            # 72 pairs: first size of the one-workgroup kernel
+    ("dsv3", 8, 0.2, 64), ("dsv3", 8, 0.2, 65),      # 64 pairs with 4096 slots (last single-wavefront size) and more
+    ("olmoe", 16, 0.5, 16), ("olmoe", 64, 0.1, 32), ("olmoe", 256, 0.2, 64),
     ("olmoe", 256, 1.0, 128),   # P = 2048: last single-workgroup size
     ("olmoe", 257, 1.0, 128),   # first multi-workgroup size, ragged tail
     ("olmoe", 512, 1.0, 128), ("olmoe", 513, 0.5, 16),
