@@ -10,7 +10,7 @@ Before the timed region the script (untimed) profiles the configuration family a
 sizes x 5 skew levels and fits the cost model, then times every configuration at every
 (T, beta) point of the model's sweep to report regret against exhaustive search, the speedup
 over static batch-size-only dispatch, and microseconds / TFLOP/s / GB/s / roofline fraction per
-point.  Rank 0 prints ONE JSON line at the end; the tables go to stderr and gpurun_out/.
+point.  Rank 0 prints ONE JSON line at the end; the tables go to stderr and to the --out folder.
 """
 from __future__ import annotations
 
