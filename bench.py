@@ -291,6 +291,50 @@ def main():
         torch.cuda.synchronize()
         async_us = (time.perf_counter() - t0s) / args.steps * 1e6
 
+    # the whole step as one HIP graph per weight copy: select on the device, then the layer behind the device-side
+    # index over the configurations the model picks at this batch size across the sweep's skew levels
+    graph_us, graph_cands = None, None
+    if fixed_cfg is None:
+        picked = []
+        for j, b in enumerate(sweep["beta"]):
+            c = tuner.select(fam, theta, tuner.Point(T_head, b, seed=900 + j).materialise(s).counts, dispatch_flags)
+            if c not in picked:
+                picked.append(c)
+        picked = picked[:4]
+        cands = [fam.cfgs[c] for c in picked]
+        table = torch.from_numpy(ramp.select_table_build(cands, fam.ntiles[picked], fam.wave_cap[picked], theta[picked],
+                                                         dispatch_flags)).to(dev)
+        res_dev = torch.zeros(ramp.select_result_bytes(s.E, len(cands)), dtype=torch.uint8, device=dev)
+        sel_dev = torch.zeros(1, dtype=torch.int32, device=dev)
+        ws_g = layers.workspace(ramp.fused_moe_selected_workspace_bytes(rs, cands))
+        graphs = []
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for li in range(layers.n_layers):
+                def enqueue():
+                    ramp.select_device(d_ids, T_head, s.k, s.E, len(cands), table, res_dev, 1, dispatcher.ws,
+                                       best_idx_dev=sel_dev, stream=side)
+                    ramp.fused_moe_selected(rs, cands, sel_dev, X, d_ids, d_w, layers.packed[li], out, ws_g, stream=side)
+                enqueue()
+                side.synchronize()
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr, stream=side):
+                    enqueue()
+                graphs.append(gr)
+        torch.cuda.current_stream().wait_stream(side)
+        for i in range(args.warmup):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        t0s = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0s) / args.steps * 1e6
+        graph_cands = [c.key() for c in cands]
+        if cands[int(sel_dev.cpu()[0])].key() != cfg_head.key():
+            log(f"[bench] note: the graph path selected {cands[int(sel_dev.cpu()[0])]} among {len(cands)} candidates")
+
     # roofline of the dominant kernel (up-projection + SwiGLU): algorithmic flops / bytes per launch
     P = T_head * s.k
     e_act = int((p.counts > 0).sum())
@@ -311,10 +355,12 @@ def main():
                  gbs=nbytes / (ms_per_step * 1e3) * 1e-3, fused_layer_us=fused_us,
                  fused_layer_frac=max(t_hbm, t_mfma) / fused_us, dispatch_idle_us=dispatch_idle_us,
                  dispatch_host_select_idle_us=dispatch_host_idle_us, async_dispatch_us_per_step=async_us,
+                 graph_dispatch_us_per_step=graph_us, graph_candidates=graph_cands,
                  paper_dispatch_us_h200=38.0)
     log(f"[bench] headline T={T_head} beta={beta_head}: {ms_per_step * 1e3:.1f} us/step (fused layer alone {fused_us:.1f} us, "
         f"dispatch on an idle GPU {dispatch_idle_us:.1f} us device-resident / {dispatch_host_idle_us:.1f} us host select, "
-        f"{async_us if async_us is None else round(async_us, 1)} us/step with asynchronous dispatch), config {cfg_head}, "
+        f"{async_us if async_us is None else round(async_us, 1)} us/step with asynchronous dispatch, "
+        f"{graph_us if graph_us is None else round(graph_us, 1)} us/step as one HIP graph with device-side selection), config {cfg_head}, "
         f"dominant kernel {k_us:.1f} us = {roof['achieved']:.1f} {roof['unit']} ({100 * roof['frac']:.1f}% of peak)")
 
     # ------------------------------------------------------------------ CPU oracle baseline (bounded sample)

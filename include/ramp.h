@@ -243,6 +243,23 @@ int ramp_select_device(const int32_t *topk_ids /*dev [T*k]*/, int T, int k, int 
 int ramp_select_poll(const void *result_host, uint32_t ticket, int *best_idx);
 int ramp_select_wait(const void *result_host, uint32_t ticket, double timeout_s, int *best_idx);
 
+/* ---- fused layer with the configuration chosen on the device ---------------------------------------
+ * For callers that cannot branch on the host between the selection and the launch (a captured HIP graph, a
+ * host thread that must not wait): every one of the n_cand candidate configurations is enqueued, and on the
+ * device each of its launches first reads *selected_idx (written, e.g., by ramp_select_device through
+ * best_idx_dev, over a table built from the same candidates in the same order) and does nothing unless it
+ * equals the candidate's position.  One candidate runs; the others cost a few empty launches.  The result is
+ * the one ramp_fused_moe gives for that candidate, bit for bit.  If *selected_idx is outside [0, n_cand)
+ * nothing runs and `out` is undefined.  1 <= n_cand <= 16.  The workspace (size from the query below) is shared
+ * by the candidates; selected_idx must not change while the call's work is in flight. */
+size_t ramp_fused_moe_selected_workspace_bytes(const ramp_shape *shape, int n_cand, const ramp_config *cfgs);
+int ramp_fused_moe_selected(const ramp_shape *shape, int n_cand, const ramp_config *cfgs /*host [n_cand]*/,
+                            const int32_t *selected_idx /*dev*/,
+                            const void *X /*dev bf16 [T,H]*/, const int32_t *topk_ids /*dev [T,k]*/,
+                            const float *topk_w /*dev fp32 [T,k]*/, const void *packed_weights /*dev*/,
+                            void *out /*dev bf16 [T,H]*/, void *ws /*dev, 256 B aligned*/, size_t ws_bytes,
+                            void *stream);
+
 /* ---- measurement hooks --------------------------------------------------------------------------
  * ramp_probe_enable(stage): from now on every ramp_fused_moe call of this process records a
  * HIP event pair on its stream around one stage (1 = align, 2 = up-projection + SwiGLU,

@@ -173,8 +173,10 @@ size_t lds_ints(int E) { return (size_t)E + (E + 1) + NW + 1 + (size_t)NW * E; }
 // ---- single workgroup: everything in one launch ----
 __global__ __launch_bounds__(NT) void align_single_kernel(const int32_t *ids, int P, int E, int bm, int cap,
                                                           int32_t *sorted, int32_t *tile_expert, int32_t *tile_rows,
-                                                          int32_t *counts, int32_t *meta, int scatter)
+                                                          int32_t *counts, int32_t *meta, int scatter,
+                                                          const int32_t *pred, int pred_value)
 {
+    if (launch_deselected(pred, pred_value)) return;
     extern __shared__ int lds[];
     int *hist, *toff, *wsum, *misc;
     unsigned *wcnt;
@@ -208,8 +210,10 @@ constexpr int kAlignTinyMaxP = 64;
 constexpr int kAlignTinyMaxCap = 4096;
 __global__ __launch_bounds__(kWave) void align_tiny_kernel(const int32_t *ids, int P, int E, int bm, int cap,
                                                            int32_t *sorted, int32_t *tile_expert, int32_t *tile_rows,
-                                                           int32_t *counts, int32_t *meta)
+                                                           int32_t *counts, int32_t *meta, const int32_t *pred,
+                                                           int pred_value)
 {
+    if (launch_deselected(pred, pred_value)) return;
     __shared__ int n_lds[kAlignMaxE];
     __shared__ int toff[kAlignMaxE + 1];
     const int lane = threadIdx.x;
@@ -288,8 +292,10 @@ __global__ __launch_bounds__(kWave) void align_tiny_kernel(const int32_t *ids, i
 
 // ---- several workgroups: histogram per chunk -> scan -> scatter ----
 __global__ __launch_bounds__(NT) void align_hist_kernel(const int32_t *ids, int P, int E, int cap, int32_t *sorted,
-                                                        int32_t *block_counts, int32_t *block_dropped, int fill)
+                                                        int32_t *block_counts, int32_t *block_dropped, int fill,
+                                                        const int32_t *pred, int pred_value)
 {
+    if (launch_deselected(pred, pred_value)) return;
     extern __shared__ int lds[];
     int *hist = lds, *dropped = lds + E;
     for (int x = threadIdx.x; x < E; x += NT) hist[x] = 0;
@@ -343,8 +349,10 @@ __global__ __launch_bounds__(NT) void align_scan_scatter_kernel(const int32_t *i
                                                                 const int32_t *block_counts,
                                                                 const int32_t *block_dropped, int32_t *sorted,
                                                                 int32_t *tile_expert, int32_t *tile_rows,
-                                                                int32_t *counts, int32_t *meta)
+                                                                int32_t *counts, int32_t *meta, const int32_t *pred,
+                                                                int pred_value)
 {
+    if (launch_deselected(pred, pred_value)) return;
     extern __shared__ int lds[];
     int *toff = lds, *wsum = toff + E + 1, *cursor = wsum + NW;
     unsigned *wcnt = reinterpret_cast<unsigned *>(cursor + E);
@@ -398,7 +406,7 @@ int allow_lds(Kernel kernel, size_t bytes)
 // scatter = 0: histogram only (sorted / tile_expert / meta untouched, may be NULL)
 static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
                              int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes,
-                             hipStream_t stream, int scatter)
+                             hipStream_t stream, int scatter, const int32_t *pred = nullptr, int pred_value = 0)
 {
     if (T < 0 || k < 0 || E <= 0 || E > kAlignMaxE || bm < 1 || bm > 1024) {
         set_error("align: bad sizes T=%d k=%d E=%d bm=%d (need E<=%d, 1<=bm<=1024)", T, k, E, bm, kAlignMaxE);
@@ -417,14 +425,14 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
     const int cap = scatter ? (int)ramp_align_capacity(T, k, E, bm) : 0;
     if (scatter && P <= kAlignTinyMaxP && cap <= kAlignTinyMaxCap) {
         hipLaunchKernelGGL(align_tiny_kernel, dim3(1), dim3(kWave), 0, stream, ids, P, E, bm, cap, sorted, tile_expert,
-                           tile_rows, counts, meta);
+                           tile_rows, counts, meta, pred, pred_value);
         return check_launch("align_tiny_kernel");
     }
     if (P <= kAlignSingleMaxP) {
         size_t lds = lds_ints(E) * sizeof(int);
         if (int rc = allow_lds(align_single_kernel, lds)) return rc;
         hipLaunchKernelGGL(align_single_kernel, dim3(1), dim3(NT), lds, stream, ids, P, E, bm, cap, sorted,
-                           tile_expert, tile_rows, counts, meta, scatter);
+                           tile_expert, tile_rows, counts, meta, scatter, pred, pred_value);
         return check_launch("align_single_kernel");
     }
     const int B = num_blocks(P);
@@ -437,7 +445,7 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
     int32_t *block_base = block_counts + (size_t)B * E;
     int32_t *block_dropped = block_base + (size_t)B * E;
     hipLaunchKernelGGL(align_hist_kernel, dim3(B), dim3(NT), (E + 1) * sizeof(int), stream, ids, P, E, cap, sorted,
-                       block_counts, block_dropped, scatter);
+                       block_counts, block_dropped, scatter, pred, pred_value);
     int rc = check_launch("align_hist_kernel");
     if (rc) return rc;
     if (!scatter) {
@@ -448,7 +456,7 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
     const size_t scatter_lds = ((size_t)(E + 1) + NW + E + (size_t)NW * E) * sizeof(int);
     if (int rc2 = allow_lds(align_scan_scatter_kernel, scatter_lds)) return rc2;
     hipLaunchKernelGGL(align_scan_scatter_kernel, dim3(B), dim3(NT), scatter_lds, stream, ids, P, B, E, bm, cap,
-                       block_counts, block_dropped, sorted, tile_expert, tile_rows, counts, meta);
+                       block_counts, block_dropped, sorted, tile_expert, tile_rows, counts, meta, pred, pred_value);
     return check_launch("align_scan_scatter_kernel");
 }
 
@@ -464,15 +472,18 @@ int launch_chunk_histograms(const int32_t *ids, int P, int E, void *ws, size_t w
     int32_t *block_counts = static_cast<int32_t *>(ws);
     int32_t *block_dropped = block_counts + 2 * (size_t)B * E;
     hipLaunchKernelGGL(align_hist_kernel, dim3(B), dim3(NT), (E + 1) * sizeof(int), stream, ids, P, E, 0,
-                       static_cast<int32_t *>(nullptr), block_counts, block_dropped, 0);
+                       static_cast<int32_t *>(nullptr), block_counts, block_dropped, 0,
+                       static_cast<const int32_t *>(nullptr), 0);
     *B_out = B;
     return check_launch("align_hist_kernel");
 }
 
 int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
-                 int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream)
+                 int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream,
+                 const int32_t *pred, int pred_value)
 {
-    return launch_align_impl(ids, T, k, E, bm, sorted, tile_expert, tile_rows, counts, meta, ws, ws_bytes, stream, 1);
+    return launch_align_impl(ids, T, k, E, bm, sorted, tile_expert, tile_rows, counts, meta, ws, ws_bytes, stream, 1,
+                             pred, pred_value);
 }
 
 }  // namespace ramp

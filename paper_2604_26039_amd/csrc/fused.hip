@@ -297,61 +297,74 @@ extern "C" int ramp_fused_moe_workspace_layout(const ramp_shape *shape, const ra
     return RAMP_OK;
 }
 
-extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, const void *X, const int32_t *topk_ids,
-                              const float *topk_w, const void *packed_weights, void *out, void *ws, size_t ws_bytes,
-                              void *stream)
+namespace {
+
+// Checks shared by the fused entry points.  Returns RAMP_OK and the kernel of cfg, or a status.
+int check_fused_call(const char *who, const ramp_shape *shape, const ramp_config *cfg, const KernelInfo **ki)
 {
     if (!shape || !cfg) {
-        set_error("fused_moe: NULL shape or config");
+        set_error("%s: NULL shape or config", who);
         return RAMP_EINVAL;
     }
     const ramp_shape &s = *shape;
     if (!shape_ok(s)) {
-        set_error("fused_moe: unsupported shape T=%d k=%d E=%d H=%d I=%d (need H, I multiples of 128, E<=%d)", s.T, s.k,
+        set_error("%s: unsupported shape T=%d k=%d E=%d H=%d I=%d (need H, I multiples of 128, E<=%d)", who, s.T, s.k,
                   s.E, s.H, s.I, kAlignMaxE);
         return RAMP_EUNSUPPORTED;
     }
-    const KernelInfo *ki = find_kernel(*cfg);
-    if (!ki) {
-        set_error("fused_moe: configuration (bm=%d bn=%d bk=%d waves=%d stages=%d mode=%d) is not instantiated",
+    *ki = find_kernel(*cfg);
+    if (!*ki) {
+        set_error("%s: configuration (bm=%d bn=%d bk=%d waves=%d stages=%d mode=%d) is not instantiated", who,
                   cfg->bm, cfg->bn, cfg->bk, cfg->waves, cfg->stages, cfg->mode);
         return RAMP_EUNSUPPORTED;
     }
-    if (!config_valid_for_shape(*ki, s)) {
-        set_error("fused_moe: configuration bm=%d bn=%d bk=%d does not tile H=%d I=%d", cfg->bm, cfg->bn, cfg->bk, s.H,
+    if (!config_valid_for_shape(**ki, s)) {
+        set_error("%s: configuration bm=%d bn=%d bk=%d does not tile H=%d I=%d", who, cfg->bm, cfg->bn, cfg->bk, s.H,
                   s.I);
         return RAMP_EUNSUPPORTED;
     }
-    if (s.T == 0) return RAMP_OK;
-    if (!X || !topk_ids || !topk_w || !packed_weights || !out || !ws) {
-        set_error("fused_moe: NULL buffer");
+    return RAMP_OK;
+}
+
+int check_fused_buffers(const char *who, const void *X, const void *topk_ids, const void *topk_w, const void *packed,
+                        const void *out, const void *ws)
+{
+    if (!X || !topk_ids || !topk_w || !packed || !out || !ws) {
+        set_error("%s: NULL buffer", who);
         return RAMP_EINVAL;
     }
-    if (reinterpret_cast<uintptr_t>(ws) % 256 || reinterpret_cast<uintptr_t>(packed_weights) % 256 ||
+    if (reinterpret_cast<uintptr_t>(ws) % 256 || reinterpret_cast<uintptr_t>(packed) % 256 ||
         reinterpret_cast<uintptr_t>(X) % 16 || reinterpret_cast<uintptr_t>(out) % 16) {
-        set_error("fused_moe: misaligned buffer (ws/packed 256 B, X and out 16 B)");
+        set_error("%s: misaligned buffer (ws/packed 256 B, X and out 16 B)", who);
         return RAMP_EINVAL;
     }
-    const Workspace w = workspace_layout(s, *cfg);
-    if (ws_bytes < w.total) {
-        set_error("fused_moe: workspace %zu < %zu bytes", ws_bytes, w.total);
-        return RAMP_ENOSPC;
-    }
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    char *base = static_cast<char *>(ws);
+    return RAMP_OK;
+}
+
+bool pair_rows_bf16(const ramp_shape &s)
+{
+    // per-pair rows: fp32 while they are small, bf16 once they would exceed 32 MB
+    return (size_t)s.T * s.k * s.H >= kPairRowsBf16Elems;
+}
+
+// align(bm) + both projections of one configuration; `base` holds every workspace section but the per-pair rows,
+// which go to y_buf.  With pred != NULL every launch is a no-op unless *pred == pred_value on the device.
+int enqueue_projections(const ramp_shape &s, const ramp_config &cfg, const KernelInfo &ki, const Workspace &w, const void *X,
+                        const int32_t *topk_ids, const float *topk_w, const void *packed_weights, char *base,
+                        float *y_buf, const int32_t *pred, int pred_value, hipStream_t st)
+{
     int32_t *sorted = reinterpret_cast<int32_t *>(base + w.sorted);
     int32_t *tile_expert = reinterpret_cast<int32_t *>(base + w.tile_expert);
     int32_t *tile_rows = reinterpret_cast<int32_t *>(base + w.tile_rows);
     int32_t *counts = reinterpret_cast<int32_t *>(base + w.counts);
     int32_t *meta = reinterpret_cast<int32_t *>(base + w.meta);
     uint16_t *a_buf = reinterpret_cast<uint16_t *>(base + w.a_buf);
-    float *y_buf = reinterpret_cast<float *>(base + w.y_buf);
 
     int rc;
     {
         ProbeScope probe(1, st);
-        rc = launch_align(topk_ids, s.T, s.k, s.E, cfg->bm, sorted, tile_expert, tile_rows, counts, meta, base + w.align_ws,
-                          w.align_ws_bytes, st);
+        rc = launch_align(topk_ids, s.T, s.k, s.E, cfg.bm, sorted, tile_expert, tile_rows, counts, meta, base + w.align_ws,
+                          w.align_ws_bytes, st, pred, pred_value);
     }
     if (rc) return rc;
 
@@ -366,11 +379,12 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     g.topk_w = topk_w;
     g.a_out = a_buf;
     g.y_out = y_buf;
-    // per-pair rows: fp32 while they are small, bf16 once they would exceed 32 MB
-    g.y_bf16 = ((size_t)s.T * s.k * s.H >= kPairRowsBf16Elems) ? 1 : 0;
+    g.y_bf16 = pair_rows_bf16(s) ? 1 : 0;
     g.P = s.T * s.k;
     g.topk = s.k;
-    g.m_tiles_cap = (int)(w.cap / (size_t)cfg->bm);
+    g.m_tiles_cap = (int)(w.cap / (size_t)cfg.bm);
+    g.pred = pred;
+    g.pred_value = pred_value;
 
     // phase 1 + 2: up-projection with SwiGLU epilogue
     g.act = static_cast<const uint16_t *>(X);
@@ -379,31 +393,106 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     g.up_offset = L.up_offset_elems;
     g.K = s.H;
     g.F = s.I;
-    g.n_tiles = 2 * s.I / cfg->bn;
+    g.n_tiles = 2 * s.I / cfg.bn;
     {
         ProbeScope probe(2, st);
-        ki->launch(1, g, st);
+        ki.launch(1, g, st);
     }
     rc = check_launch("moe_gemm_kernel<1>");
     if (rc) return rc;
 
-    // phase 3: down-projection, router weight applied, one fp32 row per pair
+    // phase 3: down-projection, router weight applied, one row per pair
     g.act = a_buf;
     g.wpacked = packed + L.w2_base_elems;
     g.expert_stride = L.w2_expert_elems;
     g.up_offset = 0;
     g.K = s.I;
     g.F = s.H;
-    g.n_tiles = s.H / cfg->bn;
+    g.n_tiles = s.H / cfg.bn;
     {
         ProbeScope probe(3, st);
-        ki->launch(2, g, st);
+        ki.launch(2, g, st);
     }
-    rc = check_launch("moe_gemm_kernel<2>");
-    if (rc) return rc;
+    return check_launch("moe_gemm_kernel<2>");
+}
 
+}  // namespace
+
+extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, const void *X, const int32_t *topk_ids,
+                              const float *topk_w, const void *packed_weights, void *out, void *ws, size_t ws_bytes,
+                              void *stream)
+{
+    const KernelInfo *ki = nullptr;
+    if (int rc = check_fused_call("fused_moe", shape, cfg, &ki)) return rc;
+    const ramp_shape &s = *shape;
+    if (s.T == 0) return RAMP_OK;
+    if (int rc = check_fused_buffers("fused_moe", X, topk_ids, topk_w, packed_weights, out, ws)) return rc;
+    const Workspace w = workspace_layout(s, *cfg);
+    if (ws_bytes < w.total) {
+        set_error("fused_moe: workspace %zu < %zu bytes", ws_bytes, w.total);
+        return RAMP_ENOSPC;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *base = static_cast<char *>(ws);
+    float *y_buf = reinterpret_cast<float *>(base + w.y_buf);
+    if (int rc = enqueue_projections(s, *cfg, *ki, w, X, topk_ids, topk_w, packed_weights, base, y_buf, nullptr, 0, st))
+        return rc;
     ProbeScope probe(4, st);
-    return launch_combine(y_buf, g.y_bf16, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st);
+    return launch_combine(y_buf, pair_rows_bf16(s) ? 1 : 0, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st);
+}
+
+// Workspace of the device-selected variant: the per-pair rows first (their size does not depend on the
+// configuration), then room for the other sections of the largest candidate.
+static size_t selected_rest_bytes(const ramp_shape &s, int n_cand, const ramp_config *cfgs)
+{
+    size_t rest = 0;
+    for (int c = 0; c < n_cand; ++c) {
+        const Workspace w = workspace_layout(s, cfgs[c]);
+        rest = w.y_buf > rest ? w.y_buf : rest;  // y_buf is the last section: its offset is the size of the others
+    }
+    return rest;
+}
+
+extern "C" size_t ramp_fused_moe_selected_workspace_bytes(const ramp_shape *shape, int n_cand, const ramp_config *cfgs)
+{
+    if (!shape || !cfgs || n_cand <= 0 || !shape_ok(*shape)) return 0;
+    for (int c = 0; c < n_cand; ++c)
+        if (cfgs[c].bm <= 0) return 0;
+    return align_up((size_t)shape->T * shape->k * shape->H * 4, 256) + selected_rest_bytes(*shape, n_cand, cfgs);
+}
+
+extern "C" int ramp_fused_moe_selected(const ramp_shape *shape, int n_cand, const ramp_config *cfgs,
+                                       const int32_t *selected_idx, const void *X, const int32_t *topk_ids,
+                                       const float *topk_w, const void *packed_weights, void *out, void *ws,
+                                       size_t ws_bytes, void *stream)
+{
+    if (n_cand <= 0 || n_cand > 16 || !cfgs || !selected_idx) {
+        set_error("fused_moe_selected: need 1..16 candidate configurations and a device index");
+        return RAMP_EINVAL;
+    }
+    const KernelInfo *ki[16];
+    for (int c = 0; c < n_cand; ++c)
+        if (int rc = check_fused_call("fused_moe_selected", shape, &cfgs[c], &ki[c])) return rc;
+    const ramp_shape &s = *shape;
+    if (s.T == 0) return RAMP_OK;
+    if (int rc = check_fused_buffers("fused_moe_selected", X, topk_ids, topk_w, packed_weights, out, ws)) return rc;
+    const size_t need = ramp_fused_moe_selected_workspace_bytes(shape, n_cand, cfgs);
+    if (ws_bytes < need) {
+        set_error("fused_moe_selected: workspace %zu < %zu bytes", ws_bytes, need);
+        return RAMP_ENOSPC;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *y_buf = static_cast<float *>(ws);
+    char *base = static_cast<char *>(ws) + align_up((size_t)s.T * s.k * s.H * 4, 256);
+    // every candidate is enqueued; on the device only the one whose position equals *selected_idx does anything
+    for (int c = 0; c < n_cand; ++c) {
+        const Workspace w = workspace_layout(s, cfgs[c]);
+        if (int rc = enqueue_projections(s, cfgs[c], *ki[c], w, X, topk_ids, topk_w, packed_weights, base, y_buf,
+                                         selected_idx, c, st))
+            return rc;
+    }
+    ProbeScope probe(4, st);
+    return launch_combine(y_buf, pair_rows_bf16(s) ? 1 : 0, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st);
 }
 
 extern "C" int ramp_probe_enable(int stage)

@@ -224,6 +224,7 @@ __global__ __launch_bounds__(WM *WN * 64, (TileTraits<BM, BN, BK, WM, WN, NSTAGE
 
     __shared__ __attribute__((aligned(1024))) uint16_t lds[NSTAGE * TT::BUF_ELEMS];
 
+    if (launch_deselected(a.pred, a.pred_value)) return;
     int n_tile, m_tile;
     tile_of_workgroup(a, n_tile, m_tile);
     if (m_tile >= a.meta[1]) return;  // overlaunched grid: surplus workgroups leave at once

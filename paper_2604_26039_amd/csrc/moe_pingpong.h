@@ -83,6 +83,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     constexpr int FEAT_PER_TILE = (STAGE == 1) ? BN / 2 : BN;
     constexpr int XS = PT::XS, NX = PT::NX, TSLOTS = PT::TSLOTS, WSLOTS = PT::WSLOTS;
 
+    if (launch_deselected(a.pred, a.pred_value)) return;
     __shared__ __attribute__((aligned(1024))) char lds[PT::LDS_BYTES];
     char *const lds_x = lds;
     char *const lds_w = lds + NX * PT::X_BYTES;

@@ -41,6 +41,7 @@ __global__ __launch_bounds__(WF *WK * 64) void moe_stream_kernel(GemmArgs a)
 
     __shared__ __attribute__((aligned(16))) float red[ST::RED_FLOATS > 0 ? ST::RED_FLOATS : 4];
 
+    if (launch_deselected(a.pred, a.pred_value)) return;
     const int n_tile = blockIdx.x % a.n_tiles;
     const int m_tile = blockIdx.x / a.n_tiles;
     if (m_tile >= a.meta[1]) return;

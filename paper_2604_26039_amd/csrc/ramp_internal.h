@@ -35,7 +35,8 @@ constexpr int kAlignSingleMaxP = 2048; // up to this many pairs one workgroup do
 constexpr int kAlignMaxE = 1024;
 
 int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
-                 int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream);
+                 int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream,
+                 const int32_t *pred = nullptr, int pred_value = 0);
 
 // ---- packed weights ----
 // One fragment = 16 weight rows x 32 k-values = 512 bf16 = 1 KB, stored in the lane order
@@ -93,7 +94,14 @@ struct GemmArgs {
     int m_tiles_cap;            // launched M-tiles (upper bound)
     int group_m, group_n;       // M-tiles x N-tiles per XCD block of the workgroup->tile map (set by the launcher)
     int total_tiles;            // persistent kernels: tile ids to walk (set by the launcher)
+    const int32_t *pred;        // device-side predicate: the launch does nothing unless *pred == pred_value (NULL: always runs)
+    int pred_value;
 };
+// True when a predicated launch is not the one selected on the device.
+__device__ __forceinline__ bool launch_deselected(const int32_t *pred, int pred_value)
+{
+    return pred != nullptr && *pred != pred_value;
+}
 
 // ramp_config.mode: bits 0-7 = WM-1 (token split of the wavefront grid), then the kernel family
 constexpr int kModeStream = 0x100;    // weight-streaming kernel (moe_stream.h); bits 0-7 = WK instead

@@ -102,6 +102,10 @@ def lib() -> ctypes.CDLL:
         L.ramp_fused_moe_workspace_layout.argtypes = [sp, cp, ctypes.POINTER(sz)]
         L.ramp_fused_moe.restype = ci
         L.ramp_fused_moe.argtypes = [sp, cp, vp, i32p, f32p, vp, vp, vp, sz, vp]
+        L.ramp_fused_moe_selected_workspace_bytes.restype = sz
+        L.ramp_fused_moe_selected_workspace_bytes.argtypes = [sp, ci, cp]
+        L.ramp_fused_moe_selected.restype = ci
+        L.ramp_fused_moe_selected.argtypes = [sp, ci, cp, i32p, vp, i32p, f32p, vp, vp, vp, sz, vp]
         L.ramp_cost_model_fit.restype = ci
         L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp, vp, ci, vp]
         L.ramp_cost_model_select.restype = ci
@@ -134,6 +138,7 @@ EXPORTS = [
     "ramp_last_error", "ramp_num_configs", "ramp_get_config", "ramp_config_ntiles", "ramp_config_wave_capacity",
     "ramp_align_capacity", "ramp_align_workspace_bytes", "ramp_moe_histogram", "ramp_moe_align", "ramp_pack_bytes",
     "ramp_pack_weights", "ramp_fused_moe_workspace_bytes", "ramp_fused_moe_workspace_layout", "ramp_fused_moe",
+    "ramp_fused_moe_selected_workspace_bytes", "ramp_fused_moe_selected",
     "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_region_classify", "ramp_select_table_bytes", "ramp_select_table_build",
     "ramp_select_result_bytes", "ramp_select_device", "ramp_select_poll", "ramp_select_wait", "ramp_copy_bytes", "ramp_probe_enable", "ramp_probe_read",
 ]
@@ -245,6 +250,20 @@ def fused_moe(shape: Shape, cfg: Config, X, topk_ids, topk_w, packed_weights, ou
     _check(lib().ramp_fused_moe(ctypes.byref(shape), ctypes.byref(cfg), _dev(X), _dev(topk_ids), _dev(topk_w),
                                 _dev(packed_weights), _dev(out), _dev(ws), ws.numel() * ws.element_size(),
                                 _stream(stream)))
+
+
+def fused_moe_selected_workspace_bytes(shape: Shape, cfgs: Sequence[Config]) -> int:
+    arr = (Config * len(cfgs))(*cfgs)
+    return lib().ramp_fused_moe_selected_workspace_bytes(ctypes.byref(shape), len(cfgs), arr)
+
+
+def fused_moe_selected(shape: Shape, cfgs: Sequence[Config], selected_idx: torch.Tensor, X, topk_ids, topk_w,
+                       packed_weights, out, ws, stream=None):
+    """Every candidate is enqueued; on the device only cfgs[selected_idx[0]] runs (selected_idx: device int32)."""
+    arr = (Config * len(cfgs))(*cfgs)
+    _check(lib().ramp_fused_moe_selected(ctypes.byref(shape), len(cfgs), arr, _dev(selected_idx), _dev(X), _dev(topk_ids),
+                                         _dev(topk_w), _dev(packed_weights), _dev(out), _dev(ws),
+                                         ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def probe_enable(stage: int):

@@ -176,3 +176,104 @@ def test_select_device_rejects_bad_arguments():
     with pytest.raises(ramp.RampError):
         ramp.select_wait(result, 7, timeout_s=20.0)
     torch.cuda.synchronize()
+
+
+def _candidates(fam):
+    """One configuration of each kernel family, small and large token blocks."""
+    pick = []
+    for want in (lambda c: c.mode & 0x100 and c.bm <= 16, lambda c: c.mode & 0x400 and c.bm == 256,
+                 lambda c: not (c.mode & 0x700) and c.bm == 64, lambda c: c.mode & 0x200):
+        pick += [c for c in fam.cfgs if want(c)][:1]
+    return pick
+
+
+@pytest.mark.parametrize("T,beta", [(1, 1.0), (96, 0.2), (700, 1.0)])
+def test_fused_moe_selected_equals_the_selected_configuration(T, beta):
+    """Every candidate is enqueued behind the device-side index; the output is bit-identical to ramp_fused_moe
+    with the candidate the index names, whichever it is; the others leave no trace in the output."""
+    s = synth.SHAPES["olmoe"]
+    fam = tuner.Family.of(s, T)
+    cands = _candidates(fam)
+    assert len(cands) == 4
+    X, Wg, Wu, Wd = synth.layer_tensors(s, T, seed=T, device=DEV, x_std=1.0)
+    rs = ramp.Shape(T, s.k, s.E, s.H, s.I)
+    packed = torch.empty(ramp.pack_bytes(rs), dtype=torch.uint8, device=DEV)
+    ramp.pack_weights(rs, Wg, Wu, Wd, packed)
+    ids, w = synth.routing(T, s, beta, seed=5)
+    d_ids = torch.from_numpy(np.ascontiguousarray(ids, np.int32)).to(DEV)
+    d_w = torch.from_numpy(np.ascontiguousarray(w, np.float32)).to(DEV)
+    nbytes = ramp.fused_moe_selected_workspace_bytes(rs, cands)
+    assert nbytes >= max(ramp.fused_moe_workspace_bytes(rs, c) for c in cands)
+    for pos, cfg in enumerate(cands):
+        ref = torch.zeros((T, s.H), dtype=torch.bfloat16, device=DEV)
+        ws1 = torch.empty(ramp.fused_moe_workspace_bytes(rs, cfg), dtype=torch.uint8, device=DEV)
+        ramp.fused_moe(rs, cfg, X, d_ids, d_w, packed, ref, ws1)
+        sel = torch.tensor([pos, -7], dtype=torch.int32, device=DEV)
+        ws = torch.full((nbytes + 1024,), 0xFF, dtype=torch.uint8, device=DEV)
+        out = torch.full((T + 1, s.H), 777.0, dtype=torch.bfloat16, device=DEV)
+        ramp.fused_moe_selected(rs, cands, sel, X, d_ids, d_w, packed, out, ws[:nbytes])
+        torch.cuda.synchronize()
+        assert (ws[nbytes:] == 0xFF).all() and (out[T] == 777.0).all()
+        assert torch.equal(out[:T].view(torch.int16), ref.view(torch.int16)), f"candidate {pos} {cfg}"
+
+
+def test_select_and_layer_in_one_hip_graph():
+    """Histogram, cost model, argmin and the layer with the chosen configuration captured once as a HIP graph: no
+    host decision between the selection and the launch.  Replays with different routing pick different candidates
+    and match the eager result of the candidate the oracle's select names."""
+    s = synth.SHAPES["olmoe"]
+    T = 96
+    fam_all = tuner.Family.of(s, T)
+    cands = _candidates(fam_all)
+    fam = tuner.Family(fam_all.shape, cands, np.array([ramp.config_ntiles(fam_all.shape, c) for c in cands], np.int32),
+                       np.array([ramp.config_wave_capacity(c) for c in cands], np.int32))
+    # coefficients under which balanced routing prefers the first candidate and skewed routing another one
+    theta = np.array([[10, 0.0, 0.00, 1e-3], [10, 0.0, 0.00, 1e-3], [10, 0.0, 0.00, 1e-3], [10, 0.0, 0.0, 1e-3]], np.float32)
+    theta[0, 2], theta[1, 2], theta[2, 2], theta[3, 2] = 0.001, 0.2, 0.05, 0.05
+    theta[0, 0], theta[1, 0] = 30.0, 10.0
+    X, Wg, Wu, Wd = synth.layer_tensors(s, T, seed=3, device=DEV, x_std=1.0)
+    rs = ramp.Shape(T, s.k, s.E, s.H, s.I)
+    packed = torch.empty(ramp.pack_bytes(rs), dtype=torch.uint8, device=DEV)
+    ramp.pack_weights(rs, Wg, Wu, Wd, packed)
+    n = len(cands)
+    table = torch.from_numpy(ramp.select_table_build(cands, fam.ntiles, fam.wave_cap, theta, ALL_FLAGS)).to(DEV)
+    result = torch.zeros(ramp.select_result_bytes(s.E, n), dtype=torch.uint8, device=DEV)  # device block: nothing is polled
+    sel = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    d_ids = torch.zeros((T, s.k), dtype=torch.int32, device=DEV)
+    d_w = torch.zeros((T, s.k), dtype=torch.float32, device=DEV)
+    out = torch.zeros((T, s.H), dtype=torch.bfloat16, device=DEV)
+    ws_sel = torch.empty(max(256, ramp.align_workspace_bytes(T, s.k, s.E)), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(ramp.fused_moe_selected_workspace_bytes(rs, cands), dtype=torch.uint8, device=DEV)
+
+    def enqueue(stream):
+        ramp.select_device(d_ids, T, s.k, s.E, n, table, result, 1, ws_sel, best_idx_dev=sel, stream=stream)
+        ramp.fused_moe_selected(rs, cands, sel, X, d_ids, d_w, packed, out, ws, stream=stream)
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue(side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            enqueue(side)
+    torch.cuda.current_stream().wait_stream(side)
+    chosen = []
+    for rep, beta in enumerate((1.0, 0.1, 1.0, 0.2)):
+        ids, w = synth.routing(T, s, beta, seed=60 + rep)
+        d_ids.copy_(torch.from_numpy(np.ascontiguousarray(ids, np.int32)))
+        d_w.copy_(torch.from_numpy(np.ascontiguousarray(w, np.float32)))
+        out.fill_(777.0)
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle_select(fam, theta, oracle_histogram(ids, s.k, s.E), ALL_FLAGS)[0]
+        assert int(sel.cpu()[0]) == want
+        chosen.append(want)
+        ref = torch.zeros_like(out)
+        ws1 = torch.empty(ramp.fused_moe_workspace_bytes(rs, cands[want]), dtype=torch.uint8, device=DEV)
+        ramp.fused_moe(rs, cands[want], X, d_ids, d_w, packed, ref, ws1)     # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), ref.view(torch.int16)), f"replay {rep} candidate {want}"
+    assert len(set(chosen)) >= 2, f"the replays should exercise more than one candidate, got {chosen}"
