@@ -120,6 +120,15 @@ def main():
     thetas = {name: tuner.fit(fam, g_fit, t_fit, counts_fit, flags) for name, flags in MODELS.items()}
     DISPATCH = "eq6_mi355x"
     theta, dispatch_flags = thetas[DISPATCH], MODELS[DISPATCH]
+    # term ablation of the dispatch model (Sec. 5.3): the same fit with the later columns zeroed, so their
+    # coefficients come out zero (minimum-norm solution): 2 terms = a + b*w, 3 terms = + c*m, 4 terms = + d*P
+    u_fit = tuner.distinct_tiles(fam, counts_fit)
+    P_fit = np.array([int(np.asarray(c).sum()) for c in counts_fit], np.int64)
+    ABLATION = {2: ramp.cost_model_fit(fam.wave_cap, g_fit, t_fit, distinct=np.zeros_like(u_fit), pairs=np.zeros_like(P_fit),
+                                       flags=dispatch_flags),
+                3: ramp.cost_model_fit(fam.wave_cap, g_fit, t_fit, distinct=u_fit, pairs=np.zeros_like(P_fit),
+                                       flags=dispatch_flags),
+                4: theta}
     if args.save_model and fixed_cfg is None:
         tuner.save_model(args.save_model, fam, theta, dispatch_flags,
                          extra=dict(model=args.model, fit_T=fit_T, fit_betas=[str(b) for b in tuner.FIT_BETAS]))
@@ -155,6 +164,7 @@ def main():
             if p.beta == 1.0 or p.beta == sweep["beta"][0]:
                 static_of_T.setdefault(p.T, int(np.argmin(t_ev[:, j])))
         regrets = {name: [] for name in MODELS}
+        abl_regrets = {k: [] for k in ABLATION}
         speedups = {}
         hdr = (f"{'T':>5} {'beta':>8} {'bH':>5} {'best us':>9} {'RA us':>9} {'static us':>9} {'regret%':>8} {'eq6 reg%':>8} "
                f"{'RA/static':>9} {'bound':>5} {'roof%':>6} {'TFLOP/s':>8} {'GB/s':>7}  best / RA / static bm")
@@ -165,15 +175,18 @@ def main():
             picks = {name: tuner.select(fam, thetas[name], p.counts, MODELS[name]) for name in MODELS}
             for name in MODELS:
                 regrets[name].append(t_ev[picks[name], j] / t_ev[best, j] - 1.0)
+            for k_terms, th_k in ABLATION.items():
+                abl_regrets[k_terms].append(t_ev[tuner.select(fam, th_k, p.counts, dispatch_flags), j] / t_ev[best, j] - 1.0)
             chosen = picks[DISPATCH]
             reg = regrets[DISPATCH][-1]
+            hot_us = tuner.time_config(layers, fam.cfgs[chosen], p, warmup=3, iters=min(args.iters, 20), budget_ms=100.0, hot=True)
             spd = t_ev[st, j] / t_ev[chosen, j]
             speedups.setdefault(str(p.beta), []).append(spd)
             t_hbm, t_mfma, nbytes, flops = tuner.roofline_lower_bound_us(s, p.T, p.counts, HBM_PEAK_TBS, MFMA_PEAK_PFLOPS)
             bound = "hbm" if t_hbm >= t_mfma else "mfma"
             frac = max(t_hbm, t_mfma) / t_ev[chosen, j]
             row = dict(T=p.T, beta=p.beta, beta_entropy=tuner.entropy_beta(p.counts), best_us=t_ev[best, j],
-                       ra_us=t_ev[chosen, j], static_us=t_ev[st, j], regret=reg, regret_eq6=regrets["eq6"][-1],
+                       ra_us=t_ev[chosen, j], ra_hot_us=hot_us, static_us=t_ev[st, j], regret=reg, regret_eq6=regrets["eq6"][-1],
                        ra_over_static=spd, bound=bound, roofline_frac=frac, roofline_frac_best=max(t_hbm, t_mfma) / t_ev[best, j],
                        tflops=flops / t_ev[chosen, j] * 1e-6, gbs=nbytes / t_ev[chosen, j] * 1e-3,
                        best_cfg=fam.cfgs[best].key(), ra_cfg=fam.cfgs[chosen].key(), static_cfg=fam.cfgs[st].key(),
@@ -188,6 +201,7 @@ def main():
                        median_regret=float(np.median(regrets[DISPATCH])),
                        mean_regret_eq6_as_printed=float(np.mean(regrets["eq6"])),
                        max_regret_eq6_as_printed=float(np.max(regrets["eq6"])),
+                       term_ablation_mean_regret={str(k): float(np.mean(v)) for k, v in abl_regrets.items()},
                        ra_over_static_geomean={b: geomean(v) for b, v in speedups.items()},
                        ra_over_static_geomean_skewed=geomean([r["ra_over_static"] for r in skew]),
                        best_over_static_geomean_skewed=geomean([r["static_us"] / r["best_us"] for r in skew]),
@@ -195,7 +209,8 @@ def main():
         log(f"[bench] sweep {time.time() - t0:.1f}s: mean regret {100 * summary['mean_regret']:.2f}% "
             f"(median {100 * summary['median_regret']:.2f}%, max {100 * summary['max_regret']:.2f}%; Eq. 6 as printed: "
             f"{100 * summary['mean_regret_eq6_as_printed']:.2f}%); RA/static geomean on skewed points "
-            f"{summary['ra_over_static_geomean_skewed']:.3f}x (exhaustive ceiling {summary['best_over_static_geomean_skewed']:.3f}x)")
+            f"{summary['ra_over_static_geomean_skewed']:.3f}x (exhaustive ceiling {summary['best_over_static_geomean_skewed']:.3f}x); "
+            f"term ablation 2/3/4: " + " / ".join(f"{100 * summary['term_ablation_mean_regret'][str(k)]:.2f}%" for k in (2, 3, 4)))
 
     if args.heldout > 0:
         rng = np.random.default_rng(7)
@@ -404,7 +419,7 @@ def main():
         "config": {"workload": f"{args.model}-shaped MoE layer H={s.H} I={s.I} E={s.E} top-{s.k}, T={T_head}, beta={beta_head}",
                    "tile_config": cfg_head.key(), "weight_copies_rotated": n_layers},
         "roofline": roof, "whole_path": whole, "cpu_baseline": cpu, "cost_model": summary,
-        "sweep": [dict(T=r["T"], beta=r["beta"], us=round(r["ra_us"], 1), best_us=round(r["best_us"], 1),
+        "sweep": [dict(T=r["T"], beta=r["beta"], us=round(r["ra_us"], 1), hot_us=round(r["ra_hot_us"], 1), best_us=round(r["best_us"], 1),
                        static_us=round(r["static_us"], 1), bound=r["bound"], roofline_frac=round(r["roofline_frac"], 3),
                        regret=round(r["regret"], 4), bm=r["ra_cfg"][0]) for r in report["points"]],
     }

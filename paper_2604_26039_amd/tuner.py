@@ -81,10 +81,11 @@ class Point:
 
 
 def time_config(layers: LayerSet, cfg: ramp.Config, pt: Point, warmup: int = 10, iters: int = 50,
-                budget_ms: float = 400.0) -> float:
+                budget_ms: float = 400.0, hot: bool = False) -> float:
     """Median time in microseconds of ramp_fused_moe(cfg) at one operating point, HIP events
     around each call, walking over the layer copies (Sec. 5.1: 10 warm-up + 50 timed, median).
-    The iteration count is cut so one measurement stays within budget_ms."""
+    The iteration count is cut so one measurement stays within budget_ms.  hot=True re-uses one
+    weight copy, so whatever part of the active experts fits the 256 MB last-level cache stays there."""
     pt.materialise(layers.shape)
     T = pt.T
     rs = layers.rs(T)
@@ -94,7 +95,7 @@ def time_config(layers: LayerSet, cfg: ramp.Config, pt: Point, warmup: int = 10,
     ws = layers.workspace(ramp.fused_moe_workspace_bytes(rs, cfg))
     X = layers.X[:T]
     out = layers.out[:T]
-    L = layers.n_layers
+    L = 1 if hot else layers.n_layers
 
     def call(i):
         ramp.fused_moe(rs, cfg, X, d_ids, d_w, layers.packed[i % L], out, ws)
