@@ -401,7 +401,19 @@ def main():
             oracle.moe(Xb, p.ids, p.w, hW[0], hW[1], hW[2], E=s.E, rows=rows)
             per_tok = (time.perf_counter() - tc) / n1
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        # the oracle's align and select on the same input, beside the layer
+        ids_flat = np.ascontiguousarray(p.ids.reshape(-1), np.int32)
+        tc = time.perf_counter()
+        for _ in range(5):
+            oracle.align(ids_flat, T_head, s.k, s.E, cfg_head.bm)
+        cpu_align_us = (time.perf_counter() - tc) / 5 * 1e6
+        bms = [c.bm for c in fam.cfgs]
+        tc = time.perf_counter()
+        for _ in range(5):
+            oracle.select(bms, fam.ntiles, fam.wave_cap, theta, p.counts, distinct_tiles=True, wave_floor=True, pairs_term=True)
+        cpu_select_us = (time.perf_counter() - tc) / 5 * 1e6
         cpu = dict(value=per_tok * T_head * 1e6, unit="us/layer", cores=threads, kind="oracle",
+                   oracle_align_us=cpu_align_us, oracle_select_us=cpu_select_us,
                    sample=f"{max(n0, n1)} of {T_head} tokens (evenly spaced rows), per-token time scaled to the full batch")
         log(f"[bench] CPU oracle: {per_tok * 1e3:.2f} ms/token on {threads} threads -> {cpu['value'] / 1e6:.2f} s/layer")
 
