@@ -277,3 +277,32 @@ def test_select_and_layer_in_one_hip_graph():
         torch.cuda.synchronize()
         assert torch.equal(out.view(torch.int16), ref.view(torch.int16)), f"replay {rep} candidate {want}"
     assert len(set(chosen)) >= 2, f"the replays should exercise more than one candidate, got {chosen}"
+
+
+def test_fused_moe_selected_with_no_candidate_selected_touches_nothing_else():
+    """An index outside the candidate list (what a rejected table leaves behind) deselects every launch: the call
+    still succeeds, stays inside its buffers, and rejects argument errors on the host."""
+    s = synth.SHAPES["olmoe"]
+    T = 40
+    fam = tuner.Family.of(s, T)
+    cands = _candidates(fam)[:2]
+    X, Wg, Wu, Wd = synth.layer_tensors(s, T, seed=2, device=DEV, x_std=1.0)
+    rs = ramp.Shape(T, s.k, s.E, s.H, s.I)
+    packed = torch.empty(ramp.pack_bytes(rs), dtype=torch.uint8, device=DEV)
+    ramp.pack_weights(rs, Wg, Wu, Wd, packed)
+    ids, w = synth.routing(T, s, 0.5, seed=1)
+    d_ids = torch.from_numpy(np.ascontiguousarray(ids, np.int32)).to(DEV)
+    d_w = torch.from_numpy(np.ascontiguousarray(w, np.float32)).to(DEV)
+    nbytes = ramp.fused_moe_selected_workspace_bytes(rs, cands)
+    ws = torch.zeros(nbytes + 512, dtype=torch.uint8, device=DEV)
+    ws[nbytes:] = 0xAB
+    out = torch.full((T + 1, s.H), 777.0, dtype=torch.bfloat16, device=DEV)
+    sel = torch.tensor([-1], dtype=torch.int32, device=DEV)
+    ramp.fused_moe_selected(rs, cands, sel, X, d_ids, d_w, packed, out, ws[:nbytes])
+    torch.cuda.synchronize()
+    assert (ws[nbytes:] == 0xAB).all() and (out[T] == 777.0).all()
+    assert (out[:T] == 0).all()          # the combine summed the zeroed per-pair rows: no projection ran
+    with pytest.raises(ramp.RampError):
+        ramp.fused_moe_selected(rs, cands, sel, X, d_ids, d_w, packed, out, ws[:nbytes - 256])   # workspace too small
+    with pytest.raises(ramp.RampError):
+        ramp.fused_moe_selected(rs, cands * 9, sel, X, d_ids, d_w, packed, out, ws[:nbytes])     # more than 16 candidates
