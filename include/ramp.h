@@ -127,7 +127,8 @@ int ramp_pack_weights(const ramp_shape *shape, const void *W_gate, const void *W
  * projections, one row per pair (already multiplied by its router weight; fp32, or bf16
  * once T*k*H reaches 8 Mi elements, where these rows dominate the memory traffic) summed in
  * fp32 in fixed j order (no atomics: results are bit-identical from run to run), one final
- * rounding to bf16.  Requires H and I to be multiples of 128 and E <= 1024.
+ * rounding to bf16.  Requires H and I to be multiples of 128, E <= 1024, k <= 1024, T*k < 2^30 and
+ * T*k <= 2^24 * k (the kernels divide pair indices by k with a 64-bit multiplication).
  * Runs align(bm) + both projections + combine on `stream`; the grid is an upper
  * bound with early exit (Sec. 4.3 "grid overlaunch"), so nothing is read back. */
 size_t ramp_fused_moe_workspace_bytes(const ramp_shape *shape, const ramp_config *cfg);
@@ -136,6 +137,19 @@ int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg,
                    const float *topk_w /*dev fp32 [T,k]*/, const void *packed_weights /*dev*/,
                    void *out /*dev bf16 [T,H]*/, void *ws /*dev, 256 B aligned*/, size_t ws_bytes,
                    void *stream);
+/* ramp_fused_moe for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is a device array inside the
+ * library image, RAMP_STATIC_WS_BYTES per GPU the library runs on, held until the process ends; the call
+ * allocates nothing and frees nothing.  Same kernels, same result bit for bit as ramp_fused_moe.
+ * Returns RAMP_ENOSPC when ramp_fused_moe_workspace_bytes(shape, cfg) exceeds RAMP_STATIC_WS_BYTES (decode- and
+ * small-prefill-sized calls fit: e.g. H=7168, I=2048, E=256, top-8 up to T=64 with bm<=16).  All calls on one
+ * GPU share the array: calls that overlap on one GPU (different streams, or replays of graphs that hold it)
+ * race and must be ordered by the caller.  Inputs and `out` are the caller's as in ramp_fused_moe. */
+#define RAMP_STATIC_WS_BYTES (64u << 20)
+int ramp_fused_moe_static(const ramp_shape *shape, const ramp_config *cfg,
+                          const void *X /*dev bf16 [T,H]*/, const int32_t *topk_ids /*dev [T,k]*/,
+                          const float *topk_w /*dev fp32 [T,k]*/, const void *packed_weights /*dev*/,
+                          void *out /*dev bf16 [T,H]*/, void *stream);
 /* Where ramp_fused_moe leaves the align result inside its workspace (byte offsets),
  * for tests: sorted_pair_ids, tile_expert, expert_counts, meta. */
 int ramp_fused_moe_workspace_layout(const ramp_shape *shape, const ramp_config *cfg,
@@ -178,6 +192,12 @@ int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts, const int
 int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
                            const int32_t *wave_cap, const float *theta,
                            const int32_t *expert_counts, int flags, int *best_idx, double *pred_us);
+
+/* Eq. 1 for every configuration on one histogram (host [E]): grid[c] = (sum_e ceil(n_e/bm_c)) * ntiles[c], the
+ * g of Eq. 6.  Optional outputs (may be NULL): distinct[c] = #{e: n_e > 0} * ntiles[c] (the column of
+ * RAMP_CM_DISTINCT_TILES) and *pairs = sum_e n_e (the column of RAMP_CM_PAIRS).  Host only. */
+int ramp_grid(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles, const int32_t *expert_counts,
+              int64_t *grid /*host out [n_cfg]*/, int64_t *distinct /*host out [n_cfg]*/, int64_t *pairs /*host out*/);
 
 /* ---- performance-region variables (Sec. 4.1: Eq. 2-5, Tab. 2) ------------------------------------
  * The four quantities the paper uses to say which optimisation modes belong in a model's pool, for
@@ -250,7 +270,7 @@ int ramp_select_wait(const void *result_host, uint32_t ticket, double timeout_s,
  * best_idx_dev, over a table built from the same candidates in the same order) and does nothing unless it
  * equals the candidate's position.  One candidate runs; the others cost a few empty launches.  The result is
  * the one ramp_fused_moe gives for that candidate, bit for bit.  If *selected_idx is outside [0, n_cand)
- * nothing runs and `out` is undefined.  1 <= n_cand <= 16.  The workspace (size from the query below) is shared
+ * nothing runs, the combine included, and `out` keeps its previous contents.  1 <= n_cand <= 16.  The workspace (size from the query below) is shared
  * by the candidates; selected_idx must not change while the call's work is in flight. */
 size_t ramp_fused_moe_selected_workspace_bytes(const ramp_shape *shape, int n_cand, const ramp_config *cfgs);
 int ramp_fused_moe_selected(const ramp_shape *shape, int n_cand, const ramp_config *cfgs /*host [n_cand]*/,
@@ -265,7 +285,8 @@ int ramp_fused_moe_selected(const ramp_shape *shape, int n_cand, const ramp_conf
  * HIP event pair on its stream around one stage (1 = align, 2 = up-projection + SwiGLU,
  * 3 = down-projection, 4 = combine; 0 = off).  At most 4096 pairs are kept between reads.
  * ramp_probe_read: waits for the recorded events, returns the summed stage time and the
- * number of launches, and clears the list.  For benchmarks; not thread safe. */
+ * number of launches, and clears the list.  The list is guarded by a mutex; a call whose stream is being
+ * captured into a graph records nothing.  Read only when no probed call is in progress on another thread. */
 int ramp_probe_enable(int stage);
 int ramp_probe_read(double *total_ms /*host*/, int *launches /*host*/);
 

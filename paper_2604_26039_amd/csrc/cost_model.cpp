@@ -192,6 +192,37 @@ extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs,
     return RAMP_OK;
 }
 
+// Eq. 1 for every configuration on one histogram, with the other two histogram sums the model's columns use.
+extern "C" int ramp_grid(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles, const int32_t *expert_counts,
+                         int64_t *grid, int64_t *distinct, int64_t *pairs)
+{
+    if (E <= 0 || n_cfg <= 0 || !cfgs || !ntiles || !expert_counts || !grid) {
+        ramp::set_error("grid: bad argument");
+        return RAMP_EINVAL;
+    }
+    int64_t active = 0, total = 0;
+    for (int e = 0; e < E; ++e) {
+        active += expert_counts[e] > 0 ? 1 : 0;
+        total += expert_counts[e] > 0 ? expert_counts[e] : 0;
+    }
+    for (int c = 0; c < n_cfg; ++c) {
+        const int bm = cfgs[c].bm;
+        if (bm <= 0 || ntiles[c] <= 0) {
+            ramp::set_error("grid: config %d has bm=%d ntiles=%d", c, bm, ntiles[c]);
+            return RAMP_EINVAL;
+        }
+        int64_t mt = 0;
+        for (int e = 0; e < E; ++e) {
+            const int64_t n = expert_counts[e] > 0 ? expert_counts[e] : 0;
+            mt += (n + bm - 1) / bm;
+        }
+        grid[c] = mt * (int64_t)ntiles[c];
+        if (distinct) distinct[c] = active * (int64_t)ntiles[c];
+    }
+    if (pairs) *pairs = total;
+    return RAMP_OK;
+}
+
 // ---- performance-region variables (Sec. 4.1, Eq. 2-5, Tab. 2) ----
 extern "C" int ramp_region_classify(const ramp_shape *shape, const ramp_config *cfg, long long grid,
                                     const ramp_region_thresholds *thresholds, ramp_region *out)

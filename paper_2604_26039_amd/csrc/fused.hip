@@ -44,10 +44,17 @@ void init_registry()
 // out[t,:] = sum_j Y[t*k+j,:] in increasing j, fp32, one rounding to bf16.  The router weight
 // was applied by the down-projection epilogue.  Pairs with an invalid expert id have no row.
 // Y rows are fp32, or bf16 (Y16) for large batches.
+// With sel != NULL (device-selected layer) the kernel leaves `out` untouched unless *sel names one of the
+// n_cand candidates: no projection has run then and Y holds whatever an earlier call left.
 template <bool Y16>
 __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ Y, const int32_t *__restrict__ ids, int T,
-                                                      int k, int E, int H, uint16_t *__restrict__ out)
+                                                      int k, int E, int H, uint16_t *__restrict__ out,
+                                                      const int32_t *__restrict__ sel, int n_cand)
 {
+    if (sel != nullptr) {
+        const int idx = *sel;
+        if (idx < 0 || idx >= n_cand) return;
+    }
     const int hv = H / 8;  // 8-feature columns: one 16-byte bf16 load (or two fp32 ones) per pair row
     const size_t total = (size_t)T * hv;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
@@ -93,7 +100,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
 }
 
 // ---- stage probe (benchmark instrumentation) ----
+// One process-wide list of HIP-event pairs, guarded by a mutex.  A call whose stream is being captured into a
+// graph records nothing (event records would become graph nodes).
 constexpr int kMaxProbe = 4096;
+std::mutex g_probe_mutex;
 int g_probe_stage = 0;
 int g_probe_used = 0;
 int g_probe_created = 0;
@@ -101,20 +111,33 @@ hipEvent_t g_probe_ev[kMaxProbe][2];
 
 struct ProbeScope {
     bool on;
+    int slot;
     hipStream_t st;
-    ProbeScope(int stage, hipStream_t stream) : on(false), st(stream)
+    ProbeScope(int stage, hipStream_t stream) : on(false), slot(-1), st(stream)
     {
+        if (stage != g_probe_stage) return;  // unlocked fast path for the common case (probe off)
+        std::lock_guard<std::mutex> lock(g_probe_mutex);
         if (stage != g_probe_stage || g_probe_used >= kMaxProbe) return;
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return;
         if (g_probe_used >= g_probe_created) {
-            if (hipEventCreate(&g_probe_ev[g_probe_created][0]) != hipSuccess) return;
-            if (hipEventCreate(&g_probe_ev[g_probe_created][1]) != hipSuccess) return;
+            hipEvent_t e0, e1;
+            if (hipEventCreate(&e0) != hipSuccess) return;
+            if (hipEventCreate(&e1) != hipSuccess) {
+                (void)hipEventDestroy(e0);
+                return;
+            }
+            g_probe_ev[g_probe_created][0] = e0;
+            g_probe_ev[g_probe_created][1] = e1;
             ++g_probe_created;
         }
-        on = hipEventRecord(g_probe_ev[g_probe_used][0], st) == hipSuccess;
+        slot = g_probe_used++;
+        on = hipEventRecord(g_probe_ev[slot][0], st) == hipSuccess;
+        if (!on) --g_probe_used;  // still under the lock: the slot was the last one handed out
     }
     ~ProbeScope()
     {
-        if (on && hipEventRecord(g_probe_ev[g_probe_used][1], st) == hipSuccess) ++g_probe_used;
+        if (on) (void)hipEventRecord(g_probe_ev[slot][1], st);
     }
 };
 
@@ -148,10 +171,17 @@ Workspace workspace_layout(const ramp_shape &s, const ramp_config &c)
     return w;
 }
 
+// pair / k by multiplication: ceil(2^40 / k).  Exact for pair < 2^30 when k <= 1024 (the error term pair * (magic*k -
+// 2^40) stays below 2^40); the 64-bit product must not overflow, which bounds the pairs by 2^64 / magic.
+unsigned long long topk_magic_of(int k) { return ((1ull << 40) + (unsigned long long)k - 1) / (unsigned long long)k; }
+
 bool shape_ok(const ramp_shape &s)
 {
-    return s.T >= 0 && s.k >= 1 && s.E >= 1 && s.E <= kAlignMaxE && s.H >= 128 && s.I >= 128 && s.H % 128 == 0 &&
-           s.I % 128 == 0 && (long long)s.T * s.k < (1ll << 30);
+    if (!(s.T >= 0 && s.k >= 1 && s.k <= 1024 && s.E >= 1 && s.E <= kAlignMaxE && s.H >= 128 && s.I >= 128 &&
+          s.H % 128 == 0 && s.I % 128 == 0 && (long long)s.T * s.k < (1ll << 30)))
+        return false;
+    const unsigned long long P = (unsigned long long)s.T * (unsigned long long)s.k;
+    return P <= ~0ull / topk_magic_of(s.k);
 }
 
 }  // namespace
@@ -208,16 +238,16 @@ int occupancy_estimate(const KernelInfo &ki)
 }
 
 int launch_combine(const float *Y, int y_bf16, const int32_t *ids, int T, int k, int E, int H, uint16_t *out,
-                   hipStream_t stream)
+                   hipStream_t stream, const int32_t *sel, int n_cand)
 {
     if (T == 0) return RAMP_OK;
     size_t total = (size_t)T * (H / 8);
     unsigned grid = (unsigned)((total + 255) / 256);
     if (grid > (unsigned)kNumCU * 16) grid = kNumCU * 16;
     if (y_bf16)
-        hipLaunchKernelGGL(combine_kernel<true>, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out);
+        hipLaunchKernelGGL(combine_kernel<true>, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out, sel, n_cand);
     else
-        hipLaunchKernelGGL(combine_kernel<false>, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out);
+        hipLaunchKernelGGL(combine_kernel<false>, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out, sel, n_cand);
     return check_launch("combine_kernel");
 }
 
@@ -374,7 +404,7 @@ int enqueue_projections(const ramp_shape &s, const ramp_config &cfg, const Kerne
     g.sorted = sorted;
     g.tile_expert = tile_expert;
     g.tile_rows = tile_rows;
-    g.topk_magic = ((1ull << 40) + (unsigned long long)s.k - 1) / (unsigned long long)s.k;
+    g.topk_magic = topk_magic_of(s.k);
     g.meta = meta;
     g.topk_w = topk_w;
     g.a_out = a_buf;
@@ -441,6 +471,61 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     return launch_combine(y_buf, pair_rows_bf16(s) ? 1 : 0, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st);
 }
 
+// ---- fused layer for callers that cannot allocate -------------------------------------------------------------
+// The workspace of ramp_fused_moe (align result, activation A, per-pair rows Y) lives in a device array that is
+// part of the library image: every GPU the library runs on holds its own copy at its own address until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address it returns
+// for the current device is what kernels and size checks use.
+static __device__ __align__(256) unsigned char scratch[RAMP_STATIC_WS_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device), or NULL with the error set.
+void *static_workspace()
+{
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        set_error("fused_moe_static: hipGetDevice: %s (device %d)", hipGetErrorString(err), dev);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !ptr) {
+            set_error("fused_moe_static: hipGetSymbolAddress: %s", hipGetErrorString(err));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int ramp_fused_moe_static(const ramp_shape *shape, const ramp_config *cfg, const void *X,
+                                     const int32_t *topk_ids, const float *topk_w, const void *packed_weights, void *out,
+                                     void *stream)
+{
+    const KernelInfo *ki = nullptr;
+    if (int rc = check_fused_call("fused_moe_static", shape, cfg, &ki)) return rc;
+    const size_t need = workspace_layout(*shape, *cfg).total;
+    if (need > (size_t)RAMP_STATIC_WS_BYTES) {
+        set_error("fused_moe_static: this shape and configuration need %zu bytes of workspace, the built-in one has %zu; "
+                  "use ramp_fused_moe with a caller-provided workspace",
+                  need, (size_t)RAMP_STATIC_WS_BYTES);
+        return RAMP_ENOSPC;
+    }
+    if (shape->T == 0) return RAMP_OK;
+    void *ws = static_workspace();
+    if (!ws) return RAMP_EHIP;
+    // nothing in the workspace has to start at zero: every section is written before it is read
+    return ramp_fused_moe(shape, cfg, X, topk_ids, topk_w, packed_weights, out, ws, (size_t)RAMP_STATIC_WS_BYTES, stream);
+}
+
 // Workspace of the device-selected variant: the per-pair rows first (their size does not depend on the
 // configuration), then room for the other sections of the largest candidate.
 static size_t selected_rest_bytes(const ramp_shape &s, int n_cand, const ramp_config *cfgs)
@@ -492,7 +577,8 @@ extern "C" int ramp_fused_moe_selected(const ramp_shape *shape, int n_cand, cons
             return rc;
     }
     ProbeScope probe(4, st);
-    return launch_combine(y_buf, pair_rows_bf16(s) ? 1 : 0, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st);
+    return launch_combine(y_buf, pair_rows_bf16(s) ? 1 : 0, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st,
+                          selected_idx, n_cand);
 }
 
 extern "C" int ramp_probe_enable(int stage)
@@ -501,6 +587,7 @@ extern "C" int ramp_probe_enable(int stage)
         set_error("probe_enable: stage must be 0..4");
         return RAMP_EINVAL;
     }
+    std::lock_guard<std::mutex> lock(g_probe_mutex);
     g_probe_stage = stage;
     return RAMP_OK;
 }
@@ -511,6 +598,7 @@ extern "C" int ramp_probe_read(double *total_ms, int *launches)
         set_error("probe_read: NULL argument");
         return RAMP_EINVAL;
     }
+    std::lock_guard<std::mutex> lock(g_probe_mutex);
     double sum = 0.0;
     for (int i = 0; i < g_probe_used; ++i) {
         float ms = 0.f;

@@ -42,11 +42,11 @@ int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorte
 // One fragment = 16 weight rows x 32 k-values = 512 bf16 = 1 KB, stored in the lane order
 // of the A operand of v_mfma_f32_16x16x32_bf16: element (row r, k = 8*q + j) at (q*16 + r)*8 + j.
 constexpr int kFragElems = 512;
-// Which output feature sits in row r of packed row block rb.  Inside every group of 8 row blocks
-// (128 features) the rows are interleaved so that, after the MFMA, lane group q of a wavefront holds
+// Which output feature sits in row r of packed row block rb.  Inside every group of 4 row blocks
+// (64 features) the rows are interleaved so that, after the MFMA, lane group q of a wavefront holds
 // 4 consecutive features per row block it owns, consecutive row blocks continuing the run: a lane
-// that owns all 8 row blocks of a group stores 32 consecutive features (64 B of bf16) per token
-// instead of 8 separate 8-byte pieces.  Pure relabelling: the packing kernel and the epilogues agree.
+// that owns all 4 row blocks of a group stores 16 consecutive features (32 B of bf16) per token
+// instead of 4 separate 8-byte pieces.  Pure relabelling: the packing kernel and the epilogues agree.
 constexpr int kPermBlocks = 4;
 __host__ __device__ inline int packed_row_feature(int rb, int r)
 {
@@ -121,7 +121,8 @@ const KernelInfo *find_kernel(const ramp_config &cfg);
 bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s);
 int occupancy_estimate(const KernelInfo &ki);
 
+// sel != NULL: the launch leaves `out` untouched unless 0 <= *sel < n_cand (device-selected layer).
 int launch_combine(const float *Y, int y_bf16, const int32_t *ids, int T, int k, int E, int H, uint16_t *out,
-                   hipStream_t stream);
+                   hipStream_t stream, const int32_t *sel = nullptr, int n_cand = 0);
 
 }  // namespace ramp

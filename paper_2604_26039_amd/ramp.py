@@ -102,6 +102,8 @@ def lib() -> ctypes.CDLL:
         L.ramp_fused_moe_workspace_layout.argtypes = [sp, cp, ctypes.POINTER(sz)]
         L.ramp_fused_moe.restype = ci
         L.ramp_fused_moe.argtypes = [sp, cp, vp, i32p, f32p, vp, vp, vp, sz, vp]
+        L.ramp_fused_moe_static.restype = ci
+        L.ramp_fused_moe_static.argtypes = [sp, cp, vp, i32p, f32p, vp, vp, vp]
         L.ramp_fused_moe_selected_workspace_bytes.restype = sz
         L.ramp_fused_moe_selected_workspace_bytes.argtypes = [sp, ci, cp]
         L.ramp_fused_moe_selected.restype = ci
@@ -110,6 +112,8 @@ def lib() -> ctypes.CDLL:
         L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp, vp, ci, vp]
         L.ramp_cost_model_select.restype = ci
         L.ramp_cost_model_select.argtypes = [ci, ci, cp, vp, vp, vp, vp, ci, ctypes.POINTER(ci), vp]
+        L.ramp_grid.restype = ci
+        L.ramp_grid.argtypes = [ci, ci, cp, vp, vp, vp, vp, vp]
         L.ramp_region_classify.restype = ci
         L.ramp_region_classify.argtypes = [sp, cp, ctypes.c_longlong, ctypes.POINTER(RegionThresholds), ctypes.POINTER(Region)]
         L.ramp_select_table_bytes.restype = sz
@@ -137,9 +141,9 @@ def lib() -> ctypes.CDLL:
 EXPORTS = [
     "ramp_last_error", "ramp_num_configs", "ramp_get_config", "ramp_config_ntiles", "ramp_config_wave_capacity",
     "ramp_align_capacity", "ramp_align_workspace_bytes", "ramp_moe_histogram", "ramp_moe_align", "ramp_pack_bytes",
-    "ramp_pack_weights", "ramp_fused_moe_workspace_bytes", "ramp_fused_moe_workspace_layout", "ramp_fused_moe",
+    "ramp_pack_weights", "ramp_fused_moe_workspace_bytes", "ramp_fused_moe_workspace_layout", "ramp_fused_moe", "ramp_fused_moe_static",
     "ramp_fused_moe_selected_workspace_bytes", "ramp_fused_moe_selected",
-    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_region_classify", "ramp_select_table_bytes", "ramp_select_table_build",
+    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_grid", "ramp_region_classify", "ramp_select_table_bytes", "ramp_select_table_build",
     "ramp_select_result_bytes", "ramp_select_device", "ramp_select_poll", "ramp_select_wait", "ramp_copy_bytes", "ramp_probe_enable", "ramp_probe_read",
 ]
 
@@ -252,6 +256,15 @@ def fused_moe(shape: Shape, cfg: Config, X, topk_ids, topk_w, packed_weights, ou
                                 _stream(stream)))
 
 
+STATIC_WS_BYTES = 64 << 20
+
+
+def fused_moe_static(shape: Shape, cfg: Config, X, topk_ids, topk_w, packed_weights, out, stream=None):
+    """ramp_fused_moe on the library's built-in workspace (no allocation anywhere)."""
+    _check(lib().ramp_fused_moe_static(ctypes.byref(shape), ctypes.byref(cfg), _dev(X), _dev(topk_ids), _dev(topk_w),
+                                       _dev(packed_weights), _dev(out), _stream(stream)))
+
+
 def fused_moe_selected_workspace_bytes(shape: Shape, cfgs: Sequence[Config]) -> int:
     arr = (Config * len(cfgs))(*cfgs)
     return lib().ramp_fused_moe_selected_workspace_bytes(ctypes.byref(shape), len(cfgs), arr)
@@ -319,6 +332,20 @@ def cost_model_select(E: int, cfgs: Sequence[Config], ntiles, wave_cap, theta, e
     _check(lib().ramp_cost_model_select(E, n, arr, nt.ctypes.data, wc.ctypes.data, th.ctypes.data, counts.ctypes.data,
                                         flags, ctypes.byref(best), pred.ctypes.data if want_pred else None))
     return (best.value, pred) if want_pred else best.value
+
+
+def grid(E: int, cfgs: Sequence[Config], ntiles, expert_counts):
+    """Eq. 1 per configuration on one histogram: (grid int64 [n_cfg], distinct int64 [n_cfg], pairs int)."""
+    n = len(cfgs)
+    arr = (Config * n)(*cfgs)
+    nt = _np(ntiles, np.int32)
+    counts = _np(expert_counts, np.int32)
+    assert counts.size == E and nt.size == n
+    g, d = np.zeros(n, np.int64), np.zeros(n, np.int64)
+    pairs = ctypes.c_int64(0)
+    _check(lib().ramp_grid(E, n, arr, nt.ctypes.data, counts.ctypes.data, g.ctypes.data, d.ctypes.data,
+                           ctypes.addressof(pairs)))
+    return g, d, int(pairs.value)
 
 
 # ----------------------------------------------------------------------------- device-resident dispatch

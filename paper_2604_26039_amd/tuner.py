@@ -139,9 +139,8 @@ class Family:
                       np.array([ramp.config_wave_capacity(c) for c in cfgs], np.int32))
 
     def grid(self, counts: np.ndarray) -> np.ndarray:
-        """Eq. 1 for every configuration."""
-        c = np.asarray(counts, np.int64)
-        return np.array([int((-(-c // cfg.bm)).sum()) * int(nt) for cfg, nt in zip(self.cfgs, self.ntiles)], np.int64)
+        """Eq. 1 for every configuration (computed by the library)."""
+        return ramp.grid(self.shape.E, self.cfgs, self.ntiles, counts)[0]
 
 
 def profile(layers: LayerSet, fam: Family, points: Sequence[Point], log=None, **timing) -> tuple:
@@ -166,16 +165,15 @@ MI355X_MODEL = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES | ramp.CM_WAVE_FLOOR | 
 
 
 def distinct_tiles(fam: Family, counts_list: Sequence[np.ndarray]) -> np.ndarray:
-    """[n_cfg, n_pts]: active experts x ntiles(c), the distinct weight tiles a point touches."""
-    active = np.array([int((np.asarray(c) > 0).sum()) for c in counts_list], np.int64)
-    return fam.ntiles.astype(np.int64)[:, None] * active[None, :]
+    """[n_cfg, n_pts]: active experts x ntiles(c), the distinct weight tiles a point touches (from the library)."""
+    return np.stack([ramp.grid(fam.shape.E, fam.cfgs, fam.ntiles, c)[1] for c in counts_list], axis=1)
 
 
 def fit(fam: Family, grid: np.ndarray, t_us: np.ndarray, counts_list=None, flags: int = ramp.CM_EQ6) -> np.ndarray:
     distinct = distinct_tiles(fam, counts_list) if (flags & ramp.CM_DISTINCT_TILES) else None
     pairs = None
     if flags & ramp.CM_PAIRS:
-        pairs = np.array([int(np.asarray(c).sum()) for c in counts_list], np.int64)
+        pairs = np.array([ramp.grid(fam.shape.E, fam.cfgs, fam.ntiles, c)[2] for c in counts_list], np.int64)
     return ramp.cost_model_fit(fam.wave_cap, grid, t_us, distinct=distinct, pairs=pairs, flags=flags)
 
 

@@ -348,3 +348,71 @@ def test_large_layers_sampled_rows(name, T, beta, n):
     for cfg in pick_configs(L.rs, bms=(32, 256)):
         out = L.run(cfg, ids, w, poison=False)
         assert_close(out[torch.tensor(rows, device=DEV)], ref, f"{name} T={T} beta={beta} {cfg}")
+
+
+# ----------------------------------------------------------------------------- the largest benchmark points
+
+_LAYERS = {}
+
+
+def big_layer(name, T_max=8192):
+    """One resident layer per shape for the large cases (the DeepSeek-V3-shaped one is 45 GB with its packed copy);
+    switching shape frees the previous one."""
+    if name not in _LAYERS:
+        _LAYERS.clear()
+        torch.cuda.empty_cache()
+        _LAYERS[name] = Layer(synth.SHAPES[name], T_max, seed=3, x_std=1.0)
+    return _LAYERS[name]
+
+
+def large_tile_configs(rs):
+    """Every persistent ping-pong configuration valid for the shape (what the large batches dispatch), plus the
+    first LDS-ring configuration of each large token block and one mid-size block."""
+    cfgs = ramp.configs(rs)
+    picked = [c for c in cfgs if c.mode & 0x400]
+    assert any(c.key()[:5] == (256, 256, 32, 8, 3) for c in picked) and any(c.key()[:5] == (256, 256, 32, 8, 4) for c in picked)
+    seen = set()
+    for c in cfgs:
+        if not (c.mode & 0x500) and c.bm in (64, 128, 256) and c.bm not in seen:
+            seen.add(c.bm)
+            picked.append(c)
+    return picked
+
+
+LARGEST = [("mixtral", 8192, 1.0, 8), ("mixtral", 8192, "zipf1.2", 8), ("dsv3", 8192, 1.0, 6), ("dsv3", 8192, 0.1, 6),
+           ("dsv3", 512, 1.0, 6), ("qwen3", 2048, 0.08, 24), ("qwen3", 8192, 0.3, 24), ("olmoe", 4096, 0.5, 24)]
+
+
+@pytest.mark.parametrize("name,T,beta,n", LARGEST)
+def test_largest_points_sampled_rows_on_the_dispatched_kernels(name, T, beta, n):
+    """Sampled token rows (seeded, plus tokens of the most and the least loaded expert) against the oracle at the
+    largest benchmark points, on every ping-pong configuration: persistent workgroups walk many tiles each, the
+    per-pair rows are bf16 and leave through the staged epilogue."""
+    L = big_layer(name)
+    s = L.s
+    ids, w = synth.routing(T, s, beta, seed=T + 5)
+    rows = sample_rows(ids, s.E, n, seed=7)
+    ref = L.oracle_rows(ids, w, rows=rows, T=T)
+    sel = torch.tensor(rows, device=DEV)
+    rs = ramp.Shape(T, s.k, s.E, s.H, s.I)
+    for cfg in large_tile_configs(rs):
+        print(f"case {name} T={T} beta={beta} {cfg}", flush=True)
+        out = L.run(cfg, ids, w, T=T, poison=False)
+        assert_close(out[sel], ref, f"{name} T={T} beta={beta} {cfg}")
+        assert torch.isfinite(out.float()).all()
+
+
+@pytest.mark.parametrize("name,T,beta", [("olmoe", 4096, 1.0), ("olmoe", 4096, 0.1), ("mixtral", 8192, "zipf1.2"), ("dsv3", 8192, 1.0)])
+def test_largest_points_run_twice_bit_identical(name, T, beta):
+    """No atomics anywhere, so two runs of one configuration give the same bits; at these sizes every persistent
+    workgroup walks several tiles (cross-tile load stream), which is what this check is for.  The second run starts
+    from a workspace full of NaN patterns."""
+    L = big_layer(name)
+    s = L.s
+    ids, w = synth.routing(T, s, beta, seed=T + 9)
+    rs = ramp.Shape(T, s.k, s.E, s.H, s.I)
+    for cfg in [c for c in ramp.configs(rs) if c.mode & 0x400]:
+        print(f"case {name} T={T} beta={beta} {cfg}", flush=True)
+        a = L.run(cfg, ids, w, T=T, poison=False).clone()
+        b = L.run(cfg, ids, w, T=T, poison=True)
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"{name} T={T} beta={beta} {cfg}"

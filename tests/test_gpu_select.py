@@ -280,8 +280,9 @@ def test_select_and_layer_in_one_hip_graph():
 
 
 def test_fused_moe_selected_with_no_candidate_selected_touches_nothing_else():
-    """An index outside the candidate list (what a rejected table leaves behind) deselects every launch: the call
-    still succeeds, stays inside its buffers, and rejects argument errors on the host."""
+    """An index outside the candidate list (what a rejected table leaves behind) deselects every launch, the combine
+    included: the call succeeds, `out` and the workspace keep their previous contents, and argument errors are
+    rejected on the host."""
     s = synth.SHAPES["olmoe"]
     T = 40
     fam = tuner.Family.of(s, T)
@@ -294,14 +295,15 @@ def test_fused_moe_selected_with_no_candidate_selected_touches_nothing_else():
     d_ids = torch.from_numpy(np.ascontiguousarray(ids, np.int32)).to(DEV)
     d_w = torch.from_numpy(np.ascontiguousarray(w, np.float32)).to(DEV)
     nbytes = ramp.fused_moe_selected_workspace_bytes(rs, cands)
-    ws = torch.zeros(nbytes + 512, dtype=torch.uint8, device=DEV)
-    ws[nbytes:] = 0xAB
+    ws = torch.full((nbytes + 512,), 0xAB, dtype=torch.uint8, device=DEV)   # stale bytes, NaN patterns as floats
     out = torch.full((T + 1, s.H), 777.0, dtype=torch.bfloat16, device=DEV)
+    for bad in (-1, len(cands), 1 << 20):
+        sel = torch.tensor([bad], dtype=torch.int32, device=DEV)
+        ramp.fused_moe_selected(rs, cands, sel, X, d_ids, d_w, packed, out, ws[:nbytes])
+        torch.cuda.synchronize()
+        assert (ws == 0xAB).all(), "a deselected launch wrote into the workspace"
+        assert (out == 777.0).all(), "a call with no candidate selected must leave `out` untouched"
     sel = torch.tensor([-1], dtype=torch.int32, device=DEV)
-    ramp.fused_moe_selected(rs, cands, sel, X, d_ids, d_w, packed, out, ws[:nbytes])
-    torch.cuda.synchronize()
-    assert (ws[nbytes:] == 0xAB).all() and (out[T] == 777.0).all()
-    assert (out[:T] == 0).all()          # the combine summed the zeroed per-pair rows: no projection ran
     with pytest.raises(ramp.RampError):
         ramp.fused_moe_selected(rs, cands, sel, X, d_ids, d_w, packed, out, ws[:nbytes - 256])   # workspace too small
     with pytest.raises(ramp.RampError):

@@ -60,6 +60,41 @@ def test_align_capacity_matches_oracle(T, k, E, bm):
     assert ramp.align_capacity(T, k, E, bm) == oracle.align_capacity(T, k, E, bm)
 
 
+@pytest.mark.parametrize("name,T,beta", [("olmoe", 256, 0.2), ("dsv3", 8192, 1.0), ("qwen3", 1, 1.0), ("mixtral", 1024, "zipf1.2")])
+def test_grid_matches_oracle(name, T, beta):
+    """ramp_grid = Eq. 1 per configuration, plus the distinct-tile and pair sums, against the oracle's Eq. 1 and a
+    plain count."""
+    s = synth.SHAPES[name]
+    sh = shape_of(name, T)
+    cfgs = ramp.configs(sh)
+    nt = [ramp.config_ntiles(sh, c) for c in cfgs]
+    ids, _ = synth.routing(T, s, beta, seed=3)
+    counts = np.zeros(s.E, np.int32)
+    for e in ids.reshape(-1):
+        counts[e] += 1
+    g, d, pairs = ramp.grid(s.E, cfgs, nt, counts)
+    assert pairs == T * s.k
+    active = int((counts > 0).sum())
+    for i, c in enumerate(cfgs):
+        assert g[i] == oracle.grid(counts, c.bm, nt[i])
+        assert d[i] == active * nt[i]
+    with pytest.raises(ramp.RampError):
+        ramp.grid(s.E, cfgs, [0] * len(cfgs), counts)
+
+
+def test_shape_limits_of_the_pair_index_division():
+    """The kernels divide pair indices by k with a 64-bit multiplication by ceil(2^40/k): exact for k <= 1024 and
+    pairs < 2^30 as long as the product fits 64 bits, so shapes beyond that are not enumerated."""
+    for k in (1, 2, 3, 7, 8, 64, 1000, 1024):
+        magic = -(-(1 << 40) // k)
+        for p in (0, 1, k - 1, k, k + 1, 12345 * k + k - 1, (1 << 24) * k - 1, min((1 << 30) - 1, (1 << 24) * k)):
+            if p * magic < (1 << 64):
+                assert (p * magic) >> 40 == p // k, (k, p)
+    assert ramp.num_configs(ramp.Shape(1 << 18, 8, 64, 2048, 1024)) > 0        # 2^21 pairs
+    assert ramp.num_configs(ramp.Shape((1 << 24) + 16, 1, 64, 128, 128)) == 0   # k = 1: product would overflow
+    assert ramp.num_configs(ramp.Shape(4, 1025, 64, 2048, 1024)) == 0           # k > 1024
+
+
 def synthetic_profile(rng, n_cfg, n_pts):
     W = rng.choice([256, 512, 1024, 2048], n_cfg).astype(np.int32)
     g = np.empty((n_cfg, n_pts), np.int64)
