@@ -1,16 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the routing-aware fused-MoE path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--model olmoe] [--no-sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--model dsv3] [--no-sweep] [--no-extra]
 
 One "step" is one pass of the whole hot path on a batch that is already resident in HBM:
-expert histogram -> read back E counts -> cost-model select (Eq. 6) -> fused MoE with the
-selected configuration (align, up-projection + SwiGLU, down-projection, top-k combine).
-Before the timed region the script (untimed) profiles the configuration family at 5 batch
-sizes x 5 skew levels and fits the cost model, then times every configuration at every
-(T, beta) point of the model's sweep to report regret against exhaustive search, the speedup
-over static batch-size-only dispatch, and microseconds / TFLOP/s / GB/s / roofline fraction per
-point.  Rank 0 prints ONE JSON line at the end; the tables go to stderr and to the --out folder.
+expert histogram -> cost-model select (Eq. 6) -> fused MoE with the selected configuration
+(align, up-projection + SwiGLU, down-projection, top-k combine).
+Default workload: the largest single-GPU one, the DeepSeek-V3-shaped layer (H=7168, I=2048, E=256,
+top-8) at T=8192 tokens with uniform routing.  Before the timed region the script (untimed) profiles
+the configuration family at 5 batch sizes x 5 skew levels and fits the cost model, then times every
+configuration at every (T, beta) point of the model's sweep to report regret against exhaustive
+search, the speedup over static batch-size-only dispatch, and microseconds / TFLOP/s / GB/s /
+roofline fraction per point.  After the timed region it adds the largest point of the other model
+shapes (best configuration of an exhaustive pass over the large-tile configurations) and the CPU
+oracle on a token sample.  Rank 0 prints ONE JSON line at the end; tables go to stderr and --out.
 """
 from __future__ import annotations
 
@@ -28,12 +31,19 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_TBS = 8.0       # MI355X HBM3E
 MFMA_PEAK_PFLOPS = 2.5   # dense bf16
 
-# HBM bytes per launch of the dominant kernel (up-projection + SwiGLU) from two separate
+# HBM bytes per launch of the dominant kernel (up-projection + SwiGLU) recorded from two separate
 # `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same
-# counter reads for the library's 1 GiB copy kernel: x2.000 and x1.000); the runs and their
-# per-kernel tables are kept as text under profiles/.  Keyed by (model, T, beta); other workloads
-# report null until they have been measured the same way.
-MEASURED_TRAFFIC_BYTES = {("olmoe", 4096, "1.0"): 1017.4e6 + 68.1e6}
+# counter reads for the library's 1 GiB copy kernel).  These are RECORDED values, not measured in the
+# run that prints them: each entry names the text summary under profiles/ that holds the run and its
+# per-kernel table.  Keyed by (model, T, beta); other workloads report null.
+RECORDED_TRAFFIC = {
+    ("olmoe", 4096, "1.0"): (1017.4e6 + 68.1e6, "profiles/olmoe_T4096_hbm_traffic_pmc.md"),
+}
+
+# Largest point of every other model shape, reported next to the headline.
+EXTRA_ROWS = {
+    "dsv3": [("dsv3", 8192, 0.1), ("mixtral", 8192, 1.0), ("qwen3", 8192, 1.0), ("olmoe", 4096, 1.0)],
+}
 
 
 def log(*a):
@@ -45,17 +55,81 @@ def geomean(v):
     return float(np.exp(np.log(v).mean())) if v.size else float("nan")
 
 
+def kernel_name(cfg):
+    fam = "moe_pingpong_kernel<1>" if cfg.mode & 0x400 else "moe_stream_kernel<1>" if cfg.mode & 0x100 else "moe_gemm_kernel<1>"
+    return fam + " (up-projection + SwiGLU)"
+
+
+def stage_times_us(ramp, tuner, layers, cfg, pt, iters=6):
+    """Mean HIP-event time of each stage of ramp_fused_moe (align, up-projection, down-projection, combine)."""
+    out = []
+    for stage in (1, 2, 3, 4):
+        ramp.probe_enable(stage)
+        ramp.probe_read()
+        tuner.time_config(layers, cfg, pt, warmup=1, iters=iters, budget_ms=100.0)
+        ms, n = ramp.probe_read()
+        out.append(ms / max(n, 1) * 1e3)
+    ramp.probe_enable(0)
+    return out
+
+
+def kernel_roofline(s, T, counts, k_us):
+    """Roofline of the dominant kernel (up-projection + SwiGLU): algorithmic flops / bytes of one launch."""
+    P = T * s.k
+    e_act = int((np.asarray(counts) > 0).sum())
+    k_flops = 4.0 * P * s.H * s.I
+    k_bytes = e_act * 2 * s.H * s.I * 2 + T * s.H * 2 + P * s.I * 2
+    t_hbm_k, t_mfma_k = k_bytes / (HBM_PEAK_TBS * 1e12) * 1e6, k_flops / (MFMA_PEAK_PFLOPS * 1e15) * 1e6
+    if t_mfma_k >= t_hbm_k:
+        roof = dict(bound="mfma", achieved=k_flops / k_us * 1e-6, peak=MFMA_PEAK_PFLOPS * 1e3, unit="TFLOP/s")
+    else:
+        roof = dict(bound="hbm", achieved=k_bytes / k_us * 1e-3, peak=HBM_PEAK_TBS * 1e3, unit="GB/s")
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof.update(kernel_us=k_us, algorithmic_flops=k_flops, algorithmic_bytes=k_bytes)
+    return roof
+
+
+def extra_row(torch, ramp, synth, tuner, name, T, beta, iters, dev):
+    """Largest point of another model shape: exhaustive pass over its large-tile configurations (bm >= 128),
+    stage times of the best one."""
+    s = synth.SHAPES[name]
+    layer_bytes = 3 * s.E * s.H * s.I * 2
+    n_layers = int(max(1, min(8, (3 << 30) // layer_bytes)))
+    layers = tuner.LayerSet(s, T, n_layers, seed=1, device=dev, x_std=1.0)
+    fam = tuner.Family.of(s)
+    p = tuner.Point(T, beta, seed=4242).materialise(s)
+    cands = [c for c in fam.cfgs if c.bm >= 128]
+    times = [tuner.time_config(layers, c, p, warmup=3, iters=iters, budget_ms=150.0) for c in cands]
+    b = int(np.argmin(times))
+    st = stage_times_us(ramp, tuner, layers, cands[b], p)
+    t_hbm, t_mfma, nbytes, flops = tuner.roofline_lower_bound_us(s, T, p.counts, HBM_PEAK_TBS, MFMA_PEAK_PFLOPS)
+    roof = kernel_roofline(s, T, p.counts, st[1])
+    row = dict(model=name, T=T, beta=beta, us=times[b], config=cands[b].key(), configs_timed=len(cands),
+               bound="hbm" if t_hbm >= t_mfma else "mfma", roofline_frac=max(t_hbm, t_mfma) / times[b],
+               tflops=flops / times[b] * 1e-6, gbs=nbytes / times[b] * 1e-3,
+               stage_us=dict(align=st[0], up=st[1], down=st[2], combine=st[3]),
+               up_kernel=dict(bound=roof["bound"], achieved=roof["achieved"], unit=roof["unit"], frac=roof["frac"]),
+               weight_copies_rotated=n_layers)
+    log(f"[bench] {name} T={T} beta={beta}: best of {len(cands)} large-tile configurations {times[b]:.1f} us "
+        f"({100 * row['roofline_frac']:.1f}% of the {row['bound']} bound), {cands[b]}; stages align/up/down/combine "
+        + "/".join(f"{v:.1f}" for v in st) + " us")
+    del layers
+    torch.cuda.empty_cache()
+    return row
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--model", default="olmoe", choices=["tiny", "olmoe", "qwen3", "mixtral", "dsv3"])
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--model", default="dsv3", choices=["tiny", "olmoe", "qwen3", "mixtral", "dsv3"])
     ap.add_argument("--T", type=int, default=None, help="headline batch size (default: largest of the sweep)")
     ap.add_argument("--beta", default=None, help="headline skew (default 1.0)")
     ap.add_argument("--layers", type=int, default=None, help="distinct weight copies to rotate over")
     ap.add_argument("--no-sweep", action="store_true", help="skip the regret / static-dispatch sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-extra", action="store_true", help="skip the largest points of the other model shapes")
     ap.add_argument("--heldout", type=int, default=0, help="extra seeded held-out histograms for regret (dsv3: 200)")
     ap.add_argument("--iters", type=int, default=50)
     ap.add_argument("--config", default=None,
@@ -77,6 +151,7 @@ def main():
     ramp.lib()  # fail loudly if the HIP library is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    t_begin = time.time()
     s = synth.SHAPES[args.model]
     sweep = synth.SWEEPS[args.model]
     T_head = args.T if args.T is not None else max(sweep["T"])
@@ -100,6 +175,7 @@ def main():
         assert match, f"configuration {want} is not in the family for this shape"
         fixed_cfg = match[0]
         args.no_sweep = True
+        args.no_extra = True
 
     # ------------------------------------------------------------------ one-time profiling + fit (Sec. 4.2)
     fit_T = tuner.fit_batch_sizes(sweep["T"])
@@ -109,26 +185,33 @@ def main():
         fit_pts = fit_pts[:2]
     log(f"[bench] profiling {len(fit_pts)} fit points x {n_cfg} configs (T in {fit_T}, beta in {tuner.FIT_BETAS})")
     if fixed_cfg is None:
-        g_fit, t_fit = tuner.profile(layers, fam, fit_pts, iters=min(args.iters, 30), warmup=5, budget_ms=150.0)
+        g_fit, t_fit = tuner.profile(layers, fam, fit_pts, iters=min(args.iters, 20), warmup=3, budget_ms=60.0)
     else:
         for pt in fit_pts:
             pt.materialise(s)
         g_fit = np.stack([fam.grid(pt.counts) for pt in fit_pts], axis=1)
         t_fit = np.ones_like(g_fit, dtype=np.float64)
     counts_fit = [p.materialise(s).counts for p in fit_pts]
-    MODELS = {"eq6": ramp.CM_EQ6, "eq6_mi355x": tuner.MI355X_MODEL}   # as printed / cache-aware + relative fit
+    # Eq. 6 as printed, every single departure from it, the fit-only change plus the traffic column, and the model
+    # that is dispatched (all four departures)
+    MODELS = {"eq6": ramp.CM_EQ6, "relative_fit": ramp.CM_RELATIVE, "distinct_tiles": ramp.CM_DISTINCT_TILES,
+              "wave_floor": ramp.CM_WAVE_FLOOR, "pairs": ramp.CM_PAIRS,
+              "relative_fit+distinct_tiles": ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES,
+              "eq6_mi355x": tuner.MI355X_MODEL}
     thetas = {name: tuner.fit(fam, g_fit, t_fit, counts_fit, flags) for name, flags in MODELS.items()}
     DISPATCH = "eq6_mi355x"
     theta, dispatch_flags = thetas[DISPATCH], MODELS[DISPATCH]
     # term ablation of the dispatch model (Sec. 5.3): the same fit with the later columns zeroed, so their
     # coefficients come out zero (minimum-norm solution): 2 terms = a + b*w, 3 terms = + c*m, 4 terms = + d*P
     u_fit = tuner.distinct_tiles(fam, counts_fit)
-    P_fit = np.array([int(np.asarray(c).sum()) for c in counts_fit], np.int64)
+    P_fit = np.array([ramp.grid(s.E, fam.cfgs, fam.ntiles, c)[2] for c in counts_fit], np.int64)
     ABLATION = {2: ramp.cost_model_fit(fam.wave_cap, g_fit, t_fit, distinct=np.zeros_like(u_fit), pairs=np.zeros_like(P_fit),
                                        flags=dispatch_flags),
                 3: ramp.cost_model_fit(fam.wave_cap, g_fit, t_fit, distinct=u_fit, pairs=np.zeros_like(P_fit),
                                        flags=dispatch_flags),
                 4: theta}
+    # Sec. 5.3's fifth term (g^2) on top of Eq. 6 as printed and on top of the dispatch model
+    theta5 = {name: tuner.fit5(fam, g_fit, t_fit, counts_fit, MODELS[name]) for name in ("eq6", DISPATCH)}
     if args.save_model and fixed_cfg is None:
         tuner.save_model(args.save_model, fam, theta, dispatch_flags,
                          extra=dict(model=args.model, fit_T=fit_T, fit_betas=[str(b) for b in tuner.FIT_BETAS]))
@@ -138,13 +221,13 @@ def main():
                                       flags=MODELS[name])[1]
 
     r2 = {}
-    for name in MODELS:
+    for name in ("eq6", DISPATCH):
         pred_fit = np.stack([predictions(name, c) for c in counts_fit], axis=1)
         ss_res = ((pred_fit - t_fit) ** 2).sum(axis=1)
         ss_tot = ((t_fit - t_fit.mean(axis=1, keepdims=True)) ** 2).sum(axis=1)
         r2[name] = 1.0 - ss_res / np.maximum(ss_tot, 1e-30)
     log(f"[bench] fit done in {time.time() - t0:.1f}s; R^2 (eq6) min {r2['eq6'].min():.3f} median {np.median(r2['eq6']):.3f}; "
-        f"log term active in {(theta[:, 3] != 0).sum()}/{n_cfg} configs")
+        f"log term active in {(thetas['eq6'][:, 3] != 0).sum()}/{n_cfg} configs")
 
     # ------------------------------------------------------------------ sweep: exhaustive vs cost model vs static
     report = {"model": args.model, "configs": [c.key() for c in fam.cfgs],
@@ -158,13 +241,14 @@ def main():
         pts = [tuner.Point(T, b, seed=500 + 31 * i + j) for i, T in enumerate(sweep["T"]) for j, b in enumerate(sweep["beta"])]
         t0 = time.time()
         log(f"[bench] sweep: {len(pts)} held-out points x {n_cfg} configs")
-        g_ev, t_ev = tuner.profile(layers, fam, pts, log=log, iters=args.iters, warmup=10, budget_ms=300.0)
+        g_ev, t_ev = tuner.profile(layers, fam, pts, log=log, iters=args.iters, warmup=5, budget_ms=100.0)
         static_of_T = {}
         for j, p in enumerate(pts):
             if p.beta == 1.0 or p.beta == sweep["beta"][0]:
                 static_of_T.setdefault(p.T, int(np.argmin(t_ev[:, j])))
         regrets = {name: [] for name in MODELS}
         abl_regrets = {k: [] for k in ABLATION}
+        regrets5 = {name: [] for name in theta5}
         speedups = {}
         hdr = (f"{'T':>5} {'beta':>8} {'bH':>5} {'best us':>9} {'RA us':>9} {'static us':>9} {'regret%':>8} {'eq6 reg%':>8} "
                f"{'RA/static':>9} {'bound':>5} {'roof%':>6} {'TFLOP/s':>8} {'GB/s':>7}  best / RA / static bm")
@@ -177,9 +261,11 @@ def main():
                 regrets[name].append(t_ev[picks[name], j] / t_ev[best, j] - 1.0)
             for k_terms, th_k in ABLATION.items():
                 abl_regrets[k_terms].append(t_ev[tuner.select(fam, th_k, p.counts, dispatch_flags), j] / t_ev[best, j] - 1.0)
+            for name, th5 in theta5.items():
+                regrets5[name].append(t_ev[tuner.select5(fam, th5, p.counts, MODELS[name]), j] / t_ev[best, j] - 1.0)
             chosen = picks[DISPATCH]
             reg = regrets[DISPATCH][-1]
-            hot_us = tuner.time_config(layers, fam.cfgs[chosen], p, warmup=3, iters=min(args.iters, 20), budget_ms=100.0, hot=True)
+            hot_us = tuner.time_config(layers, fam.cfgs[chosen], p, warmup=3, iters=min(args.iters, 20), budget_ms=60.0, hot=True)
             spd = t_ev[st, j] / t_ev[chosen, j]
             speedups.setdefault(str(p.beta), []).append(spd)
             t_hbm, t_mfma, nbytes, flops = tuner.roofline_lower_bound_us(s, p.T, p.counts, HBM_PEAK_TBS, MFMA_PEAK_PFLOPS)
@@ -196,36 +282,49 @@ def main():
                 f"{row['static_us']:9.1f} {100 * reg:8.2f} {100 * row['regret_eq6']:8.2f} {spd:9.3f} {bound:>5} {100 * frac:6.1f} "
                 f"{row['tflops']:8.1f} {row['gbs']:7.0f}  {fam.cfgs[best].bm}/{fam.cfgs[chosen].bm}/{fam.cfgs[st].bm}")
         skew = [r for r in report["points"] if str(r["beta"]) != str(sweep["beta"][0])]
+        uniform = [r for r in report["points"] if str(r["beta"]) == str(sweep["beta"][0])]
         summary = dict(dispatch_model=DISPATCH,
                        mean_regret=float(np.mean(regrets[DISPATCH])), max_regret=float(np.max(regrets[DISPATCH])),
                        median_regret=float(np.median(regrets[DISPATCH])),
                        mean_regret_eq6_as_printed=float(np.mean(regrets["eq6"])),
                        max_regret_eq6_as_printed=float(np.max(regrets["eq6"])),
+                       model_variants={name: dict(flags=int(MODELS[name]), mean_regret=float(np.mean(v)), max_regret=float(np.max(v)))
+                                       for name, v in regrets.items()},
                        term_ablation_mean_regret={str(k): float(np.mean(v)) for k, v in abl_regrets.items()},
+                       five_term_mean_regret={name: float(np.mean(v)) for name, v in regrets5.items()},
                        ra_over_static_geomean={b: geomean(v) for b, v in speedups.items()},
                        ra_over_static_geomean_skewed=geomean([r["ra_over_static"] for r in skew]),
+                       ra_over_static_min_uniform=float(min(r["ra_over_static"] for r in uniform)),
                        best_over_static_geomean_skewed=geomean([r["static_us"] / r["best_us"] for r in skew]),
                        paper_context=dict(mean_regret=0.0093, ra_over_static=1.22, hardware="H200 FP8"))
         log(f"[bench] sweep {time.time() - t0:.1f}s: mean regret {100 * summary['mean_regret']:.2f}% "
-            f"(median {100 * summary['median_regret']:.2f}%, max {100 * summary['max_regret']:.2f}%; Eq. 6 as printed: "
-            f"{100 * summary['mean_regret_eq6_as_printed']:.2f}%); RA/static geomean on skewed points "
-            f"{summary['ra_over_static_geomean_skewed']:.3f}x (exhaustive ceiling {summary['best_over_static_geomean_skewed']:.3f}x); "
-            f"term ablation 2/3/4: " + " / ".join(f"{100 * summary['term_ablation_mean_regret'][str(k)]:.2f}%" for k in (2, 3, 4)))
+            f"(median {100 * summary['median_regret']:.2f}%, max {100 * summary['max_regret']:.2f}%); RA/static geomean on skewed points "
+            f"{summary['ra_over_static_geomean_skewed']:.3f}x (exhaustive ceiling {summary['best_over_static_geomean_skewed']:.3f}x), "
+            f"worst uniform point {summary['ra_over_static_min_uniform']:.3f}x")
+        log("[bench] mean / max regret by model variant: " + "; ".join(
+            f"{name} {100 * v['mean_regret']:.2f}/{100 * v['max_regret']:.1f}%" for name, v in summary["model_variants"].items()))
+        log("[bench] term ablation of the dispatch model 2/3/4 terms: "
+            + " / ".join(f"{100 * summary['term_ablation_mean_regret'][str(k)]:.2f}%" for k in (2, 3, 4))
+            + "; with a fifth term g^2: " + ", ".join(f"{n} {100 * v:.2f}%" for n, v in summary["five_term_mean_regret"].items()))
 
     if args.heldout > 0:
         rng = np.random.default_rng(7)
-        regs = []
+        regs, regs_eq6 = [], []
         t0 = time.time()
         for h in range(args.heldout):
             T = int(rng.choice(sweep["T"][1:]))
             b = sweep["beta"][int(rng.integers(len(sweep["beta"])))]
             p = tuner.Point(T, b, seed=900000 + h).materialise(s)
-            times = np.array([tuner.time_config(layers, c, p, warmup=2, iters=8, budget_ms=40.0) for c in fam.cfgs])
+            times = np.array([tuner.time_config(layers, c, p, warmup=2, iters=8, budget_ms=30.0) for c in fam.cfgs])
             regs.append(times[tuner.select(fam, theta, p.counts, dispatch_flags)] / times.min() - 1.0)
+            regs_eq6.append(times[tuner.select(fam, thetas["eq6"], p.counts, MODELS["eq6"])] / times.min() - 1.0)
             if h % 20 == 19:
                 log(f"[bench] held-out {h + 1}/{args.heldout}: mean regret so far {100 * np.mean(regs):.2f}%")
-        summary["heldout_histograms"] = dict(n=args.heldout, mean_regret=float(np.mean(regs)), max_regret=float(np.max(regs)))
-        log(f"[bench] held-out histograms {time.time() - t0:.1f}s: mean {100 * np.mean(regs):.2f}% max {100 * np.max(regs):.2f}%")
+        summary["heldout_histograms"] = dict(n=args.heldout, mean_regret=float(np.mean(regs)), max_regret=float(np.max(regs)),
+                                             median_regret=float(np.median(regs)),
+                                             mean_regret_eq6_as_printed=float(np.mean(regs_eq6)))
+        log(f"[bench] held-out histograms {time.time() - t0:.1f}s: mean {100 * np.mean(regs):.2f}% max {100 * np.max(regs):.2f}% "
+            f"(Eq. 6 as printed: mean {100 * np.mean(regs_eq6):.2f}%)")
 
     # ------------------------------------------------------------------ headline: K timed steps of the whole path
     p = tuner.Point(T_head, beta_head, seed=4242).materialise(s)
@@ -236,12 +335,9 @@ def main():
     ws = layers.workspace(max(ramp.fused_moe_workspace_bytes(rs, c) for c in fam.cfgs))
     X, out = layers.X[:T_head], layers.out[:T_head]
     chosen_log = []
-    t_select = [0.0]
 
     def step(i):
-        t0s = time.perf_counter()
         c = dispatcher.select(d_ids)            # histogram + Eq. 6 + argmin on the device, result polled in pinned memory
-        t_select[0] += time.perf_counter() - t0s
         if fixed_cfg is not None:
             c = fixed_cfg
         ramp.fused_moe(rs, fam.cfgs[c], X, d_ids, d_w, layers.packed[i % layers.n_layers], out, ws)
@@ -262,7 +358,6 @@ def main():
     torch.cuda.synchronize()
     ramp.probe_enable(2)  # the up-projection kernel dominates (2/3 of the flops and of the weight bytes)
     ramp.probe_read()
-    t_select[0] = 0.0
     t_start = time.perf_counter()
     for i in range(args.steps):
         chosen_log.append(step(i))
@@ -272,8 +367,9 @@ def main():
     ramp.probe_enable(0)
     ms_per_step = elapsed / args.steps * 1e3
     cfg_head = fam.cfgs[chosen_log[-1]]
-    # the layer alone with the dispatched configuration (no histogram / select), HIP events per call
+    # the layer alone with the dispatched configuration (no histogram / select), HIP events per call, and its stages
     fused_us = tuner.time_config(layers, cfg_head, p, warmup=5, iters=args.iters)
+    stage_us = stage_times_us(ramp, tuner, layers, cfg_head, p)
     # dispatch latency on an idle GPU, device-resident select (one enqueue, ticket polled in pinned host memory)
     # next to the host-side select (histogram kernel, E-count copy, stream synchronisation, model on the host)
     torch.cuda.synchronize()
@@ -351,28 +447,23 @@ def main():
             log(f"[bench] note: the graph path selected {cands[int(sel_dev.cpu()[0])]} among {len(cands)} candidates")
 
     # roofline of the dominant kernel (up-projection + SwiGLU): algorithmic flops / bytes per launch
-    P = T_head * s.k
-    e_act = int((p.counts > 0).sum())
-    k_flops = 4.0 * P * s.H * s.I
-    k_bytes = e_act * 2 * s.H * s.I * 2 + T_head * s.H * 2 + P * s.I * 2
     k_us = probe_ms / max(probe_n, 1) * 1e3
-    t_hbm_k, t_mfma_k = k_bytes / (HBM_PEAK_TBS * 1e12) * 1e6, k_flops / (MFMA_PEAK_PFLOPS * 1e15) * 1e6
-    if t_mfma_k >= t_hbm_k:
-        roof = dict(bound="mfma", achieved=k_flops / k_us * 1e-6, peak=MFMA_PEAK_PFLOPS * 1e3, unit="TFLOP/s")
-    else:
-        roof = dict(bound="hbm", achieved=k_bytes / k_us * 1e-3, peak=HBM_PEAK_TBS * 1e3, unit="GB/s")
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof.update(traffic=MEASURED_TRAFFIC_BYTES.get((args.model, T_head, str(beta_head))), kernel=("moe_pingpong_kernel<1>" if cfg_head.mode & 0x400 else "moe_stream_kernel<1>" if cfg_head.mode & 0x100 else "moe_gemm_kernel<1>") + " (up-projection + SwiGLU)", kernel_us=k_us, launches=probe_n,
-                algorithmic_flops=k_flops, algorithmic_bytes=k_bytes)
+    roof = kernel_roofline(s, T_head, p.counts, k_us)
+    rec = RECORDED_TRAFFIC.get((args.model, T_head, str(beta_head)))
+    roof.update(traffic=rec[0] if rec else None, traffic_source=(rec[1] + " (recorded rocprofv3 --pmc value, not measured in this run)") if rec else None,
+                kernel=kernel_name(cfg_head), launches=probe_n)
     t_hbm, t_mfma, nbytes, flops = tuner.roofline_lower_bound_us(s, T_head, p.counts, HBM_PEAK_TBS, MFMA_PEAK_PFLOPS)
     whole = dict(bound="hbm" if t_hbm >= t_mfma else "mfma", lower_bound_us=max(t_hbm, t_mfma),
                  frac=max(t_hbm, t_mfma) / (ms_per_step * 1e3), tflops=flops / (ms_per_step * 1e3) * 1e-6,
                  gbs=nbytes / (ms_per_step * 1e3) * 1e-3, fused_layer_us=fused_us,
-                 fused_layer_frac=max(t_hbm, t_mfma) / fused_us, dispatch_idle_us=dispatch_idle_us,
+                 fused_layer_frac=max(t_hbm, t_mfma) / fused_us,
+                 stage_us=dict(align=stage_us[0], up=stage_us[1], down=stage_us[2], combine=stage_us[3]),
+                 dispatch_idle_us=dispatch_idle_us,
                  dispatch_host_select_idle_us=dispatch_host_idle_us, async_dispatch_us_per_step=async_us,
                  graph_dispatch_us_per_step=graph_us, graph_candidates=graph_cands,
                  paper_dispatch_us_h200=38.0)
-    log(f"[bench] headline T={T_head} beta={beta_head}: {ms_per_step * 1e3:.1f} us/step (fused layer alone {fused_us:.1f} us, "
+    log(f"[bench] headline {args.model} T={T_head} beta={beta_head}: {ms_per_step * 1e3:.1f} us/step (fused layer alone {fused_us:.1f} us: "
+        + "/".join(f"{v:.1f}" for v in stage_us) + " us align/up/down/combine; "
         f"dispatch on an idle GPU {dispatch_idle_us:.1f} us device-resident / {dispatch_host_idle_us:.1f} us host select, "
         f"{async_us if async_us is None else round(async_us, 1)} us/step with asynchronous dispatch, "
         f"{graph_us if graph_us is None else round(graph_us, 1)} us/step as one HIP graph with device-side selection), config {cfg_head}, "
@@ -383,7 +474,7 @@ def main():
     if not args.no_cpu:
         from oracle import oracle
         Wg, Wu, Wd = layers.raw0
-        n0 = min(T_head, 8)
+        n0 = min(T_head, 4)
         rows = np.linspace(0, T_head - 1, n0).astype(np.int32)
         used = sorted({int(e) for t in rows for e in p.ids[t]})
         # host copies of the experts the sample touches
@@ -392,7 +483,8 @@ def main():
         tc = time.perf_counter()
         oracle.moe(Xb, p.ids, p.w, hW[0], hW[1], hW[2], E=s.E, rows=rows)
         per_tok = (time.perf_counter() - tc) / n0
-        n1 = int(min(T_head, max(n0, 15.0 / max(per_tok, 1e-6))))
+        # about 15 s of CPU work, at most 256 sampled tokens (each sampled token needs host copies of its experts)
+        n1 = int(min(T_head, 256, max(n0, 15.0 / max(per_tok, 1e-6))))
         if n1 > n0:
             rows = np.linspace(0, T_head - 1, n1).astype(np.int32)
             used = sorted({int(e) for t in rows for e in p.ids[t]})
@@ -400,6 +492,7 @@ def main():
             tc = time.perf_counter()
             oracle.moe(Xb, p.ids, p.w, hW[0], hW[1], hW[2], E=s.E, rows=rows)
             per_tok = (time.perf_counter() - tc) / n1
+        del hW
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         # the oracle's align and select on the same input, beside the layer
         ids_flat = np.ascontiguousarray(p.ids.reshape(-1), np.int32)
@@ -414,11 +507,25 @@ def main():
         cpu_select_us = (time.perf_counter() - tc) / 5 * 1e6
         cpu = dict(value=per_tok * T_head * 1e6, unit="us/layer", cores=threads, kind="oracle",
                    oracle_align_us=cpu_align_us, oracle_select_us=cpu_select_us,
-                   sample=f"{max(n0, n1)} of {T_head} tokens (evenly spaced rows), per-token time scaled to the full batch")
-        log(f"[bench] CPU oracle: {per_tok * 1e3:.2f} ms/token on {threads} threads -> {cpu['value'] / 1e6:.2f} s/layer")
+                   sample=f"{max(n0, n1)} of {T_head} tokens (evenly spaced rows), per-token time scaled to the full batch "
+                          f"(extrapolated)")
+        log(f"[bench] CPU oracle: {per_tok * 1e3:.2f} ms/token on {threads} threads -> {cpu['value'] / 1e6:.2f} s/layer (extrapolated)")
+
+    # ------------------------------------------------------------------ largest points of the other model shapes
+    extra = []
+    if not args.no_extra:
+        del dispatcher, ws
+        layers = None
+        torch.cuda.empty_cache()
+        for name, T, beta in EXTRA_ROWS.get(args.model, []):
+            if time.time() - t_begin > 420:
+                log(f"[bench] time budget reached, skipping {name} T={T}")
+                continue
+            extra.append(extra_row(torch, ramp, synth, tuner, name, T, beta, min(args.iters, 12), dev))
 
     report["summary"] = summary
     report["headline"] = dict(T=T_head, beta=beta_head, us=ms_per_step * 1e3, config=cfg_head.key(), whole_path=whole)
+    report["largest_points"] = extra
     tag = "_fixed_config" if fixed_cfg is not None else ""
     with open(os.path.join(args.out, f"bench_{args.model}{tag}.json"), "w") as f:
         json.dump(report, f)
@@ -431,9 +538,11 @@ def main():
         "config": {"workload": f"{args.model}-shaped MoE layer H={s.H} I={s.I} E={s.E} top-{s.k}, T={T_head}, beta={beta_head}",
                    "tile_config": cfg_head.key(), "weight_copies_rotated": n_layers},
         "roofline": roof, "whole_path": whole, "cpu_baseline": cpu, "cost_model": summary,
+        "largest_points": extra,
         "sweep": [dict(T=r["T"], beta=r["beta"], us=round(r["ra_us"], 1), hot_us=round(r["ra_hot_us"], 1), best_us=round(r["best_us"], 1),
                        static_us=round(r["static_us"], 1), bound=r["bound"], roofline_frac=round(r["roofline_frac"], 3),
                        regret=round(r["regret"], 4), bm=r["ra_cfg"][0]) for r in report["points"]],
+        "total_s": round(time.time() - t_begin, 1),
     }
     print(json.dumps(line), flush=True)
 

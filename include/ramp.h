@@ -85,6 +85,12 @@ int ramp_config_ntiles(const ramp_shape *shape, const ramp_config *cfg);
  * configuration that fit on one unit (from its LDS and register footprint). */
 int ramp_config_wave_capacity(const ramp_config *cfg);
 
+/* What the HIP runtime says about the same quantity on the current device: workgroups of the configuration's
+ * up-projection kernel (wg_per_cu[0]) and down-projection kernel (wg_per_cu[1]) that can be resident on one
+ * compute unit (hipOccupancyMaxActiveBlocksPerMultiprocessor).  Needs a GPU; ramp_config_wave_capacity is the
+ * static table the cost model uses and is tested against this. */
+int ramp_config_runtime_occupancy(const ramp_config *cfg, int *wg_per_cu /*host out [2]*/);
+
 /* ---- align (Eq. 1 first factor; Fig. 1) --------------------------------------------------
  * Pair p = t*k + j is routed to expert topk_ids[p].  Expert e owns
  * ceil(n_e/bm) consecutive tiles of bm slots; its pairs fill them in increasing p,
@@ -192,6 +198,17 @@ int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts, const int
 int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
                            const int32_t *wave_cap, const float *theta,
                            const int32_t *expert_counts, int flags, int *best_idx, double *pred_us);
+
+/* The five-term ablation of Sec. 5.3 ("a 5th term g^2"): the model above plus e*(g/W)^2, i.e. g^2 up to the
+ * configuration's constant W^2.  theta5: host [n_cfg,5] = a,b,c,d,e; otherwise as ramp_cost_model_fit /
+ * ramp_cost_model_select (same flags, same adaptive fourth column).  For the ablation report only: the
+ * device-resident dispatch evaluates the four-term model. */
+int ramp_cost_model_fit5(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
+                         const int64_t *distinct, const int64_t *pairs, const double *time_us, int flags,
+                         float *theta5);
+int ramp_cost_model_select5(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
+                            const int32_t *wave_cap, const float *theta5,
+                            const int32_t *expert_counts, int flags, int *best_idx, double *pred_us);
 
 /* Eq. 1 for every configuration on one histogram (host [E]): grid[c] = (sum_e ceil(n_e/bm_c)) * ntiles[c], the
  * g of Eq. 6.  Optional outputs (may be NULL): distinct[c] = #{e: n_e > 0} * ntiles[c] (the column of

@@ -260,8 +260,10 @@ def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4, distinct=None, rela
     g: profiling grids, t_us: measured times.  The log column is used only if
     the (lower) median profiling grid is below wave_cap.  Solves the literal
     four-column system in the minimum-norm least-squares sense.
-    n_terms = 2 / 3 reproduce the ablation rows (a + k*g; a + b*g/W + c*g).
-    Returns (theta[4] as float64, use_log).
+    n_terms = 2 / 3 reproduce the ablation rows (a + k*g; a + b*g/W + c*g); n_terms = 5 adds the fifth
+    term of Sec. 5.3 (g^2, here (g/W)^2: the same column up to the configuration's constant W^2) and
+    returns theta[5].
+    Returns (theta as float64, use_log).
     """
     g = np.asarray(g, dtype=np.float64)
     t = np.asarray(t_us, dtype=np.float64)
@@ -270,13 +272,23 @@ def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4, distinct=None, rela
     cols = [0, 1, 2] + ([3] if use_log else [])
     if n_terms == 2:
         cols = [0, 2]
+    if n_terms == 5:
+        X = np.concatenate([X, ((g / float(wave_cap)) ** 2)[:, None]], axis=1)
+        cols = cols + [4]
     A, rhs = X[:, cols], t
     if relative:
         A, rhs = A / t[:, None], np.ones_like(t)
     sol = np.linalg.lstsq(A, rhs, rcond=None)[0]
-    theta = np.zeros(4, np.float64)
+    theta = np.zeros(5 if n_terms == 5 else 4, np.float64)
     theta[cols] = sol
     return theta, use_log
+
+
+def predict5(theta5, g: int, wave_cap: int, distinct=None, wave_floor: bool = False, pairs=None) -> float:
+    """Five-term model of Sec. 5.3 on one grid: the row of design_matrix plus (g/W)^2, times theta5."""
+    x = design_matrix([g], wave_cap, None if distinct is None else [distinct], wave_floor, None if pairs is None else [pairs])[0]
+    th = np.asarray(theta5, np.float64)
+    return float(x @ th[:4] + th[4] * (float(g) / float(wave_cap)) ** 2)
 
 
 def regret(t_meas_row, chosen: int) -> float:

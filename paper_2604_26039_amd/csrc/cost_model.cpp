@@ -26,10 +26,12 @@ void set_error(const char *fmt, ...);
 
 namespace {
 
-// Minimum-norm least squares  min |A x - t|  for an n x m matrix (column major, m <= 4).
+constexpr int kMaxTerms = 5;
+
+// Minimum-norm least squares  min |A x - t|  for an n x m matrix (column major, m <= kMaxTerms).
 void lstsq_min_norm(std::vector<double> A, int n, int m, const double *t, double *x)
 {
-    double V[4][4] = {};
+    double V[kMaxTerms][kMaxTerms] = {};
     for (int j = 0; j < m; ++j) V[j][j] = 1.0;
     auto col = [&](int j) { return A.data() + (size_t)j * n; };
     for (int sweep = 0; sweep < 60; ++sweep) {
@@ -63,7 +65,7 @@ void lstsq_min_norm(std::vector<double> A, int n, int m, const double *t, double
             }
         if (off < 1e-15) break;
     }
-    double sigma[4], smax = 0.0;
+    double sigma[kMaxTerms], smax = 0.0;
     for (int j = 0; j < m; ++j) {
         double s = 0;
         for (int i = 0; i < n; ++i) s += col(j)[i] * col(j)[i];
@@ -85,9 +87,10 @@ void lstsq_min_norm(std::vector<double> A, int n, int m, const double *t, double
 
 static const int kAllFlags = RAMP_CM_RELATIVE | RAMP_CM_DISTINCT_TILES | RAMP_CM_WAVE_FLOOR | RAMP_CM_PAIRS;
 
-extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
-                                   const int64_t *distinct, const int64_t *pairs, const double *time_us, int flags,
-                                   float *theta)
+// n_theta = 4: Eq. 6; n_theta = 5: the ablation of Sec. 5.3 with a fifth column (g/W)^2, i.e. g^2 up to the
+// configuration's constant W^2 (kept of order one for the conditioning of the system).
+static int fit_impl(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid, const int64_t *distinct,
+                    const int64_t *pairs, const double *time_us, int flags, float *theta, int n_theta)
 {
     const bool use_distinct = (flags & RAMP_CM_DISTINCT_TILES) != 0;
     const bool relative = (flags & RAMP_CM_RELATIVE) != 0;
@@ -98,7 +101,7 @@ extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts
         ramp::set_error("cost_model_fit: bad argument");
         return RAMP_EINVAL;
     }
-    std::vector<double> A((size_t)4 * n_pts), sorted_g(n_pts), rhs(n_pts);
+    std::vector<double> A((size_t)kMaxTerms * n_pts), sorted_g(n_pts), rhs(n_pts);
     for (int c = 0; c < n_cfg; ++c) {
         const int64_t *g = grid + (size_t)c * n_pts;
         const double *t = time_us + (size_t)c * n_pts;
@@ -111,7 +114,8 @@ extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts
         std::sort(sorted_g.begin(), sorted_g.end());
         // fourth column: the log term only when the lower median grid is in the sub-wave region; the pair count always
         const bool use_fourth = use_pairs || sorted_g[(n_pts - 1) / 2] < W;
-        const int m = use_fourth ? 4 : 3;
+        const int m = (use_fourth ? 4 : 3) + (n_theta == 5 ? 1 : 0);
+        const int quad_col = use_fourth ? 4 : 3;  // where the quadratic column sits in the system that is solved
         for (int i = 0; i < n_pts; ++i) {
             const double gi = (double)g[i];
             const double mi = use_distinct ? (double)distinct[(size_t)c * n_pts + i] : gi;
@@ -128,18 +132,36 @@ extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts
             A[1 * (size_t)n_pts + i] = ((wave_floor && wi < 1.0) ? 1.0 : wi) * scale;
             A[2 * (size_t)n_pts + i] = mi * scale;
             A[3 * (size_t)n_pts + i] = (use_pairs ? (double)pairs[i] : std::log(gi + 1.0)) * scale;
+            if (n_theta == 5) A[(size_t)quad_col * n_pts + i] = (gi / W) * (gi / W) * scale;
             rhs[i] = t[i] * scale;
         }
-        double x[4] = {0, 0, 0, 0};
+        double x[kMaxTerms] = {0, 0, 0, 0, 0};
         lstsq_min_norm(std::vector<double>(A.begin(), A.begin() + (size_t)m * n_pts), n_pts, m, rhs.data(), x);
-        for (int j = 0; j < 4; ++j) theta[(size_t)c * 4 + j] = (j < m) ? (float)x[j] : 0.0f;
+        float *th = theta + (size_t)c * n_theta;
+        for (int j = 0; j < 3; ++j) th[j] = (float)x[j];
+        th[3] = use_fourth ? (float)x[3] : 0.0f;
+        if (n_theta == 5) th[4] = (float)x[quad_col];
     }
     return RAMP_OK;
 }
 
-extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
-                                      const int32_t *wave_cap, const float *theta, const int32_t *expert_counts,
-                                      int flags, int *best_idx, double *pred_us)
+extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
+                                   const int64_t *distinct, const int64_t *pairs, const double *time_us, int flags,
+                                   float *theta)
+{
+    return fit_impl(n_cfg, wave_cap, n_pts, grid, distinct, pairs, time_us, flags, theta, 4);
+}
+
+extern "C" int ramp_cost_model_fit5(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
+                                    const int64_t *distinct, const int64_t *pairs, const double *time_us, int flags,
+                                    float *theta5)
+{
+    return fit_impl(n_cfg, wave_cap, n_pts, grid, distinct, pairs, time_us, flags, theta5, 5);
+}
+
+static int select_impl(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles, const int32_t *wave_cap,
+                       const float *theta, const int32_t *expert_counts, int flags, int *best_idx, double *pred_us,
+                       int n_theta)
 {
     if (E <= 0 || n_cfg <= 0 || !cfgs || !ntiles || !wave_cap || !theta || !expert_counts || !best_idx ||
         (flags & ~kAllFlags)) {
@@ -175,13 +197,14 @@ extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs,
             last_mt = mt;
         }
         const double g = (double)(last_mt * (int64_t)ntiles[c]);
-        const float *th = theta + (size_t)c * 4;
+        const float *th = theta + (size_t)c * n_theta;
         double t = (double)th[0];
         const double w = g / (double)wave_cap[c];
         t = t + (double)th[1] * ((wave_floor && w < 1.0) ? 1.0 : w);
         const double m = use_distinct ? (double)(active * (int64_t)ntiles[c]) : g;
         t = t + (double)th[2] * m;
         t = t + (double)th[3] * (use_pairs ? (double)pairs : std::log(g + 1.0));
+        if (n_theta == 5) t = t + (double)th[4] * (w * w);  // w = g/W, not floored
         if (pred_us) pred_us[c] = t;
         if (best < 0 || t < best_t) {
             best = c;
@@ -190,6 +213,20 @@ extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs,
     }
     *best_idx = best;
     return RAMP_OK;
+}
+
+extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
+                                      const int32_t *wave_cap, const float *theta, const int32_t *expert_counts,
+                                      int flags, int *best_idx, double *pred_us)
+{
+    return select_impl(E, n_cfg, cfgs, ntiles, wave_cap, theta, expert_counts, flags, best_idx, pred_us, 4);
+}
+
+extern "C" int ramp_cost_model_select5(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
+                                       const int32_t *wave_cap, const float *theta5, const int32_t *expert_counts,
+                                       int flags, int *best_idx, double *pred_us)
+{
+    return select_impl(E, n_cfg, cfgs, ntiles, wave_cap, theta5, expert_counts, flags, best_idx, pred_us, 5);
 }
 
 // Eq. 1 for every configuration on one histogram, with the other two histogram sums the model's columns use.

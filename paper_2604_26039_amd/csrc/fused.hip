@@ -223,16 +223,17 @@ bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s)
 }
 int occupancy_estimate(const KernelInfo &ki)
 {
-    // Workgroups of this configuration resident on one compute unit: bounded by LDS, by the
-    // 512-register file per lane (accumulators plus ~96 working registers) and by 8 wavefronts
-    // per SIMD.
-    int by_lds = kLdsBytesPerCU / ki.lds_bytes;
-    int regs = ki.acc_regs + 96;
-    int waves_per_simd = 512 / regs;
-    if (waves_per_simd > 8) waves_per_simd = 8;
+    // Workgroups of this configuration resident on one compute unit, from what the compiler reported for its
+    // up-projection kernel when the library was built: wavefronts per SIMD allowed by the register allocation
+    // (4 SIMDs per unit, at most 8 wavefronts each), and 160 KB of LDS.  The persistent kernels launch one
+    // workgroup per unit whatever would fit.
+    if (ki.cfg.mode & kModePingPong) return 1;
+    const KernelResources *r = find_resources(ki.family, ki.targs, ki.n_targs);
+    if (!r) return 0;  // no record for this kernel: the library was not built by its build script
+    int waves_per_simd = r->waves_per_simd < 8 ? r->waves_per_simd : 8;
     if (waves_per_simd < 1) waves_per_simd = 1;
     int by_regs = waves_per_simd * 4 / ki.cfg.waves;
-    if (by_regs < 1) by_regs = 1;
+    const int by_lds = r->lds_bytes > 0 ? kLdsBytesPerCU / r->lds_bytes : 64;
     int occ = by_lds < by_regs ? by_lds : by_regs;
     return occ < 1 ? 1 : occ;
 }
@@ -304,7 +305,35 @@ extern "C" int ramp_config_wave_capacity(const ramp_config *cfg)
         set_error("config_wave_capacity: configuration not instantiated");
         return RAMP_EUNSUPPORTED;
     }
-    return kNumCU * occupancy_estimate(*ki);
+    const int occ = occupancy_estimate(*ki);
+    if (occ <= 0) {
+        set_error("config_wave_capacity: no compiler resource record for this kernel (rebuild with paper_2604_26039_amd.build)");
+        return RAMP_EUNSUPPORTED;
+    }
+    return kNumCU * occ;
+}
+
+extern "C" int ramp_config_runtime_occupancy(const ramp_config *cfg, int *wg_per_cu)
+{
+    if (!cfg || !wg_per_cu) {
+        set_error("config_runtime_occupancy: NULL argument");
+        return RAMP_EINVAL;
+    }
+    const KernelInfo *ki = find_kernel(*cfg);
+    if (!ki) {
+        set_error("config_runtime_occupancy: configuration not instantiated");
+        return RAMP_EUNSUPPORTED;
+    }
+    for (int st = 0; st < 2; ++st) {
+        int n = 0;
+        hipError_t err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, ki->kernel_fn[st], ki->block_threads, 0);
+        if (err != hipSuccess) {
+            set_error("config_runtime_occupancy: %s", hipGetErrorString(err));
+            return RAMP_EHIP;
+        }
+        wg_per_cu[st] = n;
+    }
+    return RAMP_OK;
 }
 
 extern "C" size_t ramp_fused_moe_workspace_bytes(const ramp_shape *shape, const ramp_config *cfg)

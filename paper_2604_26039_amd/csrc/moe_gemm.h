@@ -466,6 +466,13 @@ KernelInfo make_info()
     ki.lds_bytes = TT::LDS_BYTES;
     ki.acc_regs = TT::ACC_REGS;
     ki.launch = &launch_gemm<BM, BN, BK, WM, WN, NSTAGE, LOOP>;
+    ki.kernel_fn[0] = reinterpret_cast<const void *>(&moe_gemm_kernel<1, BM, BN, BK, WM, WN, NSTAGE, LOOP>);
+    ki.kernel_fn[1] = reinterpret_cast<const void *>(&moe_gemm_kernel<2, BM, BN, BK, WM, WN, NSTAGE, LOOP>);
+    ki.block_threads = WM * WN * 64;
+    ki.family = "moe_gemm_kernel";
+    const int targs[8] = {1, BM, BN, BK, WM, WN, NSTAGE, LOOP};
+    for (int i = 0; i < 8; ++i) ki.targs[i] = targs[i];
+    ki.n_targs = 8;
     return ki;
 }
 

@@ -456,6 +456,13 @@ KernelInfo make_pingpong_info()
     ki.lds_bytes = l1 > l2 ? l1 : l2;
     ki.acc_regs = TT::ACC_REGS;
     ki.launch = &launch_pingpong<BM, BN, BK, WM, WN, NSTAGE>;
+    ki.kernel_fn[0] = reinterpret_cast<const void *>(&moe_pingpong_kernel<1, BM, BN, BK, WM, WN, NSTAGE>);
+    ki.kernel_fn[1] = reinterpret_cast<const void *>(&moe_pingpong_kernel<2, BM, BN, BK, WM, WN, (NSTAGE > 4 ? 4 : NSTAGE)>);
+    ki.block_threads = 512;
+    ki.family = "moe_pingpong_kernel";
+    const int targs[8] = {1, BM, BN, BK, WM, WN, NSTAGE, 0};
+    for (int i = 0; i < 8; ++i) ki.targs[i] = targs[i];
+    ki.n_targs = 7;
     return ki;
 }
 

@@ -197,6 +197,13 @@ KernelInfo make_stream_info()
     ki.lds_bytes = ST::LDS_BYTES > 1024 ? ST::LDS_BYTES : 1024;
     ki.acc_regs = ST::ACC_REGS + 2 * U * (FBW + ST::NB) * 4;  // accumulators + the two load batches
     ki.launch = &launch_stream<BM, FBW, WF, WK, U>;
+    ki.kernel_fn[0] = reinterpret_cast<const void *>(&moe_stream_kernel<1, BM, FBW, WF, WK, U>);
+    ki.kernel_fn[1] = reinterpret_cast<const void *>(&moe_stream_kernel<2, BM, FBW, WF, WK, U>);
+    ki.block_threads = WF * WK * 64;
+    ki.family = "moe_stream_kernel";
+    const int targs[8] = {1, BM, FBW, WF, WK, U, 0, 0};
+    for (int i = 0; i < 8; ++i) ki.targs[i] = targs[i];
+    ki.n_targs = 6;
     return ki;
 }
 

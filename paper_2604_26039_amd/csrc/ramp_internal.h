@@ -114,7 +114,22 @@ struct KernelInfo {
     int lds_bytes;
     int acc_regs;               // fp32 accumulators per lane (stage 1, the larger one)
     void (*launch)(int stage, const GemmArgs &, hipStream_t);
+    const void *kernel_fn[2];   // the two projection kernels (stage 1, stage 2), for occupancy queries
+    int block_threads;
+    const char *family;         // kernel template name and the template arguments of the stage-1 instantiation:
+    int targs[8];               // the key into the compiler's per-kernel resource table (kernel_resources.inc)
+    int n_targs;
 };
+
+// What the compiler reported for one kernel instantiation when the library was built (registers, LDS,
+// wavefronts per SIMD that fit); generated by the build into kernel_resources.inc.
+struct KernelResources {
+    const char *family;
+    int n_targs;
+    int targs[8];
+    int vgprs, agprs, lds_bytes, waves_per_simd;
+};
+const KernelResources *find_resources(const char *family, const int *targs, int n_targs);
 int num_kernels();
 const KernelInfo &kernel_info(int i);
 const KernelInfo *find_kernel(const ramp_config &cfg);

@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.ramp_config_ntiles.argtypes = [sp, cp]
         L.ramp_config_wave_capacity.restype = ci
         L.ramp_config_wave_capacity.argtypes = [cp]
+        L.ramp_config_runtime_occupancy.restype = ci
+        L.ramp_config_runtime_occupancy.argtypes = [cp, ctypes.POINTER(ci)]
         L.ramp_align_capacity.restype = sz
         L.ramp_align_capacity.argtypes = [ci, ci, ci, ci]
         L.ramp_align_workspace_bytes.restype = sz
@@ -112,6 +114,10 @@ def lib() -> ctypes.CDLL:
         L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp, vp, ci, vp]
         L.ramp_cost_model_select.restype = ci
         L.ramp_cost_model_select.argtypes = [ci, ci, cp, vp, vp, vp, vp, ci, ctypes.POINTER(ci), vp]
+        L.ramp_cost_model_fit5.restype = ci
+        L.ramp_cost_model_fit5.argtypes = [ci, vp, ci, vp, vp, vp, vp, ci, vp]
+        L.ramp_cost_model_select5.restype = ci
+        L.ramp_cost_model_select5.argtypes = [ci, ci, cp, vp, vp, vp, vp, ci, ctypes.POINTER(ci), vp]
         L.ramp_grid.restype = ci
         L.ramp_grid.argtypes = [ci, ci, cp, vp, vp, vp, vp, vp]
         L.ramp_region_classify.restype = ci
@@ -139,11 +145,11 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = [
-    "ramp_last_error", "ramp_num_configs", "ramp_get_config", "ramp_config_ntiles", "ramp_config_wave_capacity",
+    "ramp_last_error", "ramp_num_configs", "ramp_get_config", "ramp_config_ntiles", "ramp_config_wave_capacity", "ramp_config_runtime_occupancy",
     "ramp_align_capacity", "ramp_align_workspace_bytes", "ramp_moe_histogram", "ramp_moe_align", "ramp_pack_bytes",
     "ramp_pack_weights", "ramp_fused_moe_workspace_bytes", "ramp_fused_moe_workspace_layout", "ramp_fused_moe", "ramp_fused_moe_static",
     "ramp_fused_moe_selected_workspace_bytes", "ramp_fused_moe_selected",
-    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_grid", "ramp_region_classify", "ramp_select_table_bytes", "ramp_select_table_build",
+    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_cost_model_fit5", "ramp_cost_model_select5", "ramp_grid", "ramp_region_classify", "ramp_select_table_bytes", "ramp_select_table_build",
     "ramp_select_result_bytes", "ramp_select_device", "ramp_select_poll", "ramp_select_wait", "ramp_copy_bytes", "ramp_probe_enable", "ramp_probe_read",
 ]
 
@@ -205,6 +211,13 @@ def config_wave_capacity(cfg: Config) -> int:
     if n < 0:
         _check(n)
     return n
+
+
+def config_runtime_occupancy(cfg: Config):
+    """(up-projection, down-projection) workgroups per compute unit according to the HIP runtime (needs a GPU)."""
+    out = (ctypes.c_int * 2)()
+    _check(lib().ramp_config_runtime_occupancy(ctypes.byref(cfg), out))
+    return int(out[0]), int(out[1])
 
 
 # ----------------------------------------------------------------------------- align
@@ -296,9 +309,11 @@ def copy_bytes(dst: torch.Tensor, src: torch.Tensor, nbytes: int, stream=None):
 
 # ----------------------------------------------------------------------------- cost model (host)
 
-def cost_model_fit(wave_cap: Sequence[int], grid, time_us, distinct=None, pairs=None, flags: int = CM_EQ6) -> np.ndarray:
+def cost_model_fit(wave_cap: Sequence[int], grid, time_us, distinct=None, pairs=None, flags: int = CM_EQ6,
+                   terms: int = 4) -> np.ndarray:
     """grid, time_us (and distinct with CM_DISTINCT_TILES): [n_cfg, n_pts]; pairs (with CM_PAIRS): [n_pts].
-    Returns theta float32 [n_cfg, 4]."""
+    Returns theta float32 [n_cfg, terms]; terms = 5 calls ramp_cost_model_fit5 (Sec. 5.3 ablation)."""
+    assert terms in (4, 5)
     grid = _np(grid, np.int64)
     time_us = _np(time_us, np.float64)
     n_cfg, n_pts = grid.shape
@@ -311,26 +326,28 @@ def cost_model_fit(wave_cap: Sequence[int], grid, time_us, distinct=None, pairs=
         assert pairs.shape == (n_pts,)
     wc = _np(wave_cap, np.int32)
     assert wc.size == n_cfg
-    theta = np.zeros((n_cfg, 4), np.float32)
-    _check(lib().ramp_cost_model_fit(n_cfg, wc.ctypes.data, n_pts, grid.ctypes.data,
-                                     distinct.ctypes.data if distinct is not None else None,
-                                     pairs.ctypes.data if pairs is not None else None, time_us.ctypes.data,
-                                     flags, theta.ctypes.data))
+    theta = np.zeros((n_cfg, terms), np.float32)
+    fn = lib().ramp_cost_model_fit if terms == 4 else lib().ramp_cost_model_fit5
+    _check(fn(n_cfg, wc.ctypes.data, n_pts, grid.ctypes.data,
+              distinct.ctypes.data if distinct is not None else None,
+              pairs.ctypes.data if pairs is not None else None, time_us.ctypes.data, flags, theta.ctypes.data))
     return theta
 
 
 def cost_model_select(E: int, cfgs: Sequence[Config], ntiles, wave_cap, theta, expert_counts, want_pred=False,
-                      flags: int = CM_EQ6):
+                      flags: int = CM_EQ6, terms: int = 4):
+    assert terms in (4, 5)
     n = len(cfgs)
     arr = (Config * n)(*cfgs)
     nt, wc = _np(ntiles, np.int32), _np(wave_cap, np.int32)
-    th = _np(theta, np.float32).reshape(n, 4)
+    th = _np(theta, np.float32).reshape(n, terms)
     counts = _np(expert_counts, np.int32)
     assert counts.size == E and nt.size == n and wc.size == n
     best = ctypes.c_int(-1)
     pred = np.zeros(n, np.float64) if want_pred else None
-    _check(lib().ramp_cost_model_select(E, n, arr, nt.ctypes.data, wc.ctypes.data, th.ctypes.data, counts.ctypes.data,
-                                        flags, ctypes.byref(best), pred.ctypes.data if want_pred else None))
+    fn = lib().ramp_cost_model_select if terms == 4 else lib().ramp_cost_model_select5
+    _check(fn(E, n, arr, nt.ctypes.data, wc.ctypes.data, th.ctypes.data, counts.ctypes.data,
+              flags, ctypes.byref(best), pred.ctypes.data if want_pred else None))
     return (best.value, pred) if want_pred else best.value
 
 

@@ -109,8 +109,13 @@ def time_config(layers: LayerSet, cfg: ramp.Config, pt: Point, warmup: int = 10,
     e1.record()
     torch.cuda.synchronize()
     one = max(e0.elapsed_time(e1), 1e-3)
-    iters = int(max(5, min(iters, budget_ms / one)))
-    warmup = int(max(1, min(warmup, iters // 3)))
+    if one * 3 > budget_ms:
+        # a call that takes a large share of the budget (a small-tile configuration far outside its regime): the two
+        # calls above were the warm-up, three timed calls give the median
+        iters, warmup = 3, 0
+    else:
+        iters = int(max(5, min(iters, budget_ms / one)))
+        warmup = int(max(1, min(warmup, iters // 3)))
     for i in range(warmup):
         call(i)
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
@@ -175,6 +180,19 @@ def fit(fam: Family, grid: np.ndarray, t_us: np.ndarray, counts_list=None, flags
     if flags & ramp.CM_PAIRS:
         pairs = np.array([ramp.grid(fam.shape.E, fam.cfgs, fam.ntiles, c)[2] for c in counts_list], np.int64)
     return ramp.cost_model_fit(fam.wave_cap, grid, t_us, distinct=distinct, pairs=pairs, flags=flags)
+
+
+def fit5(fam: Family, grid: np.ndarray, t_us: np.ndarray, counts_list=None, flags: int = ramp.CM_EQ6) -> np.ndarray:
+    """The five-term ablation of Sec. 5.3 (a fifth column g^2): theta5 [n_cfg, 5]."""
+    distinct = distinct_tiles(fam, counts_list) if (flags & ramp.CM_DISTINCT_TILES) else None
+    pairs = None
+    if flags & ramp.CM_PAIRS:
+        pairs = np.array([ramp.grid(fam.shape.E, fam.cfgs, fam.ntiles, c)[2] for c in counts_list], np.int64)
+    return ramp.cost_model_fit(fam.wave_cap, grid, t_us, distinct=distinct, pairs=pairs, flags=flags, terms=5)
+
+
+def select5(fam: Family, theta5: np.ndarray, counts: np.ndarray, flags: int = ramp.CM_EQ6) -> int:
+    return ramp.cost_model_select(fam.shape.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta5, counts, flags=flags, terms=5)
 
 
 def select(fam: Family, theta: np.ndarray, counts: np.ndarray, flags: int = ramp.CM_EQ6) -> int:

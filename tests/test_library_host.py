@@ -128,6 +128,45 @@ def test_fit_predictions_match_oracle():
     assert saw_log and saw_nolog
 
 
+@pytest.mark.parametrize("flags", [0, 15])
+def test_five_term_fit_and_select_match_oracle(flags):
+    """ramp_cost_model_fit5 / select5 (Sec. 5.3 ablation) against the oracle's five-term fit: predictions on the
+    profiling grids and beyond, and the argmin of a brute-force evaluation."""
+    rng = np.random.default_rng(11)
+    n_cfg, n_pts = 12, 25
+    W, g, t = synthetic_profile(rng, n_cfg, n_pts)
+    t = t + 0.5 * (g / W[:, None]) ** 2
+    distinct = np.maximum(1, g // 3) if flags & ramp.CM_DISTINCT_TILES else None
+    pairs = rng.integers(8, 60000, n_pts).astype(np.int64) if flags & ramp.CM_PAIRS else None
+    theta5 = ramp.cost_model_fit(W, g, t, distinct=distinct, pairs=pairs, flags=flags, terms=5)
+    assert theta5.shape == (n_cfg, 5)
+    for c in range(n_cfg):
+        th_o, _ = oracle.fit_cost_model(g[c], t[c], int(W[c]), n_terms=5, distinct=None if distinct is None else distinct[c],
+                                        relative=bool(flags & ramp.CM_RELATIVE), wave_floor=bool(flags & ramp.CM_WAVE_FLOOR),
+                                        pairs=pairs)
+        for i in range(n_pts):
+            kw = dict(distinct=None if distinct is None else distinct[c, i], wave_floor=bool(flags & ramp.CM_WAVE_FLOOR),
+                      pairs=None if pairs is None else pairs[i])
+            po = oracle.predict5(th_o, g[c, i], int(W[c]), **kw)
+            pl = oracle.predict5(theta5[c].astype(np.float64), g[c, i], int(W[c]), **kw)
+            assert abs(po - pl) <= 5e-5 * max(abs(po), 1.0)
+    # select5 on a histogram: brute force over the oracle's five-term prediction with the library's coefficients
+    E = 16
+    counts = rng.integers(0, 300, E).astype(np.int32)
+    cfgs = [ramp.Config(int(bm), 128, 64, 4, 2, 0) for bm in rng.choice([4, 16, 64, 256], n_cfg)]
+    nt = rng.integers(2, 40, n_cfg).astype(np.int32)
+    best, pred = ramp.cost_model_select(E, cfgs, nt, W, theta5, counts, want_pred=True, flags=flags, terms=5)
+    active, P = int((counts > 0).sum()), int(counts.sum())
+    want = []
+    for c in range(n_cfg):
+        gc = oracle.grid(counts, cfgs[c].bm, int(nt[c]))
+        want.append(oracle.predict5(theta5[c].astype(np.float64), gc, int(W[c]),
+                                    distinct=active * int(nt[c]) if flags & ramp.CM_DISTINCT_TILES else None,
+                                    wave_floor=bool(flags & ramp.CM_WAVE_FLOOR), pairs=P if flags & ramp.CM_PAIRS else None))
+    assert np.allclose(pred, want, rtol=1e-12, atol=1e-9)
+    assert best == int(np.argmin(want))
+
+
 def test_fit_handles_constant_grid():
     # every profiling point has the same grid (T=1: one tile per routed expert whatever the skew)
     W = np.array([256], np.int32)

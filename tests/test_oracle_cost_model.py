@@ -315,3 +315,48 @@ def test_select_with_wave_floor_and_pairs_matches_brute_force():
     for c in range(n):
         g = sum(-(-int(x) // int(bm[c])) for x in counts) * int(nt[c])
         assert p_floor[c] - p_plain[c] == pytest.approx(float(theta[c, 1]) * (max(g / W[c], 1.0) - g / W[c]), abs=1e-9)
+
+
+# ----------------------------------------------------------------------------- five-term ablation (Sec. 5.3)
+
+def test_five_term_fit_is_a_quadratic_polynomial_fit_when_the_log_is_off():
+    """With grids above the wave capacity the log column is off and a + b*g/W + c*g + e*(g/W)^2 spans the
+    polynomials of degree 2 in g: predictions must equal numpy.polyfit's (a textbook routine)."""
+    rng = np.random.default_rng(3)
+    W = 256
+    g = rng.integers(300, 9000, 25).astype(np.float64)
+    t = 12.0 + 0.02 * g + 3e-7 * g * g + rng.normal(0, 0.5, 25)
+    theta5, use_log = oracle.fit_cost_model(g, t, W, n_terms=5)
+    assert not use_log and theta5.shape == (5,) and theta5[3] == 0.0
+    poly = np.polyfit(g, t, 2)
+    for q in (300.0, 1234.0, 9000.0, 20000.0):
+        assert oracle.predict5(theta5, q, W) == pytest.approx(np.polyval(poly, q), rel=1e-9)
+
+
+def test_five_term_fit_recovers_an_exact_model_and_reduces_to_four_terms():
+    W = 1024
+    g = np.array([3, 8, 20, 50, 90, 160, 300, 520, 800, 1500, 2600, 4000, 7000], np.float64)   # lower median 300 < W: log on
+    exact = 9.0 + 0.004 * g + 2.5 * np.log(g + 1.0) + 0.7 * (g / W) ** 2
+    theta5, use_log = oracle.fit_cost_model(g, exact, W, n_terms=5)
+    assert use_log
+    for gi, ti in zip(g, exact):
+        assert oracle.predict5(theta5, gi, W) == pytest.approx(ti, rel=1e-9)
+    assert theta5[4] == pytest.approx(0.7, rel=1e-6) and theta5[3] == pytest.approx(2.5, rel=1e-6)
+    # data without a quadratic part: the fifth coefficient vanishes and the predictions are the four-term ones
+    four = 9.0 + 0.004 * g + 2.5 * np.log(g + 1.0)
+    th5, _ = oracle.fit_cost_model(g, four, W, n_terms=5)
+    th4, _ = oracle.fit_cost_model(g, four, W, n_terms=4)
+    assert abs(th5[4]) < 1e-8
+    X = oracle.design_matrix(g, W)
+    assert np.allclose(X @ th4, [oracle.predict5(th5, gi, W) for gi in g], rtol=1e-9)
+
+
+def test_five_term_residual_is_orthogonal_to_the_quadratic_column():
+    rng = np.random.default_rng(5)
+    W = 512
+    g = rng.integers(1, 3000, 25).astype(np.float64)
+    t = 5 + 0.01 * g + rng.normal(0, 1.0, 25)
+    th5, use_log = oracle.fit_cost_model(g, t, W, n_terms=5)
+    res = np.array([oracle.predict5(th5, gi, W) for gi in g]) - t
+    assert abs(res @ (g / W) ** 2) <= 1e-6 * np.linalg.norm(res) * np.linalg.norm((g / W) ** 2)
+    assert abs(res.sum()) <= 1e-8 * 25 * np.abs(t).max()
