@@ -62,7 +62,11 @@ typedef struct {
  *          bk is then the k-extent of one register load batch); 0x200 = LDS-staged path with
  *          the register-pipelined main loop; 0x400 = persistent ping-pong kernel for the
  *          large tiles (one workgroup per compute unit walks its share of the tiles, two
- *          groups of four wavefronts alternate memory and MFMA phases).
+ *          groups of four wavefronts alternate memory and MFMA phases); bits 12-15 = v > 0: GROUP_M
+ *          mode (Sec. 4.1, Eq. 4) in its XCD-aware form: the workgroups of one XCD (one L2) take
+ *          blocks of 2^v M-tiles x about 32/2^v N-tiles, so the M-tiles of a block share the weight
+ *          slices of a few N-tiles in L2; v = 0: a block spans all N-tiles and the token rows of its
+ *          M-tiles are what stays in L2.
  *          Take configurations from ramp_get_config rather than composing mode words. */
 typedef struct {
     int32_t bm, bn, bk, waves, stages, mode;

@@ -444,6 +444,7 @@ int enqueue_projections(const ramp_shape &s, const ramp_config &cfg, const Kerne
     g.m_tiles_cap = (int)(w.cap / (size_t)cfg.bm);
     g.pred = pred;
     g.pred_value = pred_value;
+    g.group_m_req = group_m_of_mode(cfg.mode);
 
     // phase 1 + 2: up-projection with SwiGLU epilogue
     g.act = static_cast<const uint16_t *>(X);

@@ -8,6 +8,11 @@
 // registers only).  Group 1 runs one barrier behind group 0, so while one group multiplies the other
 // does its memory phase on the same SIMDs and the matrix pipe does not wait for LDS.
 //
+// Token blocks and wavefronts.  The 16-row token blocks of a tile are dealt to the WM wavefront rows round robin
+// (block b belongs to row b % WM), so a ragged tile (the real rows come first, the sentinel padding after them)
+// spreads its real blocks evenly over all wavefronts instead of leaving whole wavefront rows idle; the products
+// and, in ragged tiles, the operand reads of all-padding blocks are skipped.
+//
 // Token staging in the up-projection.  The token rows are gathered (row = pair / k of X, 2*H bytes
 // apart), so every row touched by a load instruction is another page for the address translation in
 // the vector memory path, and that, not bytes, is what the gather costs: 16 rows x 64 B per
@@ -193,11 +198,13 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
 
     // ---- LDS read offsets of this lane's operand fragments ----
     // tokens, row-major batch: row (wm*NB+nb)*16 + r16 sits in block row/8 at (row%8)*128, chunk c at (c ^ (row/2)%8)*16
-    const int xrow_off = (wm * NB * 16 + r16) / 8 * 1024 + (r16 & 7) * 128;
+    const int xrow_off = wm * 2048 + (r16 >> 3) * 1024 + (r16 & 7) * 128;  // token block nb of this wavefront is block nb*WM + wm
     const int xsw = (r16 >> 1) & 7;
     bf16x8 fx[KS][NB], fw[KS][NACC];
     int nb_valid = 0;  // token blocks of this wavefront with at least one real row in the current tile
-    auto read_all = [&](int kk0, int xbuf, int wbuf) {  // kk0: 32-wide k-step of the slice inside its token batch
+    // kk0: 32-wide k-step of the slice inside its token batch; partial_c: skip the token fragments of all-padding blocks
+    auto read_all = [&](int kk0, int xbuf, int wbuf, auto partial_c) {
+        constexpr bool PARTIAL = decltype(partial_c)::value;
         const char *xs = lds_x + xbuf * PT::X_BYTES;
         const char *ws = lds_w + wbuf * PT::W_BYTES + lane * 16;
 #pragma unroll
@@ -214,11 +221,13 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
                 const int coff = ((kk * 4 + q) ^ xsw) * 16;
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
-                    fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + xrow_off + nb * 2048 + coff);
+                    if (!PARTIAL || nb < nb_valid)
+                        fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + xrow_off + nb * (WM * 2048) + coff);
             } else {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
-                    fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + ((wm * NB + nb) * KS + ks) * 1024 + lane * 16);
+                    if (!PARTIAL || nb < nb_valid)
+                        fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + ((nb * WM + wm) * KS + ks) * 1024 + lane * 16);
             }
         }
     };
@@ -243,8 +252,8 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto blocks_valid = [&](int rows) {  // token blocks of this wavefront that hold at least one real row
-        const int v = (rows - wm * NB * 16 + 15) / 16;
+    auto blocks_valid = [&](int rows) {  // token blocks of this wavefront (wm, wm + WM, ...) with at least one real row
+        const int v = ((rows + 15) / 16 - wm + WM - 1) / WM;
         return v < 0 ? 0 : (v > NB ? NB : v);
     };
 
@@ -289,7 +298,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         if (STAGE == 2) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                const int tr = (wm * NB + nb) * 16 + r16;
+                const int tr = (nb * WM + wm) * 16 + r16;
                 out_pair[nb] = (nb < nb_valid) ? a.sorted[m_tile * BM + tr] : a.P;
                 out_wgt[nb] = (out_pair[nb] < a.P) ? a.topk_w[out_pair[nb]] : 0.0f;
             }
@@ -304,7 +313,8 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             // ---- M phase: both groups have read slice kt-1 (its buffers are free).  Operand reads first, then the
             // loads: the reads are what the barrier waits for, the loads only have to be issued.
             const int par = (XS == 2) ? (kt & 1) : 0;  // position of the slice inside its token batch
-            if (MODE != 2) read_all(par * KS, xbat_cur % NX, wbuf_cur);
+            // (the down-projection has no registers to spare for the conditional form of the reads)
+            if (MODE != 2) read_all(par * KS, xbat_cur % NX, wbuf_cur, std::integral_constant<bool, MODE == 0 && STAGE == 1>{});
             // the load stream crosses into the next tile NSTAGE-1 slices (one token batch) before this one ends
             if (kt == KT - NSTAGE + 1) {
 #pragma unroll
@@ -405,7 +415,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             if (nb >= nb_valid) continue;
-            const int slot = m_tile * BM + (wm * NB + nb) * 16 + r16;
+            const int slot = m_tile * BM + (nb * WM + wm) * 16 + r16;
             const int rb0 = f0 / 16 + wn * FB;
             if (STAGE == 1) {
                 store_token_row<1, FB>(a, &acc[0][nb], &acc[FB][nb], NB, (size_t)slot, rb0, q, 1.0f);
@@ -444,13 +454,13 @@ void launch_pingpong(int stage, const GemmArgs &a, hipStream_t stream)
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int NSTAGE>
-KernelInfo make_pingpong_info()
+KernelInfo make_pingpong_info(int group_bits = 0)
 {
     using TT = TileTraits<BM, BN, BK, WM, WN, 2>;  // tile geometry only; the ring depths are defined here
     constexpr int l1 = PingPongTraits<1, BM, BN, BK, WM, WN, NSTAGE>::LDS_BYTES;
     constexpr int l2 = PingPongTraits<2, BM, BN, BK, WM, WN, (NSTAGE > 4 ? 4 : NSTAGE)>::LDS_BYTES;
     KernelInfo ki;
-    ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | kModePingPong};
+    ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | kModePingPong | (group_bits << kModeGroupShift)};
     ki.wm = WM;
     ki.wn = WN;
     ki.lds_bytes = l1 > l2 ? l1 : l2;

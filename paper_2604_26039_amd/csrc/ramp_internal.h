@@ -92,6 +92,7 @@ struct GemmArgs {
     int topk;                   // k
     int n_tiles;                // feature tiles of this stage
     int m_tiles_cap;            // launched M-tiles (upper bound)
+    int group_m_req;            // GROUP_M of the configuration (mode bits 12-15): M-tiles per XCD block, 0 = automatic
     int group_m, group_n;       // M-tiles x N-tiles per XCD block of the workgroup->tile map (set by the launcher)
     int total_tiles;            // persistent kernels: tile ids to walk (set by the launcher)
     const int32_t *pred;        // device-side predicate: the launch does nothing unless *pred == pred_value (NULL: always runs)
@@ -107,6 +108,12 @@ __device__ __forceinline__ bool launch_deselected(const int32_t *pred, int pred_
 constexpr int kModeStream = 0x100;    // weight-streaming kernel (moe_stream.h); bits 0-7 = WK instead
 constexpr int kModePipe = 0x200;      // LDS-staged kernel with the register-pipelined main loop (moe_gemm.h)
 constexpr int kModePingPong = 0x400;  // persistent ping-pong kernel (moe_pingpong.h)
+// GROUP_M (Sec. 4.1, Eq. 4), XCD-aware: bits 12-15 = v > 0 makes every XCD take blocks of 2^v M-tiles x (32 >> v)
+// N-tiles, so that the M-tiles of a block share the weight slices of its few N-tiles in that XCD's L2; 0 = a block
+// spans all N-tiles (the token rows of its M-tiles stay in L2 instead).
+constexpr int kModeGroupShift = 12;
+constexpr int kModeGroupMask = 0xF << kModeGroupShift;
+inline int group_m_of_mode(int mode) { const int v = (mode & kModeGroupMask) >> kModeGroupShift; return v ? (1 << v) : 0; }
 
 struct KernelInfo {
     ramp_config cfg;
