@@ -89,6 +89,27 @@ def kernel_roofline(s, T, counts, k_us):
     return roof
 
 
+def mfma_ceiling(torch, ramp, dev, rounds=20000):
+    """PFLOP/s of a register-resident MFMA loop (no memory traffic) on zero operands and on N(0,1) bf16 operands:
+    what the matrix pipes sustain under this chip's power limit, next to the nominal 2.5 PFLOP/s."""
+    sink = torch.empty(256 * 512 * 4, dtype=torch.float32, device=dev)
+    out = {}
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    for name, ops in (("zeros", torch.zeros(12 * 512, dtype=torch.bfloat16, device=dev)),
+                      ("normal", torch.randn(12 * 512, generator=gen, device=dev).to(torch.bfloat16))):
+        best = 0.0
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = ramp.mfma_rate_probe(ops, rounds, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) * 1e-15)
+        out[name + "_operands_pflops"] = best
+    return out
+
+
 def extra_row(torch, ramp, synth, tuner, name, T, beta, iters, dev):
     """Largest point of another model shape: exhaustive pass over its large-tile configurations (bm >= 128),
     stage times of the best one."""
@@ -449,6 +470,9 @@ def main():
     # roofline of the dominant kernel (up-projection + SwiGLU): algorithmic flops / bytes per launch
     k_us = probe_ms / max(probe_n, 1) * 1e3
     roof = kernel_roofline(s, T_head, p.counts, k_us)
+    ceiling = mfma_ceiling(torch, ramp, dev)
+    log(f"[bench] register-resident MFMA loop: {ceiling['zeros_operands_pflops']:.2f} PFLOP/s on zeros, "
+        f"{ceiling['normal_operands_pflops']:.2f} PFLOP/s on N(0,1) bf16 operands (nominal peak {MFMA_PEAK_PFLOPS})")
     rec = RECORDED_TRAFFIC.get((args.model, T_head, str(beta_head)))
     roof.update(traffic=rec[0] if rec else None, traffic_source=(rec[1] + " (recorded rocprofv3 --pmc value, not measured in this run)") if rec else None,
                 kernel=kernel_name(cfg_head), launches=probe_n)
@@ -537,7 +561,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.model}-shaped MoE layer H={s.H} I={s.I} E={s.E} top-{s.k}, T={T_head}, beta={beta_head}",
                    "tile_config": cfg_head.key(), "weight_copies_rotated": n_layers},
-        "roofline": roof, "whole_path": whole, "cpu_baseline": cpu, "cost_model": summary,
+        "roofline": roof, "mfma_ceiling_measured": ceiling, "whole_path": whole, "cpu_baseline": cpu, "cost_model": summary,
         "largest_points": extra,
         "sweep": [dict(T=r["T"], beta=r["beta"], us=round(r["ra_us"], 1), hot_us=round(r["ra_hot_us"], 1), best_us=round(r["best_us"], 1),
                        static_us=round(r["static_us"], 1), bound=r["bound"], roofline_frac=round(r["roofline_frac"], 3),

@@ -316,6 +316,16 @@ int ramp_probe_read(double *total_ms /*host*/, int *launches /*host*/);
  * known-size reference kernel that profiler byte counters are calibrated against. */
 int ramp_copy_bytes(void *dst /*dev*/, const void *src /*dev*/, size_t bytes, void *stream);
 
+
+/* Register-resident matrix-pipe loop, the ceiling that the MFMA-bound kernels are compared with next to the
+ * nominal peak: 256 workgroups of 8 wavefronts (two per SIMD) each run `rounds` rounds of 32 independent
+ * v_mfma_f32_16x16x32_bf16 on operand fragments read once from `operands` (dev, 12 fragments of 512 bf16 = 12 KB)
+ * and write their sums to `sink` (dev, 256*512*4 floats).  *flops (host, optional) receives the floating-point
+ * operations of the launch; the caller times it.  The chip is power limited and its clock follows the operand
+ * bits, so zeros and random values give different rates. */
+int ramp_mfma_rate_probe(const void *operands /*dev bf16 [12*512]*/, int rounds, void *sink /*dev fp32 [524288]*/,
+                         void *stream, double *flops /*host out, may be NULL*/);
+
 #ifdef __cplusplus
 }
 #endif

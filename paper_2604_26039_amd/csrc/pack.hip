@@ -72,6 +72,40 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4 *__restrict__ dst, cons
         dst[i] = src[i];
 }
 
+// Register-resident MFMA loop: the matrix-pipe rate this chip sustains on the operand values it is given, with no
+// memory traffic at all.  Two wavefronts per SIMD, each with the 4 x 8 accumulator blocks of the 256x256 ping-pong
+// tile (32 independent v_mfma_f32_16x16x32_bf16 per round).  The clock, and with it the rate, depends on the
+// operand bits (the chip is power limited), which is why the operands come from the caller.
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_floatx4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(512, 1) void mfma_rate_kernel(const uint16_t *__restrict__ operands, int rounds,
+                                                           float *__restrict__ sink)
+{
+    const int lane = threadIdx.x & 63;
+    probe_bf16x8 fw[4], fx[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fw[i] = *reinterpret_cast<const probe_bf16x8 *>(operands + (i * 64 + lane) * 8);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) fx[j] = *reinterpret_cast<const probe_bf16x8 *>(operands + ((4 + j) * 64 + lane) * 8);
+    probe_floatx4 acc[4][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = probe_floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < rounds; ++r) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[i], fx[j], acc[i][j], 0, 0, 0);
+    }
+    probe_floatx4 s = probe_floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += acc[i][j];
+    reinterpret_cast<probe_floatx4 *>(sink)[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 }  // namespace
 }  // namespace ramp
 
@@ -124,4 +158,18 @@ extern "C" int ramp_copy_bytes(void *dst, const void *src, size_t bytes, void *s
     hipLaunchKernelGGL(copy_kernel, dim3(kNumCU * 8), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), bytes / 16);
     return check_launch("copy_kernel");
+}
+
+extern "C" int ramp_mfma_rate_probe(const void *operands, int rounds, void *sink, void *stream, double *flops)
+{
+    using namespace ramp;
+    if (!operands || !sink || rounds <= 0 || reinterpret_cast<uintptr_t>(operands) % 16 ||
+        reinterpret_cast<uintptr_t>(sink) % 16) {
+        set_error("mfma_rate_probe: bad argument");
+        return RAMP_EINVAL;
+    }
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(kNumCU), dim3(512), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint16_t *>(operands), rounds, static_cast<float *>(sink));
+    if (flops) *flops = (double)kNumCU * 8.0 * (double)rounds * 32.0 * (2.0 * 16 * 16 * 32);
+    return check_launch("mfma_rate_kernel");
 }

@@ -138,6 +138,8 @@ def lib() -> ctypes.CDLL:
         L.ramp_probe_enable.argtypes = [ci]
         L.ramp_probe_read.restype = ci
         L.ramp_probe_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
+        L.ramp_mfma_rate_probe.restype = ci
+        L.ramp_mfma_rate_probe.argtypes = [vp, ci, vp, vp, ctypes.POINTER(ctypes.c_double)]
         L.ramp_copy_bytes.restype = ci
         L.ramp_copy_bytes.argtypes = [vp, vp, sz, vp]
         _lib = L
@@ -150,7 +152,7 @@ EXPORTS = [
     "ramp_pack_weights", "ramp_fused_moe_workspace_bytes", "ramp_fused_moe_workspace_layout", "ramp_fused_moe", "ramp_fused_moe_static",
     "ramp_fused_moe_selected_workspace_bytes", "ramp_fused_moe_selected",
     "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_cost_model_fit5", "ramp_cost_model_select5", "ramp_grid", "ramp_region_classify", "ramp_select_table_bytes", "ramp_select_table_build",
-    "ramp_select_result_bytes", "ramp_select_device", "ramp_select_poll", "ramp_select_wait", "ramp_copy_bytes", "ramp_probe_enable", "ramp_probe_read",
+    "ramp_select_result_bytes", "ramp_select_device", "ramp_select_poll", "ramp_select_wait", "ramp_copy_bytes", "ramp_mfma_rate_probe", "ramp_probe_enable", "ramp_probe_read",
 ]
 
 
@@ -305,6 +307,13 @@ def probe_read():
 
 def copy_bytes(dst: torch.Tensor, src: torch.Tensor, nbytes: int, stream=None):
     _check(lib().ramp_copy_bytes(_dev(dst), _dev(src), nbytes, _stream(stream)))
+
+
+def mfma_rate_probe(operands: torch.Tensor, rounds: int, sink: torch.Tensor, stream=None) -> float:
+    """Enqueues the register-resident MFMA loop; returns the flops of the launch (the caller times it)."""
+    fl = ctypes.c_double(0.0)
+    _check(lib().ramp_mfma_rate_probe(_dev(operands), rounds, _dev(sink), _stream(stream), ctypes.byref(fl)))
+    return fl.value
 
 
 # ----------------------------------------------------------------------------- cost model (host)
