@@ -165,6 +165,39 @@ int ramp_fused_moe_static(const ramp_shape *shape, const ramp_config *cfg,
 int ramp_fused_moe_workspace_layout(const ramp_shape *shape, const ramp_config *cfg,
                                     size_t offsets[4]);
 
+/* ---- W8A8 FP8 variant (Sec. 4.3 "W8A8 FP8, 128x128 block scales"; Sec. 2.2 phase 2 re-quantisation) -------------
+ * Same layer, same arguments, 8-bit operands: OCP E4M3 codes (largest value 448, round to nearest even, saturating)
+ * with power-of-two block scales kept as E8M0 bytes b (scale 2^(b-127), the smallest power of two with
+ * amax/scale <= 448; b = 127 for an all-zero block): one scale per 128 x 128 block of every weight matrix, one per
+ * token and 128 consecutive k-values for the activations.  The up-projection multiplies the quantised tokens, its
+ * SwiGLU output is rounded to bf16, quantised the same way and multiplied by the quantised down-projection weights;
+ * accumulation is fp32 in the matrix pipe (v_mfma_scale_f32_16x16x128_f8f6f4, which applies the block scales).
+ * ramp_fp8_pack_weights quantises bf16 boundary-layout weights (as ramp_pack_weights takes them) on the device and
+ * lays the codes out in MFMA fragment order, followed by the scale bytes; outside the timed path.
+ * The FP8 tile family is enumerated apart from the bf16 one (mode bit 0x10000, bk = 128); its configurations
+ * work with ramp_config_ntiles, ramp_grid, ramp_cost_model_fit / select like any other. */
+int ramp_fp8_num_configs(const ramp_shape *shape);
+int ramp_fp8_get_config(const ramp_shape *shape, int idx, ramp_config *out);
+int ramp_fp8_config_wave_capacity(const ramp_config *cfg);
+size_t ramp_fp8_pack_bytes(const ramp_shape *shape);
+int ramp_fp8_pack_weights(const ramp_shape *shape, const void *W_gate, const void *W_up, const void *W_down /*dev bf16*/,
+                          void *packed_fp8 /*dev, 256 B aligned*/, void *stream);
+/* Where things sit inside the packed buffer, for tests (bytes): offsets = {gate+up codes per expert, offset of the
+ * up codes inside an expert, start of the down codes, down codes per expert, start of the scale bytes, scale bytes
+ * per expert}; strides = {scale row stride for k over H, for k over I} (k blocks padded to a multiple of 4).
+ * Codes of one matrix: [feature/16 row blocks][k/128][2 KB], a 2 KB fragment = two 1 KB halves, half h holding
+ * for lane l the bytes k = 32*(l/16) + 16*h + 0..15 of the row l%16 (row -> feature by the bf16 layout's
+ * interleave).  Scale bytes per expert: gate, up [I/128][stride0], then down [H/128][stride1]. */
+int ramp_fp8_pack_layout(const ramp_shape *shape, size_t offsets[6], int32_t strides[2]);
+/* The activation quantiser by itself (tests): src dev bf16 [rows, K] row-major, K % 128 == 0 ->
+ * codes dev uint8 [rows, K], scales dev uint8 [rows][(K/128 rounded up to 4)]. */
+int ramp_fp8_quantize_rows(const void *src, int rows, int K, void *codes, void *scales, void *stream);
+size_t ramp_fused_moe_fp8_workspace_bytes(const ramp_shape *shape, const ramp_config *cfg);
+int ramp_fused_moe_fp8(const ramp_shape *shape, const ramp_config *cfg,
+                       const void *X /*dev bf16 [T,H]*/, const int32_t *topk_ids /*dev [T,k]*/,
+                       const float *topk_w /*dev fp32 [T,k]*/, const void *packed_fp8 /*dev*/,
+                       void *out /*dev bf16 [T,H]*/, void *ws /*dev, 256 B aligned*/, size_t ws_bytes, void *stream);
+
 /* ---- cost model (Eq. 6, Sec. 4.2) -----------------------------------------------------------
  * T_hat(c) = a + b*w + c*m + d*l,  g = (sum_e ceil(n_e/bm_c)) * ntiles_c.
  * flags = 0 is the paper's model as printed: w = g/W, m = g, l = ln(g+1), ordinary least squares.

@@ -186,6 +186,10 @@ bool shape_ok(const ramp_shape &s)
 
 }  // namespace
 
+bool moe_shape_ok(const ramp_shape &s) { return shape_ok(s); }
+bool moe_pair_rows_bf16(const ramp_shape &s) { return (size_t)s.T * s.k * s.H >= kPairRowsBf16Elems; }
+unsigned long long moe_topk_magic(int k) { return topk_magic_of(k); }
+
 int num_kernels()
 {
     init_registry();

@@ -133,7 +133,9 @@ __device__ __forceinline__ void store_token_row(const GemmArgs &a, const floatx4
     // stage 1 writes the activation in the fragment-major layout that stage 2 loads (row_elem is the slot);
     // 8 features aligned to 8 are contiguous in both layouts
     auto dst = [&](int feature) -> uint16_t * {
-        if (STAGE == 1) return a.a_out + act_elem((uint32_t)row_elem, (uint32_t)feature, (uint32_t)a.F >> 5);
+        if (STAGE == 1)
+            return a.a_row_major ? a.a_out + row_elem * (size_t)a.F + (size_t)feature
+                                 : a.a_out + act_elem((uint32_t)row_elem, (uint32_t)feature, (uint32_t)a.F >> 5);
         return reinterpret_cast<uint16_t *>(a.y_out) + row_elem + feature;
     };
     // row blocks rb0.. are consecutive; pairs (even, odd) inside a group of kPermBlocks are 8 adjacent features

@@ -95,6 +95,7 @@ struct GemmArgs {
     int group_m_req;            // GROUP_M of the configuration (mode bits 12-15): M-tiles per XCD block, 0 = automatic
     int group_m, group_n;       // M-tiles x N-tiles per XCD block of the workgroup->tile map (set by the launcher)
     int total_tiles;            // persistent kernels: tile ids to walk (set by the launcher)
+    int a_row_major;            // stage 1: A is written row-major [slot, I] instead of fragment-major (FP8 path)
     const int32_t *pred;        // device-side predicate: the launch does nothing unless *pred == pred_value (NULL: always runs)
     int pred_value;
 };
@@ -111,6 +112,7 @@ constexpr int kModePingPong = 0x400;  // persistent ping-pong kernel (moe_pingpo
 // GROUP_M (Sec. 4.1, Eq. 4), XCD-aware: bits 12-15 = v > 0 makes every XCD take blocks of 2^v M-tiles x (32 >> v)
 // N-tiles, so that the M-tiles of a block share the weight slices of its few N-tiles in that XCD's L2; 0 = a block
 // spans all N-tiles (the token rows of its M-tiles stay in L2 instead).
+constexpr int kModeFp8 = 0x10000;     // W8A8 FP8 family (fp8.hip), listed by ramp_fp8_get_config
 constexpr int kModeGroupShift = 12;
 constexpr int kModeGroupMask = 0xF << kModeGroupShift;
 inline int group_m_of_mode(int mode) { const int v = (mode & kModeGroupMask) >> kModeGroupShift; return v ? (1 << v) : 0; }
@@ -144,6 +146,11 @@ bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s);
 int occupancy_estimate(const KernelInfo &ki);
 
 // sel != NULL: the launch leaves `out` untouched unless 0 <= *sel < n_cand (device-selected layer).
+// shape limits shared by the fused entry points (fused.hip)
+bool moe_shape_ok(const ramp_shape &s);
+bool moe_pair_rows_bf16(const ramp_shape &s);      // per-pair rows kept in bf16 (large batches) instead of fp32
+unsigned long long moe_topk_magic(int k);
+
 int launch_combine(const float *Y, int y_bf16, const int32_t *ids, int T, int k, int E, int H, uint16_t *out,
                    hipStream_t stream, const int32_t *sel = nullptr, int n_cand = 0);
 

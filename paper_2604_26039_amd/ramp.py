@@ -110,6 +110,24 @@ def lib() -> ctypes.CDLL:
         L.ramp_fused_moe_selected_workspace_bytes.argtypes = [sp, ci, cp]
         L.ramp_fused_moe_selected.restype = ci
         L.ramp_fused_moe_selected.argtypes = [sp, ci, cp, i32p, vp, i32p, f32p, vp, vp, vp, sz, vp]
+        L.ramp_fp8_num_configs.restype = ci
+        L.ramp_fp8_num_configs.argtypes = [sp]
+        L.ramp_fp8_get_config.restype = ci
+        L.ramp_fp8_get_config.argtypes = [sp, ci, cp]
+        L.ramp_fp8_config_wave_capacity.restype = ci
+        L.ramp_fp8_config_wave_capacity.argtypes = [cp]
+        L.ramp_fp8_pack_bytes.restype = sz
+        L.ramp_fp8_pack_bytes.argtypes = [sp]
+        L.ramp_fp8_pack_weights.restype = ci
+        L.ramp_fp8_pack_weights.argtypes = [sp, vp, vp, vp, vp, vp]
+        L.ramp_fp8_pack_layout.restype = ci
+        L.ramp_fp8_pack_layout.argtypes = [sp, ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_int32)]
+        L.ramp_fp8_quantize_rows.restype = ci
+        L.ramp_fp8_quantize_rows.argtypes = [vp, ci, ci, vp, vp, vp]
+        L.ramp_fused_moe_fp8_workspace_bytes.restype = sz
+        L.ramp_fused_moe_fp8_workspace_bytes.argtypes = [sp, cp]
+        L.ramp_fused_moe_fp8.restype = ci
+        L.ramp_fused_moe_fp8.argtypes = [sp, cp, vp, i32p, f32p, vp, vp, vp, sz, vp]
         L.ramp_cost_model_fit.restype = ci
         L.ramp_cost_model_fit.argtypes = [ci, vp, ci, vp, vp, vp, vp, ci, vp]
         L.ramp_cost_model_select.restype = ci
@@ -151,6 +169,8 @@ EXPORTS = [
     "ramp_align_capacity", "ramp_align_workspace_bytes", "ramp_moe_histogram", "ramp_moe_align", "ramp_pack_bytes",
     "ramp_pack_weights", "ramp_fused_moe_workspace_bytes", "ramp_fused_moe_workspace_layout", "ramp_fused_moe", "ramp_fused_moe_static",
     "ramp_fused_moe_selected_workspace_bytes", "ramp_fused_moe_selected",
+    "ramp_fp8_num_configs", "ramp_fp8_get_config", "ramp_fp8_config_wave_capacity", "ramp_fp8_pack_bytes", "ramp_fp8_pack_weights",
+    "ramp_fp8_pack_layout", "ramp_fp8_quantize_rows", "ramp_fused_moe_fp8_workspace_bytes", "ramp_fused_moe_fp8",
     "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_cost_model_fit5", "ramp_cost_model_select5", "ramp_grid", "ramp_region_classify", "ramp_select_table_bytes", "ramp_select_table_build",
     "ramp_select_result_bytes", "ramp_select_device", "ramp_select_poll", "ramp_select_wait", "ramp_copy_bytes", "ramp_mfma_rate_probe", "ramp_probe_enable", "ramp_probe_read",
 ]
@@ -292,6 +312,62 @@ def fused_moe_selected(shape: Shape, cfgs: Sequence[Config], selected_idx: torch
     _check(lib().ramp_fused_moe_selected(ctypes.byref(shape), len(cfgs), arr, _dev(selected_idx), _dev(X), _dev(topk_ids),
                                          _dev(topk_w), _dev(packed_weights), _dev(out), _dev(ws),
                                          ws.numel() * ws.element_size(), _stream(stream)))
+
+
+# ----------------------------------------------------------------------------- W8A8 FP8 variant
+
+FP8_MODE = 0x10000
+
+
+def fp8_configs(shape: Shape):
+    n = lib().ramp_fp8_num_configs(ctypes.byref(shape))
+    if n < 0:
+        _check(n)
+    out = []
+    for i in range(n):
+        c = Config()
+        _check(lib().ramp_fp8_get_config(ctypes.byref(shape), i, ctypes.byref(c)))
+        out.append(c)
+    return out
+
+
+def fp8_config_wave_capacity(cfg: Config) -> int:
+    n = lib().ramp_fp8_config_wave_capacity(ctypes.byref(cfg))
+    if n < 0:
+        _check(n)
+    return n
+
+
+def fp8_pack_bytes(shape: Shape) -> int:
+    return int(lib().ramp_fp8_pack_bytes(ctypes.byref(shape)))
+
+
+def fp8_pack_weights(shape: Shape, W_gate, W_up, W_down, packed, stream=None):
+    _check(lib().ramp_fp8_pack_weights(ctypes.byref(shape), _dev(W_gate), _dev(W_up), _dev(W_down), _dev(packed),
+                                       _stream(stream)))
+
+
+def fp8_pack_layout(shape: Shape):
+    """(offsets[6], strides[2]) of the packed FP8 buffer, see ramp_fp8_pack_layout."""
+    off = (ctypes.c_size_t * 6)()
+    st = (ctypes.c_int32 * 2)()
+    _check(lib().ramp_fp8_pack_layout(ctypes.byref(shape), off, st))
+    return [int(v) for v in off], [int(v) for v in st]
+
+
+def fp8_quantize_rows(src: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, stream=None):
+    rows, K = src.shape
+    _check(lib().ramp_fp8_quantize_rows(_dev(src), rows, K, _dev(codes), _dev(scales), _stream(stream)))
+
+
+def fused_moe_fp8_workspace_bytes(shape: Shape, cfg: Config) -> int:
+    return int(lib().ramp_fused_moe_fp8_workspace_bytes(ctypes.byref(shape), ctypes.byref(cfg)))
+
+
+def fused_moe_fp8(shape: Shape, cfg: Config, X, topk_ids, topk_w, packed_fp8, out, ws, stream=None):
+    _check(lib().ramp_fused_moe_fp8(ctypes.byref(shape), ctypes.byref(cfg), _dev(X), _dev(topk_ids), _dev(topk_w),
+                                    _dev(packed_fp8), _dev(out), _dev(ws), ws.numel() * ws.element_size(),
+                                    _stream(stream)))
 
 
 def probe_enable(stage: int):
