@@ -30,6 +30,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_TBS = 8.0       # MI355X HBM3E
 MFMA_PEAK_PFLOPS = 2.5   # dense bf16
+FP8_PEAK_PFLOPS = 5.0    # dense FP8
 
 # HBM bytes per launch of the dominant kernel (up-projection + SwiGLU) recorded from two separate
 # `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same
@@ -43,6 +44,10 @@ RECORDED_TRAFFIC = {
 # Largest point of every other model shape, reported next to the headline.
 EXTRA_ROWS = {
     "dsv3": [("dsv3", 8192, 0.1), ("mixtral", 8192, 1.0), ("qwen3", 8192, 1.0), ("olmoe", 4096, 1.0)],
+}
+# Points of the W8A8 FP8 variant (Sec. 4.3) reported next to them: a weight-bound decode-sized batch and the largest one.
+FP8_ROWS = {
+    "dsv3": [("dsv3", 64, 1.0), ("dsv3", 8192, 1.0), ("mixtral", 16, 1.0), ("mixtral", 8192, 1.0), ("olmoe", 64, 1.0)],
 }
 
 
@@ -107,6 +112,34 @@ def mfma_ceiling(torch, ramp, dev, rounds=20000):
             torch.cuda.synchronize()
             best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) * 1e-15)
         out[name + "_operands_pflops"] = best
+    return out
+
+
+def fp8_rows(torch, ramp, synth, tuner, rows, iters, dev, log_fn):
+    """W8A8 FP8 variant: exhaustive pass over its tile family at each point (one layer set per model shape),
+    against the FP8 roofline (weights one byte each, 5.0 PFLOP/s)."""
+    out = []
+    for name in dict.fromkeys(r[0] for r in rows):
+        s = synth.SHAPES[name]
+        pts = [r for r in rows if r[0] == name]
+        layer_bytes = 3 * s.E * s.H * s.I
+        n_layers = int(max(1, min(8, (3 << 30) // layer_bytes)))
+        layers = tuner.LayerSet(s, max(r[1] for r in pts), n_layers, seed=1, device=dev, x_std=1.0, fp8=True, bf16=False)
+        fam = tuner.Family.of(s, fp8=True)
+        for _, T, beta in pts:
+            p = tuner.Point(T, beta, seed=4242).materialise(s)
+            times = [tuner.time_config(layers, c, p, warmup=3, iters=iters, budget_ms=150.0) for c in fam.cfgs]
+            b = int(np.argmin(times))
+            t_hbm, t_mfma, nbytes, flops = tuner.roofline_lower_bound_us(s, T, p.counts, HBM_PEAK_TBS, FP8_PEAK_PFLOPS, weight_bytes=1)
+            row = dict(model=name, T=T, beta=beta, dtype="fp8_e4m3 (W8A8, power-of-two 128x128 block scales)", us=times[b],
+                       config=fam.cfgs[b].key(), configs_timed=len(fam.cfgs), bound="hbm" if t_hbm >= t_mfma else "mfma",
+                       roofline_frac=max(t_hbm, t_mfma) / times[b], tflops=flops / times[b] * 1e-6, gbs=nbytes / times[b] * 1e-3,
+                       weight_copies_rotated=n_layers)
+            out.append(row)
+            log_fn(f"[bench] FP8 {name} T={T} beta={beta}: best of {len(fam.cfgs)} configurations {times[b]:.1f} us "
+                   f"({100 * row['roofline_frac']:.1f}% of the FP8 {row['bound']} bound), {fam.cfgs[b]}")
+        del layers
+        torch.cuda.empty_cache()
     return out
 
 
@@ -193,7 +226,13 @@ def main():
     if args.config:
         want = tuple(int(v) for v in args.config.split(","))
         match = [i for i, c in enumerate(fam.cfgs) if c.key() == want]
-        assert match, f"configuration {want} is not in the family for this shape"
+        if not match:
+            # an instantiated variant that the pool rule leaves out for this shape (e.g. a GROUP_M block shape): run it by name
+            extra_cfg = ramp.Config(*want)
+            fam = tuner.Family(fam.shape, fam.cfgs + [extra_cfg], np.append(fam.ntiles, ramp.config_ntiles(fam.shape, extra_cfg)).astype(np.int32),
+                               np.append(fam.wave_cap, ramp.config_wave_capacity(extra_cfg)).astype(np.int32))
+            n_cfg = len(fam.cfgs)
+            match = [n_cfg - 1]
         fixed_cfg = match[0]
         args.no_sweep = True
         args.no_extra = True
@@ -536,7 +575,7 @@ def main():
         log(f"[bench] CPU oracle: {per_tok * 1e3:.2f} ms/token on {threads} threads -> {cpu['value'] / 1e6:.2f} s/layer (extrapolated)")
 
     # ------------------------------------------------------------------ largest points of the other model shapes
-    extra = []
+    extra, fp8 = [], []
     if not args.no_extra:
         del dispatcher, ws
         layers = None
@@ -546,10 +585,13 @@ def main():
                 log(f"[bench] time budget reached, skipping {name} T={T}")
                 continue
             extra.append(extra_row(torch, ramp, synth, tuner, name, T, beta, min(args.iters, 12), dev))
+        if time.time() - t_begin <= 420:
+            fp8 = fp8_rows(torch, ramp, synth, tuner, FP8_ROWS.get(args.model, []), min(args.iters, 12), dev, log)
 
     report["summary"] = summary
     report["headline"] = dict(T=T_head, beta=beta_head, us=ms_per_step * 1e3, config=cfg_head.key(), whole_path=whole)
     report["largest_points"] = extra
+    report["fp8_points"] = fp8
     tag = "_fixed_config" if fixed_cfg is not None else ""
     with open(os.path.join(args.out, f"bench_{args.model}{tag}.json"), "w") as f:
         json.dump(report, f)
@@ -562,7 +604,7 @@ def main():
         "config": {"workload": f"{args.model}-shaped MoE layer H={s.H} I={s.I} E={s.E} top-{s.k}, T={T_head}, beta={beta_head}",
                    "tile_config": cfg_head.key(), "weight_copies_rotated": n_layers},
         "roofline": roof, "mfma_ceiling_measured": ceiling, "whole_path": whole, "cpu_baseline": cpu, "cost_model": summary,
-        "largest_points": extra,
+        "largest_points": extra, "fp8_points": fp8,
         "sweep": [dict(T=r["T"], beta=r["beta"], us=round(r["ra_us"], 1), hot_us=round(r["ra_hot_us"], 1), best_us=round(r["best_us"], 1),
                        static_us=round(r["static_us"], 1), bound=r["bound"], roofline_frac=round(r["roofline_frac"], 3),
                        regret=round(r["regret"], 4), bm=r["ra_cfg"][0]) for r in report["points"]],

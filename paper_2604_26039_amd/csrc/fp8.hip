@@ -428,7 +428,7 @@ Fp8Kernel make_fp8()
     X(32, 128, 1, 4, 3)     \
     X(64, 256, 1, 4, 3)     \
     X(128, 256, 2, 2, 3)    \
-    X(256, 256, 2, 2, 2)
+    X(128, 256, 2, 4, 3)
 
 const Fp8Kernel *fp8_kernels(int *n)
 {

@@ -223,8 +223,22 @@ bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s)
     if (2ull * s.I * s.H >= (1ull << 32)) return false;
     // the ping-pong kernel keeps stages-1 slices in flight across tile boundaries: a tile must be at least that long
     if ((c.mode & kModePingPong) && (s.H / c.bk < c.stages || s.I / c.bk < c.stages)) return false;
+
     return true;
 }
+// Pool membership (what ramp_get_config enumerates) on top of "runs on this shape": the region analysis of Sec. 4.1
+// re-derived for this chip.  GROUP_M variants enter the pool of a shape only where their premise holds: an XCD that
+// works on a block of group_m M-tiles x a few N-tiles re-reads the token rows of those M-tiles for every N-block, so
+// they must stay in its 4 MB L2: group_m * bm * H * 2 bytes <= 4 MiB.  Outside the pool a variant still runs when
+// asked for by name (profiling).
+bool config_in_pool(const KernelInfo &ki, const ramp_shape &s)
+{
+    if (!config_valid_for_shape(ki, s)) return false;
+    const int gm = group_m_of_mode(ki.cfg.mode);
+    if (gm > 0 && (size_t)gm * ki.cfg.bm * s.H * 2 > ((size_t)4 << 20)) return false;
+    return true;
+}
+
 int occupancy_estimate(const KernelInfo &ki)
 {
     // Workgroups of this configuration resident on one compute unit, from what the compiler reported for its
@@ -267,7 +281,7 @@ extern "C" int ramp_num_configs(const ramp_shape *shape)
         return RAMP_EINVAL;
     }
     int n = 0;
-    for (int i = 0; i < num_kernels(); ++i) n += config_valid_for_shape(kernel_info(i), *shape) ? 1 : 0;
+    for (int i = 0; i < num_kernels(); ++i) n += config_in_pool(kernel_info(i), *shape) ? 1 : 0;
     return n;
 }
 
@@ -279,7 +293,7 @@ extern "C" int ramp_get_config(const ramp_shape *shape, int idx, ramp_config *ou
     }
     int n = 0;
     for (int i = 0; i < num_kernels(); ++i) {
-        if (!config_valid_for_shape(kernel_info(i), *shape)) continue;
+        if (!config_in_pool(kernel_info(i), *shape)) continue;
         if (n++ == idx) {
             *out = kernel_info(i).cfg;
             return RAMP_OK;

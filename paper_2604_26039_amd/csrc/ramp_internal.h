@@ -143,6 +143,7 @@ int num_kernels();
 const KernelInfo &kernel_info(int i);
 const KernelInfo *find_kernel(const ramp_config &cfg);
 bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s);
+bool config_in_pool(const KernelInfo &ki, const ramp_shape &s);
 int occupancy_estimate(const KernelInfo &ki);
 
 // sel != NULL: the launch leaves `out` untouched unless 0 <= *sel < n_cand (device-selected layer).

@@ -32,19 +32,28 @@ class LayerSet:
     timing loop that walks over them reads weights from HBM as a model's layers would, instead
     of re-reading one layer out of the 256 MB last-level cache."""
 
-    def __init__(self, shape: synth.Shape, T_max: int, n_layers: int, seed: int, device="cuda:0", x_std=None):
+    def __init__(self, shape: synth.Shape, T_max: int, n_layers: int, seed: int, device="cuda:0", x_std=None,
+                 fp8: bool = False, bf16: bool = True):
+        """fp8: also keep the W8A8 packed copy of every layer (packed_fp8); bf16=False drops the bf16 packed copies."""
         self.shape, self.T_max, self.device = shape, T_max, device
         self.packed = []
+        self.packed_fp8 = []
         self.X = None
         for l in range(n_layers):
             X, Wg, Wu, Wd = synth.layer_tensors(shape, T_max if l == 0 else 1, seed + 7919 * l, device=device, x_std=x_std)
             if l == 0:
                 self.X = X
             rs = ramp.Shape(T_max, shape.k, shape.E, shape.H, shape.I)
-            buf = torch.empty(ramp.pack_bytes(rs), dtype=torch.uint8, device=device)
-            ramp.pack_weights(rs, Wg, Wu, Wd, buf)
-            torch.cuda.synchronize()
-            self.packed.append(buf)
+            if bf16:
+                buf = torch.empty(ramp.pack_bytes(rs), dtype=torch.uint8, device=device)
+                ramp.pack_weights(rs, Wg, Wu, Wd, buf)
+                torch.cuda.synchronize()
+                self.packed.append(buf)
+            if fp8:
+                buf8 = torch.empty(ramp.fp8_pack_bytes(rs), dtype=torch.uint8, device=device)
+                ramp.fp8_pack_weights(rs, Wg, Wu, Wd, buf8)
+                torch.cuda.synchronize()
+                self.packed_fp8.append(buf8)
             if l == 0:
                 self.raw0 = (Wg, Wu, Wd)  # kept for oracle checks
             else:
@@ -92,13 +101,17 @@ def time_config(layers: LayerSet, cfg: ramp.Config, pt: Point, warmup: int = 10,
     dev = layers.device
     d_ids = torch.from_numpy(pt.ids).to(dev)
     d_w = torch.from_numpy(pt.w).to(dev)
-    ws = layers.workspace(ramp.fused_moe_workspace_bytes(rs, cfg))
+    is_fp8 = bool(cfg.mode & ramp.FP8_MODE)
+    ws = layers.workspace(ramp.fused_moe_fp8_workspace_bytes(rs, cfg) if is_fp8 else ramp.fused_moe_workspace_bytes(rs, cfg))
     X = layers.X[:T]
     out = layers.out[:T]
     L = 1 if hot else layers.n_layers
 
     def call(i):
-        ramp.fused_moe(rs, cfg, X, d_ids, d_w, layers.packed[i % L], out, ws)
+        if is_fp8:
+            ramp.fused_moe_fp8(rs, cfg, X, d_ids, d_w, layers.packed_fp8[i % L], out, ws)
+        else:
+            ramp.fused_moe(rs, cfg, X, d_ids, d_w, layers.packed[i % L], out, ws)
 
     # one probing call decides how many iterations the budget allows
     call(0)
@@ -137,11 +150,13 @@ class Family:
     wave_cap: np.ndarray
 
     @staticmethod
-    def of(s: synth.Shape, T: int = 1) -> "Family":
+    def of(s: synth.Shape, T: int = 1, fp8: bool = False) -> "Family":
+        """The bf16 tile family of the shape, or (fp8=True) the W8A8 FP8 one."""
         rs = ramp.Shape(T, s.k, s.E, s.H, s.I)
-        cfgs = ramp.configs(rs)
+        cfgs = ramp.fp8_configs(rs) if fp8 else ramp.configs(rs)
+        cap = ramp.fp8_config_wave_capacity if fp8 else ramp.config_wave_capacity
         return Family(rs, cfgs, np.array([ramp.config_ntiles(rs, c) for c in cfgs], np.int32),
-                      np.array([ramp.config_wave_capacity(c) for c in cfgs], np.int32))
+                      np.array([cap(c) for c in cfgs], np.int32))
 
     def grid(self, counts: np.ndarray) -> np.ndarray:
         """Eq. 1 for every configuration (computed by the library)."""
@@ -339,11 +354,12 @@ def entropy_beta(counts) -> float:
 
 
 def roofline_lower_bound_us(s: synth.Shape, T: int, counts: np.ndarray, hbm_tbs: float = 8.0,
-                            mfma_pflops: float = 2.5):
+                            mfma_pflops: float = 2.5, weight_bytes: int = 2):
     """Algorithmic minimum time: weights of the active experts once + activations in/out + routing,
-    against HBM peak; 6*P*H*I flops against dense bf16 MFMA peak.  Returns (t_hbm, t_mfma, bytes, flops)."""
+    against HBM peak; 6*P*H*I flops against the dense MFMA peak of the operand type (bf16 2.5, FP8 5.0 PFLOP/s;
+    weight_bytes 2 or 1).  Returns (t_hbm, t_mfma, bytes, flops)."""
     e_act = int((np.asarray(counts) > 0).sum())
     P = int(np.asarray(counts).sum())
-    nbytes = e_act * 3 * s.H * s.I * 2 + 2 * T * s.H * 2 + P * 8
+    nbytes = e_act * 3 * s.H * s.I * weight_bytes + 2 * T * s.H * 2 + P * 8
     flops = 6.0 * P * s.H * s.I
     return nbytes / (hbm_tbs * 1e12) * 1e6, flops / (mfma_pflops * 1e15) * 1e6, nbytes, flops

@@ -47,6 +47,27 @@ def test_config_family(name):
         assert ramp.fused_moe_workspace_bytes(sh, c) > 0
 
 
+@pytest.mark.parametrize("name", ["tiny", "olmoe", "qwen3", "mixtral", "dsv3"])
+def test_fp8_config_family(name):
+    """The W8A8 FP8 family (Sec. 4.3) is enumerated apart from the bf16 one and sized by the same queries."""
+    sh = shape_of(name, 64)
+    cfgs = ramp.fp8_configs(sh)
+    assert len(cfgs) >= 4 and len({c.key() for c in cfgs}) == len(cfgs)
+    assert not any(c.mode & ramp.FP8_MODE for c in ramp.configs(sh))
+    for c in cfgs:
+        assert c.mode & ramp.FP8_MODE and c.bk == 128
+        assert (2 * sh.I) % c.bn == 0 and sh.H % c.bn == 0
+        assert ramp.config_ntiles(sh, c) == 2 * sh.I // c.bn + sh.H // c.bn
+        W = ramp.fp8_config_wave_capacity(c)
+        assert W >= 256 and W % 256 == 0
+        assert ramp.fused_moe_fp8_workspace_bytes(sh, c) > ramp.fused_moe_workspace_bytes(sh, ramp.configs(sh)[0]) // 8
+    assert ramp.fp8_pack_bytes(sh) > 3 * sh.E * sh.H * sh.I
+    off, strides = ramp.fp8_pack_layout(sh)
+    assert off[0] == 2 * sh.I * sh.H and off[1] == sh.I * sh.H and strides[0] % 4 == 0 and strides[0] >= sh.H // 128
+    with pytest.raises(ramp.RampError):
+        ramp.fp8_config_wave_capacity(ramp.configs(sh)[0])
+
+
 def test_unknown_config_is_rejected():
     bad = ramp.Config(24, 64, 128, 2, 2, 0)  # bm=24 is not in the family
     with pytest.raises(ramp.RampError) as ei:
