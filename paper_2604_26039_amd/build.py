@@ -29,7 +29,7 @@ KERNEL_SOURCES = ["gemm_group0.hip", "gemm_group1.hip", "gemm_group2.hip", "gemm
                   "gemm_group5.hip", "gemm_group6.hip", "gemm_group7.hip", "stream_group0.hip", "stream_group1.hip",
                   "stream_group2.hip"]
 SOURCES = ["align.hip", "select.hip", "pack.hip", "fused.hip", "fp8.hip"] + KERNEL_SOURCES + ["cost_model.cpp"]
-HEADERS = ["ramp_internal.h", "moe_gemm.h", "moe_pingpong.h", "moe_stream.h", "config_list.h", os.path.join(ROOT, "include", "ramp.h")]
+HEADERS = ["ramp_internal.h", "moe_gemm.h", "moe_pingpong.h", "moe_stream.h", "moe_decode.h", "align_tiny.h", "config_list.h", os.path.join(ROOT, "include", "ramp.h")]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-ffp-contract=off"]
 # packed fp32 ops are disabled on purpose: some of their forms have produced wrong results on this hardware

@@ -13,6 +13,7 @@
 // histograms, then a kernel in which every workgroup scans them and scatters
 // its chunk); the histogram-only entry point ends with a small scan kernel.
 #include "ramp_internal.h"
+#include "align_tiny.h"
 
 namespace ramp {
 namespace {
@@ -216,78 +217,9 @@ __global__ __launch_bounds__(kWave) void align_tiny_kernel(const int32_t *ids, i
     if (launch_deselected(pred, pred_value)) return;
     __shared__ int n_lds[kAlignMaxE];
     __shared__ int toff[kAlignMaxE + 1];
-    const int lane = threadIdx.x;
-    for (int x = lane; x < E; x += kWave) n_lds[x] = 0;
-    for (int s = lane; s < cap; s += kWave) sorted[s] = P;
-    int e = -1;
-    if (lane < P) {
-        const int v = ids[lane];
-        if (v >= 0 && v < E) e = v;
-    }
-    const int dropped = __popcll(__ballot(lane < P && e < 0));
-    // lanes with the same expert: one ballot per bit of the expert index
-    const int ebits = 32 - __clz((E - 1) | 1);
-    unsigned long long same = __ballot(e >= 0);
-#pragma unroll
-    for (int b = 0; b < 10; ++b) {
-        if (b < ebits) {
-            const bool bit = (e >> b) & 1;
-            const unsigned long long m = __ballot(e >= 0 && bit);
-            same &= bit ? m : ~m;
-        }
-    }
-    const int rank = __popcll(same & ((1ull << lane) - 1ull));
-    __syncthreads();
-    if (e >= 0 && rank == 0) n_lds[e] = __popcll(same);
-    __syncthreads();
-    // exclusive scan of the padded slot counts: lane l owns experts [l*per, (l+1)*per)
-    const int per = (E + kWave - 1) / kWave;
-    int local = 0;
-    for (int i = 0; i < per; ++i) {
-        const int x = lane * per + i;
-        if (x < E) local += (n_lds[x] + bm - 1) / bm * bm;
-    }
-    int incl = local;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int up = __shfl_up(incl, d, kWave);
-        if (lane >= d) incl += up;
-    }
-    const int p_pad = __shfl(incl, kWave - 1, kWave);
-    int run = incl - local;
-    for (int i = 0; i < per; ++i) {
-        const int x = lane * per + i;
-        if (x < E) {
-            toff[x] = run;
-            run += (n_lds[x] + bm - 1) / bm * bm;
-        }
-    }
-    if (lane == 0) {
-        toff[E] = p_pad;
-        meta[0] = p_pad;
-        meta[1] = p_pad / bm;
-        meta[2] = dropped;
-        meta[3] = 0;
-    }
-    __syncthreads();
-    for (int x = lane; x < E; x += kWave) counts[x] = n_lds[x];
-    const int m_tiles = p_pad / bm, m_cap = cap / bm;
-    for (int m = lane; m < m_cap; m += kWave) {
-        int owner = -1, rows = 0;
-        if (m < m_tiles) {
-            int target = m * bm, lo = 0, hi = E - 1;  // first expert with toff[e+1] > m*bm (empty experts are skipped)
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (toff[mid + 1] > target) hi = mid; else lo = mid + 1;
-            }
-            owner = lo;
-            rows = n_lds[owner] - (target - toff[owner]);
-            rows = rows > bm ? bm : rows;
-        }
-        tile_expert[m] = owner;
-        if (tile_rows) tile_rows[m] = rows;
-    }
-    if (e >= 0) sorted[toff[e] + rank] = lane;  // after the sentinel fill of the same wavefront
+    int e, rank;
+    tiny_align_wavefront(ids, P, E, bm, (int)threadIdx.x, n_lds, toff, e, rank);
+    tiny_align_emit(P, E, bm, cap, (int)threadIdx.x, n_lds, toff, e, rank, ids, sorted, tile_expert, tile_rows, counts, meta);
 }
 
 // ---- several workgroups: histogram per chunk -> scan -> scatter ----

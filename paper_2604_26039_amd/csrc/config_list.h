@@ -90,3 +90,14 @@
 #define RAMP_STREAM_GROUP2(X) \
     X(16, 2, 2, 4, 4)         \
     X(16, 2, 2, 2, 4)
+
+// Stream configurations that also have the two-launch form for calls of at most 64 pairs (moe_decode.h):
+// X(bm, FBW, WF, WK, U) as above; listed as separate configurations (mode bit 0x2000).
+#define RAMP_DECODE_GROUP(X) \
+    X(8, 2, 1, 8, 2)         \
+    X(16, 2, 1, 8, 2)        \
+    X(16, 2, 2, 4, 2)        \
+    X(32, 2, 1, 8, 2)        \
+    X(32, 2, 2, 4, 2)        \
+    X(16, 2, 2, 4, 4)        \
+    X(16, 2, 1, 8, 4)

@@ -49,11 +49,12 @@ void init_registry()
 template <bool Y16>
 __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ Y, const int32_t *__restrict__ ids, int T,
                                                       int k, int E, int H, uint16_t *__restrict__ out,
-                                                      const int32_t *__restrict__ sel, int n_cand)
+                                                      const int32_t *__restrict__ sel, int n_cand, unsigned skip_mask)
 {
     if (sel != nullptr) {
         const int idx = *sel;
         if (idx < 0 || idx >= n_cand) return;
+        if ((skip_mask >> idx) & 1u) return;  // the selected candidate's own launches wrote `out`
     }
     const int hv = H / 8;  // 8-feature columns: one 16-byte bf16 load (or two fp32 ones) per pair row
     const size_t total = (size_t)T * hv;
@@ -257,16 +258,16 @@ int occupancy_estimate(const KernelInfo &ki)
 }
 
 int launch_combine(const float *Y, int y_bf16, const int32_t *ids, int T, int k, int E, int H, uint16_t *out,
-                   hipStream_t stream, const int32_t *sel, int n_cand)
+                   hipStream_t stream, const int32_t *sel, int n_cand, unsigned skip_mask)
 {
     if (T == 0) return RAMP_OK;
     size_t total = (size_t)T * (H / 8);
     unsigned grid = (unsigned)((total + 255) / 256);
     if (grid > (unsigned)kNumCU * 16) grid = kNumCU * 16;
     if (y_bf16)
-        hipLaunchKernelGGL(combine_kernel<true>, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out, sel, n_cand);
+        hipLaunchKernelGGL(combine_kernel<true>, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out, sel, n_cand, skip_mask);
     else
-        hipLaunchKernelGGL(combine_kernel<false>, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out, sel, n_cand);
+        hipLaunchKernelGGL(combine_kernel<false>, dim3(grid), dim3(256), 0, stream, Y, ids, T, k, E, H, out, sel, n_cand, skip_mask);
     return check_launch("combine_kernel");
 }
 
@@ -426,16 +427,54 @@ bool pair_rows_bf16(const ramp_shape &s)
 
 // align(bm) + both projections of one configuration; `base` holds every workspace section but the per-pair rows,
 // which go to y_buf.  With pred != NULL every launch is a no-op unless *pred == pred_value on the device.
+// *wrote_out is set when the configuration's launches wrote `out` themselves (two-launch decode form): no combine then.
 int enqueue_projections(const ramp_shape &s, const ramp_config &cfg, const KernelInfo &ki, const Workspace &w, const void *X,
                         const int32_t *topk_ids, const float *topk_w, const void *packed_weights, char *base,
-                        float *y_buf, const int32_t *pred, int pred_value, hipStream_t st)
+                        float *y_buf, void *out, const int32_t *pred, int pred_value, hipStream_t st, bool *wrote_out)
 {
+    *wrote_out = false;
     int32_t *sorted = reinterpret_cast<int32_t *>(base + w.sorted);
     int32_t *tile_expert = reinterpret_cast<int32_t *>(base + w.tile_expert);
     int32_t *tile_rows = reinterpret_cast<int32_t *>(base + w.tile_rows);
     int32_t *counts = reinterpret_cast<int32_t *>(base + w.counts);
     int32_t *meta = reinterpret_cast<int32_t *>(base + w.meta);
     uint16_t *a_buf = reinterpret_cast<uint16_t *>(base + w.a_buf);
+
+    const PackedLayout L = packed_layout(s);
+    const uint16_t *packed = static_cast<const uint16_t *>(packed_weights);
+    const int P = s.T * s.k;
+    if (ki.launch_decode_up && P <= kDecodeMaxPairs && 16 % s.k == 0) {
+        // decode-sized call: align + up-projection + SwiGLU in one launch, down-projection + top-k sum in the other
+        GemmArgs g = {};
+        g.act = static_cast<const uint16_t *>(X);
+        g.wpacked = packed;
+        g.expert_stride = L.w1_expert_elems;
+        g.up_offset = L.up_offset_elems;
+        g.a_out = a_buf;
+        g.a_row_major = 1;
+        g.K = s.H;
+        g.F = s.I;
+        g.P = P;
+        g.topk = s.k;
+        g.n_tiles = 2 * s.I / cfg.bn;
+        g.m_tiles_cap = (int)(w.cap / (size_t)cfg.bm);
+        g.pred = pred;
+        g.pred_value = pred_value;
+        DecodeArgs da = {topk_ids, s.E, cfg.bm, (int)w.cap, sorted, tile_expert, tile_rows, counts, meta};
+        {
+            ProbeScope probe(2, st);
+            ki.launch_decode_up(g, da, st);
+        }
+        if (int rc = check_launch("moe_decode_up_kernel")) return rc;
+        DecodeDownArgs dd = {a_buf, packed + L.w2_base_elems, L.w2_expert_elems, topk_ids, topk_w, static_cast<uint16_t *>(out),
+                             s.T, s.k, s.E, s.H, s.I, pred, pred_value};
+        {
+            ProbeScope probe(3, st);
+            launch_decode_down_any(dd, st);
+        }
+        *wrote_out = true;
+        return check_launch("moe_decode_down_kernel");
+    }
 
     int rc;
     {
@@ -445,8 +484,6 @@ int enqueue_projections(const ramp_shape &s, const ramp_config &cfg, const Kerne
     }
     if (rc) return rc;
 
-    const PackedLayout L = packed_layout(s);
-    const uint16_t *packed = static_cast<const uint16_t *>(packed_weights);
     GemmArgs g = {};
     g.sorted = sorted;
     g.tile_expert = tile_expert;
@@ -513,8 +550,11 @@ extern "C" int ramp_fused_moe(const ramp_shape *shape, const ramp_config *cfg, c
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *base = static_cast<char *>(ws);
     float *y_buf = reinterpret_cast<float *>(base + w.y_buf);
-    if (int rc = enqueue_projections(s, *cfg, *ki, w, X, topk_ids, topk_w, packed_weights, base, y_buf, nullptr, 0, st))
+    bool wrote_out = false;
+    if (int rc = enqueue_projections(s, *cfg, *ki, w, X, topk_ids, topk_w, packed_weights, base, y_buf, out, nullptr, 0, st,
+                                     &wrote_out))
         return rc;
+    if (wrote_out) return RAMP_OK;
     ProbeScope probe(4, st);
     return launch_combine(y_buf, pair_rows_bf16(s) ? 1 : 0, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st);
 }
@@ -618,15 +658,18 @@ extern "C" int ramp_fused_moe_selected(const ramp_shape *shape, int n_cand, cons
     float *y_buf = static_cast<float *>(ws);
     char *base = static_cast<char *>(ws) + align_up((size_t)s.T * s.k * s.H * 4, 256);
     // every candidate is enqueued; on the device only the one whose position equals *selected_idx does anything
+    unsigned self_combined = 0;  // candidates whose own launches write `out` (two-launch decode form)
     for (int c = 0; c < n_cand; ++c) {
         const Workspace w = workspace_layout(s, cfgs[c]);
-        if (int rc = enqueue_projections(s, cfgs[c], *ki[c], w, X, topk_ids, topk_w, packed_weights, base, y_buf,
-                                         selected_idx, c, st))
+        bool wrote_out = false;
+        if (int rc = enqueue_projections(s, cfgs[c], *ki[c], w, X, topk_ids, topk_w, packed_weights, base, y_buf, out,
+                                         selected_idx, c, st, &wrote_out))
             return rc;
+        if (wrote_out) self_combined |= 1u << c;
     }
     ProbeScope probe(4, st);
     return launch_combine(y_buf, pair_rows_bf16(s) ? 1 : 0, topk_ids, s.T, s.k, s.E, s.H, static_cast<uint16_t *>(out), st,
-                          selected_idx, n_cand);
+                          selected_idx, n_cand, self_combined);
 }
 
 extern "C" int ramp_probe_enable(int stage)

@@ -470,7 +470,7 @@ template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int LOOP>
 KernelInfo make_info()
 {
     using TT = TileTraits<BM, BN, BK, WM, WN, NSTAGE>;
-    KernelInfo ki;
+    KernelInfo ki = {};
     ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | (LOOP == 1 ? kModePipe : 0)};
     ki.wm = WM;
     ki.wn = WN;

@@ -459,7 +459,7 @@ KernelInfo make_pingpong_info(int group_bits = 0)
     using TT = TileTraits<BM, BN, BK, WM, WN, 2>;  // tile geometry only; the ring depths are defined here
     constexpr int l1 = PingPongTraits<1, BM, BN, BK, WM, WN, NSTAGE>::LDS_BYTES;
     constexpr int l2 = PingPongTraits<2, BM, BN, BK, WM, WN, (NSTAGE > 4 ? 4 : NSTAGE)>::LDS_BYTES;
-    KernelInfo ki;
+    KernelInfo ki = {};
     ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | kModePingPong | (group_bits << kModeGroupShift)};
     ki.wm = WM;
     ki.wn = WN;

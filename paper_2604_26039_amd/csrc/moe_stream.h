@@ -190,7 +190,7 @@ template <int BM, int FBW, int WF, int WK, int U>
 KernelInfo make_stream_info()
 {
     using ST = StreamTraits<BM, FBW, WF, WK, U>;
-    KernelInfo ki;
+    KernelInfo ki = {};
     ki.cfg = ramp_config{BM, ST::BN, U * 32, WF * WK, 2, kModeStream | WK};
     ki.wm = 1;
     ki.wn = WF;

@@ -112,17 +112,22 @@ constexpr int kModePingPong = 0x400;  // persistent ping-pong kernel (moe_pingpo
 // GROUP_M (Sec. 4.1, Eq. 4), XCD-aware: bits 12-15 = v > 0 makes every XCD take blocks of 2^v M-tiles x (32 >> v)
 // N-tiles, so that the M-tiles of a block share the weight slices of its few N-tiles in that XCD's L2; 0 = a block
 // spans all N-tiles (the token rows of its M-tiles stay in L2 instead).
+constexpr int kModeDecode = 0x2000;   // with kModeStream: calls of at most 64 pairs run the two-launch form (moe_decode.h)
 constexpr int kModeFp8 = 0x10000;     // W8A8 FP8 family (fp8.hip), listed by ramp_fp8_get_config
 constexpr int kModeGroupShift = 12;
 constexpr int kModeGroupMask = 0xF << kModeGroupShift;
 inline int group_m_of_mode(int mode) { const int v = (mode & kModeGroupMask) >> kModeGroupShift; return v ? (1 << v) : 0; }
 
+struct DecodeArgs;
+struct DecodeDownArgs;
 struct KernelInfo {
     ramp_config cfg;
     int wm, wn;                 // wavefront grid inside the workgroup (tokens x features)
     int lds_bytes;
     int acc_regs;               // fp32 accumulators per lane (stage 1, the larger one)
     void (*launch)(int stage, const GemmArgs &, hipStream_t);
+    // decode-sized calls (kModeDecode): align + up-projection in one launch; NULL for every other configuration
+    void (*launch_decode_up)(const GemmArgs &, const DecodeArgs &, hipStream_t);
     const void *kernel_fn[2];   // the two projection kernels (stage 1, stage 2), for occupancy queries
     int block_threads;
     const char *family;         // kernel template name and the template arguments of the stage-1 instantiation:
@@ -146,13 +151,34 @@ bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s);
 bool config_in_pool(const KernelInfo &ki, const ramp_shape &s);
 int occupancy_estimate(const KernelInfo &ki);
 
-// sel != NULL: the launch leaves `out` untouched unless 0 <= *sel < n_cand (device-selected layer).
+// sel != NULL: the launch leaves `out` untouched unless 0 <= *sel < n_cand (device-selected layer) and bit *sel of
+// skip_mask is clear (a candidate whose own launches write `out`).
+// Two-launch form for decode-sized calls (moe_decode.h, instantiated in stream_group2.hip)
+struct DecodeArgs {
+    const int32_t *ids;      // [T*k]
+    int E, bm, cap;
+    int32_t *sorted, *tile_expert, *tile_rows, *counts, *meta;  // align result, written by workgroup 0
+};
+struct DecodeDownArgs {
+    const uint16_t *act;       // A [P, I] bf16, row-major, one row per pair
+    const uint16_t *wpacked;   // packed down-projection weights
+    size_t expert_stride;      // elements between experts
+    const int32_t *ids;        // [T, k]
+    const float *topk_w;       // [T, k]
+    uint16_t *out;             // [T, H] bf16
+    int T, k, E, H, I;
+    const int32_t *pred;
+    int pred_value;
+};
+constexpr int kDecodeMaxPairs = 64;
+void launch_decode_down_any(const DecodeDownArgs &d, hipStream_t stream);
+
 // shape limits shared by the fused entry points (fused.hip)
 bool moe_shape_ok(const ramp_shape &s);
 bool moe_pair_rows_bf16(const ramp_shape &s);      // per-pair rows kept in bf16 (large batches) instead of fp32
 unsigned long long moe_topk_magic(int k);
 
 int launch_combine(const float *Y, int y_bf16, const int32_t *ids, int T, int k, int E, int H, uint16_t *out,
-                   hipStream_t stream, const int32_t *sel = nullptr, int n_cand = 0);
+                   hipStream_t stream, const int32_t *sel = nullptr, int n_cand = 0, unsigned skip_mask = 0);
 
 }  // namespace ramp
