@@ -33,21 +33,27 @@ namespace ramp {
 
 template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
 struct PingPongTraits {
-    using TT = TileTraits<BM, BN, BK, WM, WN, 2>;  // tile geometry only; the ring depths are defined here
+    // A tile of bm = (NB*WM + 1)*16 rows has one tail block beyond the blocks dealt to the wavefront rows; all
+    // wavefronts share it, each multiplying it with part of its weight fragments.
+    static constexpr int TAILB = (BM / 16) % WM;
+    static constexpr int BMAIN = BM - 16 * TAILB;
+    using TT = TileTraits<BMAIN, BN, BK, WM, WN, 2>;  // tile geometry only; the ring depths are defined here
     static constexpr bool ROWX = (STAGE == 1);           // gathered rows, 128-byte pieces
     static constexpr int XK = ROWX ? 64 : BK;            // k-values of one token load batch ("super-slice")
     static constexpr int XS = XK / BK;                   // k-slices fed by one super-slice
     static constexpr int NX = (XS == 2) ? 2 : NSTAGE;    // token ring depth in super-slices
-    static constexpr int X_BYTES = BM * XK * 2;
+    static constexpr int X_BLOCKS = BM * XK * 2 / 1024;                           // 1 KB token load blocks per super-slice
+    static constexpr int TSLOTS = (X_BLOCKS + TT::NWAVE - 1) / TT::NWAVE;         // token load instructions per wavefront per super-slice
+    static constexpr int X_BYTES = TSLOTS * TT::NWAVE * 1024;                     // (the surplus slots of a tail tile load nothing)
     static constexpr int W_BYTES = TT::W_FRAGS * kFragElems * 2;
-    static constexpr int TSLOTS = X_BYTES / 1024 / TT::NWAVE;  // token load instructions per wavefront per super-slice
     static constexpr int WSLOTS = TT::W_FRAGS / TT::NWAVE;     // weight load instructions per wavefront per slice
     static constexpr int RING_BYTES = NX * X_BYTES + NSTAGE * W_BYTES;
     static constexpr int STG_BYTES = (STAGE == 2) ? 4096 * TT::NWAVE : 0;  // per-wavefront staging of bf16 output rows
     static constexpr int LDS_BYTES = RING_BYTES + STG_BYTES;
     static_assert(TT::NWAVE == 8, "ping-pong needs two groups of four wavefronts");
     static_assert(BK == 32 || BK == 64, "bk 32 or 64");
-    static_assert(BM % 16 == 0 && (X_BYTES / 1024) % TT::NWAVE == 0, "token loads must split evenly");
+    static_assert(BM % 16 == 0 && TAILB <= 1, "whole token blocks, at most one tail block");
+    static_assert(TAILB == 0 || (BK == 32 && WM == 2 && (STAGE == 1 ? TT::FB1 == 2 : TT::FB2 == 4)), "tail block: 256-wide tiles of two wavefront rows");
     static_assert(TT::W_FRAGS % TT::NWAVE == 0, "weight loads must split evenly");
     static_assert(NSTAGE >= 3 || XS == 1, "a two-slice token batch needs three weight stages");
     static_assert(LDS_BYTES <= kLdsBytesPerCU, "tile does not fit in LDS");
@@ -80,8 +86,9 @@ __device__ __forceinline__ void wait_vmcnt_upto(int n)
 template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
 __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
 {
-    using TT = TileTraits<BM, BN, BK, WM, WN, 2>;  // tile geometry only; the ring depths are defined here
     using PT = PingPongTraits<STAGE, BM, BN, BK, WM, WN, NSTAGE>;
+    using TT = typename PT::TT;
+    constexpr int TAILB = PT::TAILB, BMAIN = PT::BMAIN;
     constexpr int KS = TT::KS, NB = TT::NB, NWAVE = TT::NWAVE;
     constexpr int FB = (STAGE == 1) ? TT::FB1 : TT::FB2;
     constexpr int NACC = (STAGE == 1) ? 2 * FB : FB;
@@ -104,7 +111,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
 
     // Tiles of this workgroup: ids blockIdx.x, + gridDim.x, ... (gridDim.x is a multiple of 8, so every tile of a
     // workgroup maps to its own XCD); ids past the real M-tiles of this call are skipped.
-    auto next_tile = [&](int id, int &n_tile, int &m_tile) -> int {
+    auto next_tile = [&](int id, int &n_tile, int &m_tile) __attribute__((always_inline)) -> int {
         for (; id < a.total_tiles; id += (int)gridDim.x) {
             tile_of_id(a, id, n_tile, m_tile);
             if (m_tile < m_tiles) return id;
@@ -113,7 +120,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     };
 
     // ---- global element offsets of this lane's loads for k-slice 0 of a tile ----
-    auto tile_offsets = [&](int n_tile, int m_tile, uint32_t *xo, uint32_t *wo, const uint16_t *&wexp, int &rows) {
+    auto tile_offsets = [&](int n_tile, int m_tile, uint32_t *xo, uint32_t *wo, const uint16_t *&wexp, int &rows) __attribute__((always_inline)) {
         rows = a.tile_rows[m_tile];  // real rows of the tile (they come first, the sentinel padding after them)
         const int e = a.tile_expert[m_tile];
         wexp = a.wpacked + (size_t)e * a.expert_stride;
@@ -122,7 +129,11 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             // all index loads first, then the arithmetic (token = pair / k by multiplication)
             int pair[TSLOTS];
 #pragma unroll
-            for (int t = 0; t < TSLOTS; ++t) pair[t] = a.sorted[m_tile * BM + (wave + t * NWAVE) * 8 + (lane >> 3)];
+            for (int t = 0; t < TSLOTS; ++t) {
+                const int tr = (wave + t * NWAVE) * 8 + (lane >> 3);
+                // (the surplus load slots of a tail tile never fetch rows, see token_loads: any slot of the tile will do)
+                pair[t] = a.sorted[m_tile * BM + (PT::X_BLOCKS % NWAVE == 0 || tr < BM ? tr : BM - 1)];
+            }
 #pragma unroll
             for (int t = 0; t < TSLOTS; ++t) {
                 const int tr = (wave + t * NWAVE) * 8 + (lane >> 3);  // 8 rows per 1 KB block, 8 lanes (128 B) per row
@@ -164,13 +175,13 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     // Token loads of all-padding row blocks are degenerate (a ragged last tile of an expert then costs little more
     // than its weights): only the first txv of this wavefront's TSLOTS token loads per batch fetch rows.
     int txv = TSLOTS, txv_n = TSLOTS;
-    auto token_loads = [&](int rows) {
+    auto token_loads = [&](int rows) __attribute__((always_inline)) {
         const int blocks = PT::ROWX ? (rows + 7) / 8 : (rows + 15) / 16 * KS;  // 1 KB load blocks that hold real rows
         int v = (blocks - wave + NWAVE - 1) / NWAVE;
         return v < 0 ? 0 : (v > TSLOTS ? TSLOTS : v);
     };
 
-    auto issue_x = [&](int xbuf) {
+    auto issue_x = [&](int xbuf) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < TSLOTS; ++t) {
             // a block of nothing but padding rows re-reads one 16-byte piece instead (one cache line request, and
@@ -180,7 +191,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             xoff[t] += XSTEP;
         }
     };
-    auto issue_w = [&](int wbuf) {
+    auto issue_w = [&](int wbuf) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < WSLOTS; ++s) {
             load_to_lds_16B(wexp_w + woff[s], lds_w + wbuf * PT::W_BYTES + (wave + s * NWAVE) * 1024);
@@ -189,21 +200,27 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     };
 
     floatx4 acc[NACC][NB];
-    auto zero_acc = [&]() {
+    // tail block (TAILB): wavefront row wm multiplies it with two of its weight fragments: (gate, up) of feature
+    // block wm in the up-projection, feature blocks 2*wm and 2*wm + 1 in the down-projection
+    floatx4 acc_t[2];
+    bool tail_valid = false;  // the current tile has real rows in its tail block
+    auto zero_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NACC; ++i)
 #pragma unroll
             for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (TAILB) acc_t[0] = acc_t[1] = floatx4{0.f, 0.f, 0.f, 0.f};
     };
 
     // ---- LDS read offsets of this lane's operand fragments ----
     // tokens, row-major batch: row (wm*NB+nb)*16 + r16 sits in block row/8 at (row%8)*128, chunk c at (c ^ (row/2)%8)*16
     const int xrow_off = wm * 2048 + (r16 >> 3) * 1024 + (r16 & 7) * 128;  // token block nb of this wavefront is block nb*WM + wm
     const int xsw = (r16 >> 1) & 7;
-    bf16x8 fx[KS][NB], fw[KS][NACC];
+    const int xtail_off = NB * WM * 2048 + (r16 >> 3) * 1024 + (r16 & 7) * 128;
+    bf16x8 fx[KS][NB], fw[KS][NACC], fx_t[KS];
     int nb_valid = 0;  // token blocks of this wavefront with at least one real row in the current tile
     // kk0: 32-wide k-step of the slice inside its token batch; partial_c: skip the token fragments of all-padding blocks
-    auto read_all = [&](int kk0, int xbuf, int wbuf, auto partial_c) {
+    auto read_all = [&](int kk0, int xbuf, int wbuf, auto partial_c) __attribute__((always_inline)) {
         constexpr bool PARTIAL = decltype(partial_c)::value;
         const char *xs = lds_x + xbuf * PT::X_BYTES;
         const char *ws = lds_w + wbuf * PT::W_BYTES + lane * 16;
@@ -223,18 +240,20 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
                 for (int nb = 0; nb < NB; ++nb)
                     if (!PARTIAL || nb < nb_valid)
                         fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + xrow_off + nb * (WM * 2048) + coff);
+                if (TAILB) fx_t[ks] = *reinterpret_cast<const bf16x8 *>(xs + xtail_off + coff);
             } else {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
                     if (!PARTIAL || nb < nb_valid)
                         fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + ((nb * WM + wm) * KS + ks) * 1024 + lane * 16);
+                if (TAILB) fx_t[ks] = *reinterpret_cast<const bf16x8 *>(xs + (NB * WM * KS + ks) * 1024 + lane * 16);
             }
         }
     };
     // FULL: every token block of the wavefront is real (no branches between the MFMAs); otherwise the products of
     // all-padding blocks are skipped.  The operand reads stay unconditional: branches between them cost more than
     // the reads they save.
-    auto mfma_all = [&](auto mode_c) {
+    auto mfma_all = [&](auto mode_c) __attribute__((always_inline)) {
         constexpr bool FULL = decltype(mode_c)::value == 1;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
@@ -246,13 +265,26 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
                         acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][i], fx[ks][nb], acc[i][nb], 0, 0, 0);
                 }
             }
+        if (TAILB && tail_valid) {
+            constexpr int I0 = (STAGE == 1) ? 0 : 0, I1 = (STAGE == 1) ? FB : 1, STEP = (STAGE == 1) ? 1 : 2;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (wm == 0) {
+                    acc_t[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I0], fx_t[ks], acc_t[0], 0, 0, 0);
+                    acc_t[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I1], fx_t[ks], acc_t[1], 0, 0, 0);
+                } else {
+                    acc_t[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I0 + STEP], fx_t[ks], acc_t[0], 0, 0, 0);
+                    acc_t[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I1 + STEP], fx_t[ks], acc_t[1], 0, 0, 0);
+                }
+            }
+        }
     };
-    auto phase_barrier = [&]() {
+    auto phase_barrier = [&]() __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto blocks_valid = [&](int rows) {  // token blocks of this wavefront (wm, wm + WM, ...) with at least one real row
+    auto blocks_valid = [&](int rows) __attribute__((always_inline)) {  // token blocks of this wavefront (wm, wm + WM, ...) with at least one real row
         const int v = ((rows + 15) / 16 - wm + WM - 1) / WM;
         return v < 0 ? 0 : (v > NB ? NB : v);
     };
@@ -263,6 +295,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     int rows_cur = 0, rows_next = 0;
     tile_offsets(n_tile, m_tile, xoff, woff, wexp_w, rows_cur);
     nb_valid = blocks_valid(rows_cur);
+    tail_valid = TAILB && rows_cur > BMAIN;
     txv = token_loads(rows_cur);
     zero_acc();
 
@@ -303,11 +336,17 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
                 out_wgt[nb] = (out_pair[nb] < a.P) ? a.topk_w[out_pair[nb]] : 0.0f;
             }
         }
+        int tail_pair = a.P;
+        float tail_wgt = 0.0f;
+        if (STAGE == 2 && TAILB && tail_valid) {
+            tail_pair = a.sorted[m_tile * BM + BMAIN + r16];
+            tail_wgt = (tail_pair < a.P) ? a.topk_w[tail_pair] : 0.0f;
+        }
 
         // mode_c: 1 = every token block of the wavefront is real, 0 = some are, 2 = none (a ragged tile that ends
         // in the other wavefront row): such a wavefront issues its loads and keeps the barriers but neither reads
         // operands nor multiplies, which leaves the LDS bandwidth of the tile to the wavefronts that do
-        auto slice = [&](int kt, auto steady_c, auto mode_c) {
+        auto slice = [&](int kt, auto steady_c, auto mode_c) __attribute__((always_inline)) {
             constexpr bool STEADY = decltype(steady_c)::value;
             constexpr int MODE = decltype(mode_c)::value;
             // ---- M phase: both groups have read slice kt-1 (its buffers are free).  Operand reads first, then the
@@ -426,15 +465,30 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             }
         }
         }
+        if (TAILB && tail_valid) {
+            if (STAGE == 1)
+                store_token_row<1, 1>(a, &acc_t[0], &acc_t[1], 1, (size_t)(m_tile * BM + BMAIN + r16), f0 / 16 + wn * FB + wm, q, 1.0f);
+            else if (tail_pair < a.P)
+                store_token_row<2, 2>(a, &acc_t[0], &acc_t[0], 1, (size_t)tail_pair * a.F, f0 / 16 + wn * FB + 2 * wm, q, tail_wgt);
+        }
         if (!has_next) break;
         id = id_next;
         n_tile = n_next;
         m_tile = m_next;
         rows_cur = rows_next;
         nb_valid = blocks_valid(rows_cur);
+        tail_valid = TAILB && rows_cur > BMAIN;
         zero_acc();
     }
     if (group == 0) phase_barrier();  // both groups execute the same number of barriers
+}
+
+// LDS stages of the down-projection, which stages tokens and weights per slice and keeps 32 KB for its output rows:
+// at most 4, and 3 for a tile with a tail block (its token buffers are padded to whole load rounds).
+template <int BM, int WM, int NSTAGE>
+constexpr int pingpong_down_stages()
+{
+    return ((BM / 16) % WM) ? 3 : (NSTAGE > 4 ? 4 : NSTAGE);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int NSTAGE>
@@ -446,7 +500,7 @@ void launch_pingpong(int stage, const GemmArgs &a, hipStream_t stream)
     // persistent: one workgroup per compute unit walks its share of the tiles (the count is a multiple of 8)
     const dim3 grid(g.total_tiles < kNumCU ? g.total_tiles : kNumCU), block(512);
     // the down-projection stages tokens and weights per slice and needs LDS for its output rows: at most 4 stages
-    constexpr int NS2 = NSTAGE > 4 ? 4 : NSTAGE;
+    constexpr int NS2 = pingpong_down_stages<BM, WM, NSTAGE>();
     if (stage == 1)
         hipLaunchKernelGGL((moe_pingpong_kernel<1, BM, BN, BK, WM, WN, NSTAGE>), grid, block, 0, stream, g);
     else
@@ -456,18 +510,18 @@ void launch_pingpong(int stage, const GemmArgs &a, hipStream_t stream)
 template <int BM, int BN, int BK, int WM, int WN, int NSTAGE>
 KernelInfo make_pingpong_info(int group_bits = 0)
 {
-    using TT = TileTraits<BM, BN, BK, WM, WN, 2>;  // tile geometry only; the ring depths are defined here
+    using TT = typename PingPongTraits<1, BM, BN, BK, WM, WN, NSTAGE>::TT;
     constexpr int l1 = PingPongTraits<1, BM, BN, BK, WM, WN, NSTAGE>::LDS_BYTES;
-    constexpr int l2 = PingPongTraits<2, BM, BN, BK, WM, WN, (NSTAGE > 4 ? 4 : NSTAGE)>::LDS_BYTES;
+    constexpr int l2 = PingPongTraits<2, BM, BN, BK, WM, WN, pingpong_down_stages<BM, WM, NSTAGE>()>::LDS_BYTES;
     KernelInfo ki = {};
     ki.cfg = ramp_config{BM, BN, BK, WM * WN, NSTAGE, (WM - 1) | kModePingPong | (group_bits << kModeGroupShift)};
     ki.wm = WM;
     ki.wn = WN;
     ki.lds_bytes = l1 > l2 ? l1 : l2;
-    ki.acc_regs = TT::ACC_REGS;
+    ki.acc_regs = TT::ACC_REGS + 8 * PingPongTraits<1, BM, BN, BK, WM, WN, NSTAGE>::TAILB;
     ki.launch = &launch_pingpong<BM, BN, BK, WM, WN, NSTAGE>;
     ki.kernel_fn[0] = reinterpret_cast<const void *>(&moe_pingpong_kernel<1, BM, BN, BK, WM, WN, NSTAGE>);
-    ki.kernel_fn[1] = reinterpret_cast<const void *>(&moe_pingpong_kernel<2, BM, BN, BK, WM, WN, (NSTAGE > 4 ? 4 : NSTAGE)>);
+    ki.kernel_fn[1] = reinterpret_cast<const void *>(&moe_pingpong_kernel<2, BM, BN, BK, WM, WN, pingpong_down_stages<BM, WM, NSTAGE>()>);
     ki.block_threads = 512;
     ki.family = "moe_pingpong_kernel";
     const int targs[8] = {1, BM, BN, BK, WM, WN, NSTAGE, 0};

@@ -140,6 +140,28 @@ def test_smallest_dimensions_many_tiles(H, I, E, k, T, beta):
         assert_close(L.run(cfg, ids, w), ref, f"H={H} I={I} {cfg}")
 
 
+def test_expert_row_counts_around_the_tile_and_tail_block_sizes():
+    """Experts whose pair counts sit on both sides of every row-block boundary that the large tiles know: 256 rows
+    (a full tile of the 256-row configurations; the start of the 16-row tail block that the 272-row tile shares
+    between its wavefront rows), 272 (that tile full), one row more or less, two tiles, an empty expert, fewer rows
+    than a block.  top-1 routing makes the counts exact; every element against the oracle on every ping-pong
+    configuration."""
+    counts = [256, 257, 260, 271, 272, 273, 288, 529, 0, 15, 255, 544]
+    shape = synth.Shape("edge", 256, 128, len(counts), 1)
+    T = sum(counts)
+    L = Layer(shape, T, seed=11, x_std=1.5)
+    rng = np.random.default_rng(3)
+    ids = np.repeat(np.arange(len(counts), dtype=np.int32), counts)
+    rng.shuffle(ids)
+    ids = ids.reshape(T, 1)
+    w = rng.uniform(0.25, 1.0, size=(T, 1)).astype(np.float32)
+    ref = L.oracle_rows(ids, w)
+    cfgs = [c for c in ramp.configs(L.rs) if c.mode & 0x400]
+    assert any(c.bm == 272 for c in cfgs) and any(c.bm == 256 for c in cfgs)
+    for cfg in cfgs:
+        assert_close(L.run(cfg, ids, w), ref, f"{cfg}")
+
+
 RANDOM_CASES = [  # H, I, E, k, T, beta: unusual tile counts (N-tiles 1, 3, 5, 6, 7, 10), few and many experts
     (384, 128, 5, 2, 900, 1.0), (256, 640, 7, 3, 400, 0.5), (768, 384, 12, 4, 260, 0.3), (128, 896, 3, 2, 1300, 1.0),
     (640, 256, 40, 6, 150, 0.2), (1280, 128, 9, 1, 2100, 1.0), (512, 768, 130, 5, 333, 0.1), (256, 256, 2, 2, 3000, 1.0),
