@@ -223,7 +223,8 @@ bool config_valid_for_shape(const KernelInfo &ki, const ramp_shape &s)
     if ((cap + 16) * (size_t)s.I >= (1ull << 32) || (size_t)s.T * s.H >= (1ull << 32)) return false;
     if (2ull * s.I * s.H >= (1ull << 32)) return false;
     // the ping-pong kernel keeps stages-1 slices in flight across tile boundaries: a tile must be at least that long
-    if ((c.mode & kModePingPong) && (s.H / c.bk < c.stages || s.I / c.bk < c.stages)) return false;
+    // (and the up-projection loads its token batches up to four slices ahead)
+    if ((c.mode & kModePingPong) && (s.H / c.bk < (c.stages > 4 ? c.stages : 4) || s.I / c.bk < c.stages)) return false;
 
     return true;
 }

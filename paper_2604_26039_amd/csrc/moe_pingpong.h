@@ -29,6 +29,10 @@
 
 #include "moe_gemm.h"
 
+#ifndef RAMP_PINGPONG_NX2
+#define RAMP_PINGPONG_NX2 0  // 1: keep two token buffers everywhere (for comparisons)
+#endif
+
 namespace ramp {
 
 template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
@@ -41,7 +45,11 @@ struct PingPongTraits {
     static constexpr bool ROWX = (STAGE == 1);           // gathered rows, 128-byte pieces
     static constexpr int XK = ROWX ? 64 : BK;            // k-values of one token load batch ("super-slice")
     static constexpr int XS = XK / BK;                   // k-slices fed by one super-slice
-    static constexpr int NX = (XS == 2) ? 2 : NSTAGE;    // token ring depth in super-slices
+    static constexpr int W_BYTES_ = TileTraits<BMAIN, BN, BK, WM, WN, 2>::W_FRAGS * kFragElems * 2;
+    static constexpr int X_BYTES_ = (BM * XK * 2 / 1024 + WM * WN - 1) / (WM * WN) * (WM * WN) * 1024;
+    // token ring depth in super-slices: two-slice batches get a third buffer where LDS has room for it (a batch
+    // then has three slice times to arrive instead of one)
+    static constexpr int NX = (XS == 2) ? ((3 * X_BYTES_ + NSTAGE * W_BYTES_ <= kLdsBytesPerCU && !RAMP_PINGPONG_NX2) ? 3 : 2) : NSTAGE;
     static constexpr int X_BLOCKS = BM * XK * 2 / 1024;                           // 1 KB token load blocks per super-slice
     static constexpr int TSLOTS = (X_BLOCKS + TT::NWAVE - 1) / TT::NWAVE;         // token load instructions per wavefront per super-slice
     static constexpr int X_BYTES = TSLOTS * TT::NWAVE * 1024;                     // (the surplus slots of a tail tile load nothing)
@@ -306,13 +314,20 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     // became free (if any), then weight slice kt+NSTAGE-1.
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s) {
-        if (XS == 1 || s == 0) issue_x(s);
+        if (XS == 1 || s == 0 || (s == 1 && NX == 3)) issue_x(s);
         issue_w(s);
     }
     // token batch 0 and weight slice 0 have landed once only the loads issued after W(0) are outstanding
-    wait_vmcnt<(NSTAGE - 2) * (XS == 1 ? TSLOTS + WSLOTS : WSLOTS)>();
+    wait_vmcnt<(NSTAGE - 2) * (XS == 1 ? TSLOTS + WSLOTS : WSLOTS) + (XS == 2 && NX == 3 ? TSLOTS : 0)>();
     phase_barrier();
     if (group == 1) phase_barrier();  // stagger
+    // Loads that may stay in flight at the end of the M phase of slice kt (two-slice token batches).  Weight slice
+    // kt+1 has to be there; younger than it are the weight slices kt+2 .. kt+NSTAGE-1 and the token batches issued
+    // with them (one per even slice, before the weight slice of that phase).  With two token buffers the batch for
+    // slice kt+1 of an odd kt was issued one phase ago and has to be there too: only what followed it may remain.
+    constexpr int WAIT_EVEN = (NSTAGE - 2) * WSLOTS + (NX == 3 ? (NSTAGE - 3) / 2 + 1 : 1) * TSLOTS;
+    constexpr int WAIT_ODD = (NX == 3) ? (NSTAGE - 2) * WSLOTS + (NSTAGE >= 4 ? (NSTAGE - 4) / 2 + 1 : 0) * TSLOTS
+                                       : (NSTAGE - 2 < 2 ? NSTAGE - 2 : 2) * WSLOTS;
 
     int wbuf_cur = 0, wbuf_issue = NSTAGE - 1;  // weight ring: buffer of the slice being read / being loaded
     int xbat_cur = 0;                           // token ring: batch being read (counts over all tiles)
@@ -374,9 +389,8 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             // this wavefront's part of the next slice has to be in LDS before the barrier after which the other group reads it
             if (STEADY) {
                 if (XS == 1) wait_vmcnt<(NSTAGE - 2) * (TSLOTS + WSLOTS)>();
-                else if (par == 0) wait_vmcnt<(NSTAGE - 2) * WSLOTS + (XS == 2 ? TSLOTS : 0)>();
-                else wait_vmcnt<(NSTAGE - 2 < 2 ? NSTAGE - 2 : 2) * WSLOTS>();  // the token batch issued one phase ago is needed now:
-                                                                              // only the weight batches issued after it may remain
+                else if (par == 0) wait_vmcnt<WAIT_EVEN>();
+                else wait_vmcnt<WAIT_ODD>();
             } else if (kt + 1 < KT) {
                 const int later = min(NSTAGE - 2, KT - 2 - kt);  // younger weight slices that may stay in flight
                 if (XS == 1) wait_vmcnt_upto(later * (TSLOTS + WSLOTS));
@@ -400,7 +414,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         using Full = std::integral_constant<int, 1>;
         using None = std::integral_constant<int, 2>;
         int kt = 0;
-        const int kt_steady = has_next ? KT : KT - NSTAGE + 1;
+        const int kt_steady = has_next ? KT : KT - (NSTAGE - 1 > (NX - 1) * XS ? NSTAGE - 1 : (NX - 1) * XS);
         if (nb_valid == NB) {
             for (; kt < kt_steady; ++kt) slice(kt, True{}, Full{});
             for (; kt < KT; ++kt) slice(kt, False{}, Some{});
