@@ -36,9 +36,14 @@ FP8_PEAK_PFLOPS = 5.0    # dense FP8
 # `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same
 # counter reads for the library's 1 GiB copy kernel).  These are RECORDED values, not measured in the
 # run that prints them: each entry names the text summary under profiles/ that holds the run and its
-# per-kernel table.  Keyed by (model, T, beta); other workloads report null.
+# per-kernel table.  Keyed by (model, T, beta), valid for the tile configuration (bm, bn, bk, waves, stages) that was
+# profiled; other workloads, or another dispatched configuration, report null.
 RECORDED_TRAFFIC = {
-    ("olmoe", 4096, "1.0"): (1017.4e6 + 68.1e6, "profiles/olmoe_T4096_hbm_traffic_pmc.md"),
+    ("dsv3", 8192, "1.0"): (18.07e9 + 326.3e6, (272, 256, 32, 8, 4), "profiles/dsv3_T8192_uniform_pingpong_272x256_and_256x256_trace_traffic_sq.md"),
+    ("dsv3", 2048, "0.2"): (6.22e9 + 68.8e6, (256, 256, 32, 8, 4), "profiles/dsv3_T2048_beta02_and_mixtral_T8192_pingpong_256x256_trace_traffic_sq.md"),
+    ("mixtral", 8192, "1.0"): (16.59e9 + 471.6e6, (256, 256, 32, 8, 4), "profiles/dsv3_T2048_beta02_and_mixtral_T8192_pingpong_256x256_trace_traffic_sq.md"),
+    ("qwen3", 8192, "1.0"): (1.88e9 + 102.3e6, (256, 256, 32, 8, 3), "profiles/qwen3_T8192_and_olmoe_T4096_pingpong_trace_traffic_sq.md"),
+    ("olmoe", 4096, "1.0"): (1.17e9 + 68.1e6, (256, 256, 32, 8, 4), "profiles/qwen3_T8192_and_olmoe_T4096_pingpong_trace_traffic_sq.md"),
 }
 
 # Largest point of every other model shape, reported next to the headline.
@@ -255,8 +260,9 @@ def main():
     # Eq. 6 as printed, every single departure from it, the fit-only change plus the traffic column, and the model
     # that is dispatched (all four departures)
     MODELS = {"eq6": ramp.CM_EQ6, "relative_fit": ramp.CM_RELATIVE, "distinct_tiles": ramp.CM_DISTINCT_TILES,
-              "wave_floor": ramp.CM_WAVE_FLOOR, "pairs": ramp.CM_PAIRS,
+              "wave_floor": ramp.CM_WAVE_FLOOR, "pairs": ramp.CM_PAIRS, "rounds": ramp.CM_ROUNDS,
               "relative_fit+distinct_tiles": ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES,
+              "all_but_rounds": tuner.MI355X_MODEL & ~ramp.CM_ROUNDS,
               "eq6_mi355x": tuner.MI355X_MODEL}
     thetas = {name: tuner.fit(fam, g_fit, t_fit, counts_fit, flags) for name, flags in MODELS.items()}
     DISPATCH = "eq6_mi355x"
@@ -265,10 +271,11 @@ def main():
     # coefficients come out zero (minimum-norm solution): 2 terms = a + b*w, 3 terms = + c*m, 4 terms = + d*P
     u_fit = tuner.distinct_tiles(fam, counts_fit)
     P_fit = np.array([ramp.grid(s.E, fam.cfgs, fam.ntiles, c)[2] for c in counts_fit], np.int64)
+    gr_fit = tuner.grid_rounds(fam, counts_fit)
     ABLATION = {2: ramp.cost_model_fit(fam.wave_cap, g_fit, t_fit, distinct=np.zeros_like(u_fit), pairs=np.zeros_like(P_fit),
-                                       flags=dispatch_flags),
+                                       flags=dispatch_flags, grid_rounds=gr_fit),
                 3: ramp.cost_model_fit(fam.wave_cap, g_fit, t_fit, distinct=u_fit, pairs=np.zeros_like(P_fit),
-                                       flags=dispatch_flags),
+                                       flags=dispatch_flags, grid_rounds=gr_fit),
                 4: theta}
     # Sec. 5.3's fifth term (g^2) on top of Eq. 6 as printed and on top of the dispatch model
     theta5 = {name: tuner.fit5(fam, g_fit, t_fit, counts_fit, MODELS[name]) for name in ("eq6", DISPATCH)}
@@ -278,7 +285,7 @@ def main():
 
     def predictions(name, counts):
         return ramp.cost_model_select(s.E, fam.cfgs, fam.ntiles, fam.wave_cap, thetas[name], counts, want_pred=True,
-                                      flags=MODELS[name])[1]
+                                      flags=MODELS[name], rounds=fam.rounds)[1]
 
     r2 = {}
     for name in ("eq6", DISPATCH):
@@ -474,7 +481,7 @@ def main():
         picked = picked[:4]
         cands = [fam.cfgs[c] for c in picked]
         table = torch.from_numpy(ramp.select_table_build(cands, fam.ntiles[picked], fam.wave_cap[picked], theta[picked],
-                                                         dispatch_flags)).to(dev)
+                                                         dispatch_flags, rounds=fam.rounds[picked])).to(dev)
         res_dev = torch.zeros(ramp.select_result_bytes(s.E, len(cands)), dtype=torch.uint8, device=dev)
         sel_dev = torch.zeros(1, dtype=torch.int32, device=dev)
         ws_g = layers.workspace(ramp.fused_moe_selected_workspace_bytes(rs, cands))
@@ -513,7 +520,9 @@ def main():
     log(f"[bench] register-resident MFMA loop: {ceiling['zeros_operands_pflops']:.2f} PFLOP/s on zeros, "
         f"{ceiling['normal_operands_pflops']:.2f} PFLOP/s on N(0,1) bf16 operands (nominal peak {MFMA_PEAK_PFLOPS})")
     rec = RECORDED_TRAFFIC.get((args.model, T_head, str(beta_head)))
-    roof.update(traffic=rec[0] if rec else None, traffic_source=(rec[1] + " (recorded rocprofv3 --pmc value, not measured in this run)") if rec else None,
+    if rec and tuple(cfg_head.key()[:5]) != rec[1]:
+        rec = None
+    roof.update(traffic=rec[0] if rec else None, traffic_source=(rec[2] + " (recorded rocprofv3 --pmc value, not measured in this run)") if rec else None,
                 kernel=kernel_name(cfg_head), launches=probe_n)
     t_hbm, t_mfma, nbytes, flops = tuner.roofline_lower_bound_us(s, T_head, p.counts, HBM_PEAK_TBS, MFMA_PEAK_PFLOPS)
     whole = dict(bound="hbm" if t_hbm >= t_mfma else "mfma", lower_bound_us=max(t_hbm, t_mfma),

@@ -213,8 +213,16 @@ int ramp_fused_moe_fp8(const ramp_shape *shape, const ramp_config *cfg,
  *   here show as a plateau rather than a logarithm.
  * RAMP_CM_PAIRS: the fourth term is l = P = sum_e n_e, the routed pairs, in place of ln(g+1) and
  *   always fitted: gather, SwiGLU, per-pair rows and the combine cost time per pair whatever the
- *   tiling, which g (padded tiles) does not separate from the padding. */
-enum { RAMP_CM_EQ6 = 0, RAMP_CM_RELATIVE = 1, RAMP_CM_DISTINCT_TILES = 2, RAMP_CM_WAVE_FLOOR = 4, RAMP_CM_PAIRS = 8 };
+ *   tiling, which g (padded tiles) does not separate from the padding.
+ * RAMP_CM_ROUNDS: the wave term counts whole hand-out rounds, w = g_r/W with
+ *   g_r = sum over the two launches of ceil(M_tiles/R)*R*ntiles_launch (ramp_config_rounds gives R and
+ *   ntiles_launch).  A persistent kernel's fixed workgroups take the M-tiles in rounds of R = 8*group_m over the
+ *   8 XCDs, so its time steps at multiples of R M-tiles: the wave staircase of Sec. 4.2 ("time jumps at wave
+ *   boundaries") in the units of this kernel's workgroup -> tile map, and what tells the GROUP_M block shapes of
+ *   one tile apart.  R = 1 (g_r = g) for kernels whose workgroups are dispatched tile by tile.  Needs the
+ *   *_rounds entry points below. */
+enum { RAMP_CM_EQ6 = 0, RAMP_CM_RELATIVE = 1, RAMP_CM_DISTINCT_TILES = 2, RAMP_CM_WAVE_FLOOR = 4, RAMP_CM_PAIRS = 8,
+       RAMP_CM_ROUNDS = 16 };
 
 /* Least-squares fit per configuration from profiling (Sec. 4.2 "Fitting").
  * grid, time_us (and distinct, required with RAMP_CM_DISTINCT_TILES, else may be NULL) are
@@ -247,11 +255,28 @@ int ramp_cost_model_select5(int E, int n_cfg, const ramp_config *cfgs, const int
                             const int32_t *wave_cap, const float *theta5,
                             const int32_t *expert_counts, int flags, int *best_idx, double *pred_us);
 
+/* The model with RAMP_CM_ROUNDS (and without: grid_rounds / rounds may then be NULL).  n_terms = 4 or 5 as in
+ * ramp_cost_model_fit / fit5.  grid_rounds: host [n_cfg, n_pts], the g_r of every profiling point (ramp_grid);
+ * rounds: host [n_cfg, 4] = ramp_config_rounds of every configuration.  The traffic, logarithm and g^2 columns
+ * keep the plain g. */
+int ramp_cost_model_fit_rounds(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
+                               const int64_t *grid_rounds, const int64_t *distinct, const int64_t *pairs,
+                               const double *time_us, int flags, int n_terms, float *theta /*host out [n_cfg, n_terms]*/);
+int ramp_cost_model_select_rounds(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
+                                  const int32_t *rounds, const int32_t *wave_cap, const float *theta,
+                                  const int32_t *expert_counts, int flags, int n_terms, int *best_idx, double *pred_us);
+/* out = {R_up, ntiles_up, R_down, ntiles_down}: M-tiles handed out per round over the 8 XCDs (8*group_m of the
+ * launch's workgroup -> tile map for the persistent kernels, 1 otherwise) and N-tiles (2I/bn, H/bn) of the
+ * up- and the down-projection launch.  Host only. */
+int ramp_config_rounds(const ramp_shape *shape, const ramp_config *cfg, int32_t out[4]);
+
 /* Eq. 1 for every configuration on one histogram (host [E]): grid[c] = (sum_e ceil(n_e/bm_c)) * ntiles[c], the
  * g of Eq. 6.  Optional outputs (may be NULL): distinct[c] = #{e: n_e > 0} * ntiles[c] (the column of
- * RAMP_CM_DISTINCT_TILES) and *pairs = sum_e n_e (the column of RAMP_CM_PAIRS).  Host only. */
+ * RAMP_CM_DISTINCT_TILES), *pairs = sum_e n_e (the column of RAMP_CM_PAIRS) and, from rounds (host [n_cfg, 4],
+ * required with it), grid_rounds[c] = the g_r of RAMP_CM_ROUNDS.  Host only. */
 int ramp_grid(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles, const int32_t *expert_counts,
-              int64_t *grid /*host out [n_cfg]*/, int64_t *distinct /*host out [n_cfg]*/, int64_t *pairs /*host out*/);
+              int64_t *grid /*host out [n_cfg]*/, int64_t *distinct /*host out [n_cfg]*/, int64_t *pairs /*host out*/,
+              const int32_t *rounds /*host [n_cfg,4] or NULL*/, int64_t *grid_rounds /*host out [n_cfg] or NULL*/);
 
 /* ---- performance-region variables (Sec. 4.1: Eq. 2-5, Tab. 2) ------------------------------------
  * The four quantities the paper uses to say which optimisation modes belong in a model's pool, for
@@ -291,8 +316,9 @@ int ramp_region_classify(const ramp_shape *shape, const ramp_config *cfg, long l
  *
  * Table (device memory, built once on the host and copied by the caller):
  *   ramp_select_table_build writes ramp_select_table_bytes(n_cfg) bytes: a 128-byte header
- *   {int32 magic, n_cfg, n_bm, flags, bm[28]} (the distinct bm values) followed by n_cfg rows of 32
- *   bytes {int32 bm_slot, ntiles, wave_cap, 0; float theta[4]}.  At most 28 distinct bm, n_cfg <= 1024.
+ *   {int32 magic, n_cfg, n_bm, flags, bm[28]} (the distinct bm values) followed by n_cfg rows of 48
+ *   bytes {int32 bm_slot, ntiles, wave_cap, 0; float theta[4]; int32 rounds[4]}.  At most 28 distinct bm,
+ *   n_cfg <= 1024.  rounds: host [n_cfg, 4] (ramp_config_rounds), required with RAMP_CM_ROUNDS, else may be NULL.
  * Result block (ramp_select_result_bytes(E, n_cfg) bytes, 8-byte aligned, written by the kernel):
  *   uint64 word = best << 32 | ticket | int32 n_cfg | int32 0 | double pred_us[n_cfg] | int32 expert_counts[E]
  *   The word carries the caller's ticket (nonzero, different from what the block held before) and the
@@ -304,7 +330,7 @@ int ramp_region_classify(const ramp_shape *shape, const ramp_config *cfg, long l
 size_t ramp_select_table_bytes(int n_cfg);
 int ramp_select_table_build(int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
                             const int32_t *wave_cap, const float *theta /*host [n_cfg,4]*/, int flags,
-                            void *table /*host out*/, size_t table_bytes);
+                            const int32_t *rounds /*host [n_cfg,4] or NULL*/, void *table /*host out*/, size_t table_bytes);
 size_t ramp_select_result_bytes(int E, int n_cfg);
 int ramp_select_device(const int32_t *topk_ids /*dev [T*k]*/, int T, int k, int E, int n_cfg,
                        const void *table /*dev*/, void *result /*pinned host or dev*/,

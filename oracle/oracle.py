@@ -230,12 +230,22 @@ def select(bm, ntiles, wave_cap, theta, counts, distinct_tiles: bool = False, wa
     return int(best), pred
 
 
-def design_matrix(g, wave_cap: int, distinct=None, wave_floor: bool = False, pairs=None) -> np.ndarray:
+def grid_rounds(counts, bm: int, rounds4) -> int:
+    """The g_r of the "rounds" departure from Eq. 6: for each of the two launches (R, ntiles) of a configuration,
+    its M-tiles (first factor of Eq. 1) rounded up to a whole number of hand-out rounds of R M-tiles, times the
+    N-tiles of that launch.  R = 1 in both launches gives back Eq. 1."""
+    m_tiles = sum((int(n) + bm - 1) // bm for n in counts if int(n) > 0)
+    r_up, nt_up, r_down, nt_down = (int(v) for v in rounds4)
+    return (-(-m_tiles // r_up)) * r_up * nt_up + (-(-m_tiles // r_down)) * r_down * nt_down
+
+
+def design_matrix(g, wave_cap: int, distinct=None, wave_floor: bool = False, pairs=None, wave_grid=None) -> np.ndarray:
     """Rows [1, w, m, l].  As printed (Eq. 6): w = g/W, m = g, l = ln(g+1).  distinct: m = the
-    distinct-weight-tile count; wave_floor: w = max(g/W, 1); pairs: l = routed pairs of each point."""
+    distinct-weight-tile count; wave_floor: w = max(g/W, 1); pairs: l = routed pairs of each point;
+    wave_grid: the wave term alone counts these grids (grid_rounds) instead of g."""
     g = np.asarray(g, dtype=np.float64)
     m = g if distinct is None else np.asarray(distinct, dtype=np.float64)
-    w = g / float(wave_cap)
+    w = (g if wave_grid is None else np.asarray(wave_grid, dtype=np.float64)) / float(wave_cap)
     if wave_floor:
         w = np.maximum(w, 1.0)
     last = np.log(g + 1.0) if pairs is None else np.asarray(pairs, dtype=np.float64)
@@ -248,14 +258,14 @@ def lower_median(v) -> float:
 
 
 def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4, distinct=None, relative: bool = False,
-                   wave_floor: bool = False, pairs=None):
+                   wave_floor: bool = False, pairs=None, wave_grid=None):
     """Sec. 4.2 "Fitting" for ONE configuration.
 
     distinct / relative / wave_floor / pairs are the documented departures from the printed recipe
     that the GPU library also offers: the traffic column holds the number of distinct weight tiles
     instead of g, the residuals are relative (every row divided by its measured time), the wave
-    column is max(g/W, 1), and the fourth column is the routed-pair count (then always fitted)
-    instead of the logarithm.
+    column is max(g/W, 1), the fourth column is the routed-pair count (then always fitted)
+    instead of the logarithm, and (wave_grid) the wave column counts whole hand-out rounds (grid_rounds).
 
     g: profiling grids, t_us: measured times.  The log column is used only if
     the (lower) median profiling grid is below wave_cap.  Solves the literal
@@ -267,7 +277,7 @@ def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4, distinct=None, rela
     """
     g = np.asarray(g, dtype=np.float64)
     t = np.asarray(t_us, dtype=np.float64)
-    X = design_matrix(g, wave_cap, distinct, wave_floor, pairs)
+    X = design_matrix(g, wave_cap, distinct, wave_floor, pairs, wave_grid)
     use_log = (n_terms >= 4) and (pairs is not None or lower_median(g) < wave_cap)
     cols = [0, 1, 2] + ([3] if use_log else [])
     if n_terms == 2:
@@ -282,6 +292,25 @@ def fit_cost_model(g, t_us, wave_cap: int, n_terms: int = 4, distinct=None, rela
     theta = np.zeros(5 if n_terms == 5 else 4, np.float64)
     theta[cols] = sol
     return theta, use_log
+
+
+def select_rounds(bm, ntiles, wave_cap, theta, counts, rounds, distinct_tiles: bool = False, wave_floor: bool = False,
+                  pairs_term: bool = False):
+    """select() with the wave term on grid_rounds (rounds: [n_cfg, 4]); plain fp64, one configuration at a time.
+    Returns (lowest index with the smallest prediction, predictions)."""
+    counts = [int(n) for n in counts]
+    active, pairs = sum(1 for n in counts if n > 0), sum(n for n in counts if n > 0)
+    theta = np.asarray(theta, dtype=np.float32).reshape(-1, 4).astype(np.float64)
+    pred = np.empty(len(bm), np.float64)
+    for c in range(len(bm)):
+        g = grid(counts, int(bm[c]), int(ntiles[c]))
+        x = design_matrix([g], int(wave_cap[c]), [active * int(ntiles[c])] if distinct_tiles else None, wave_floor,
+                          [pairs] if pairs_term else None, [grid_rounds(counts, int(bm[c]), rounds[c])])[0]
+        t = float(theta[c][0]) * float(x[0])
+        for j in (1, 2, 3):     # term by term, in the order the model is written
+            t = t + float(theta[c][j]) * float(x[j])
+        pred[c] = t
+    return int(np.argmin(pred)), pred
 
 
 def predict5(theta5, g: int, wave_cap: int, distinct=None, wave_floor: bool = False, pairs=None) -> float:

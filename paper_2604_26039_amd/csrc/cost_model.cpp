@@ -7,6 +7,8 @@
 //   per-block traffic term is made cache aware (RAMP_CM_DISTINCT_TILES);
 //   l = ln(g + 1) as printed (used only in the sub-wave case), or the number of routed pairs
 //   (RAMP_CM_PAIRS: the work that does not depend on the tiling).
+//   RAMP_CM_ROUNDS: the g of the wave term counts the M-tiles of each launch in whole hand-out rounds of the
+//   launch's workgroup -> tile map (persistent kernels; g_r = g for the others).
 //
 // The columns g/W and g of the design matrix are proportional for a fixed configuration, so
 // the literal four-column system is rank deficient.  The fit returns the minimum-norm
@@ -85,19 +87,21 @@ void lstsq_min_norm(std::vector<double> A, int n, int m, const double *t, double
 
 }  // namespace
 
-static const int kAllFlags = RAMP_CM_RELATIVE | RAMP_CM_DISTINCT_TILES | RAMP_CM_WAVE_FLOOR | RAMP_CM_PAIRS;
+static const int kAllFlags = RAMP_CM_RELATIVE | RAMP_CM_DISTINCT_TILES | RAMP_CM_WAVE_FLOOR | RAMP_CM_PAIRS | RAMP_CM_ROUNDS;
 
 // n_theta = 4: Eq. 6; n_theta = 5: the ablation of Sec. 5.3 with a fifth column (g/W)^2, i.e. g^2 up to the
 // configuration's constant W^2 (kept of order one for the conditioning of the system).
-static int fit_impl(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid, const int64_t *distinct,
-                    const int64_t *pairs, const double *time_us, int flags, float *theta, int n_theta)
+static int fit_impl(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid, const int64_t *grid_rounds,
+                    const int64_t *distinct, const int64_t *pairs, const double *time_us, int flags, float *theta,
+                    int n_theta)
 {
+    const bool use_rounds = (flags & RAMP_CM_ROUNDS) != 0;
     const bool use_distinct = (flags & RAMP_CM_DISTINCT_TILES) != 0;
     const bool relative = (flags & RAMP_CM_RELATIVE) != 0;
     const bool wave_floor = (flags & RAMP_CM_WAVE_FLOOR) != 0;
     const bool use_pairs = (flags & RAMP_CM_PAIRS) != 0;
     if (n_cfg < 0 || n_pts <= 0 || !wave_cap || !grid || !time_us || !theta || (use_distinct && !distinct) ||
-        (use_pairs && !pairs) || (flags & ~kAllFlags)) {
+        (use_pairs && !pairs) || (use_rounds && !grid_rounds) || (flags & ~kAllFlags) || (n_theta != 4 && n_theta != 5)) {
         ramp::set_error("cost_model_fit: bad argument");
         return RAMP_EINVAL;
     }
@@ -128,7 +132,7 @@ static int fit_impl(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t
                 scale = 1.0 / t[i];
             }
             A[0 * (size_t)n_pts + i] = 1.0 * scale;
-            const double wi = gi / W;
+            const double wi = (use_rounds ? (double)grid_rounds[(size_t)c * n_pts + i] : gi) / W;
             A[1 * (size_t)n_pts + i] = ((wave_floor && wi < 1.0) ? 1.0 : wi) * scale;
             A[2 * (size_t)n_pts + i] = mi * scale;
             A[3 * (size_t)n_pts + i] = (use_pairs ? (double)pairs[i] : std::log(gi + 1.0)) * scale;
@@ -149,22 +153,41 @@ extern "C" int ramp_cost_model_fit(int n_cfg, const int32_t *wave_cap, int n_pts
                                    const int64_t *distinct, const int64_t *pairs, const double *time_us, int flags,
                                    float *theta)
 {
-    return fit_impl(n_cfg, wave_cap, n_pts, grid, distinct, pairs, time_us, flags, theta, 4);
+    return fit_impl(n_cfg, wave_cap, n_pts, grid, nullptr, distinct, pairs, time_us, flags, theta, 4);
 }
 
 extern "C" int ramp_cost_model_fit5(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
                                     const int64_t *distinct, const int64_t *pairs, const double *time_us, int flags,
                                     float *theta5)
 {
-    return fit_impl(n_cfg, wave_cap, n_pts, grid, distinct, pairs, time_us, flags, theta5, 5);
+    return fit_impl(n_cfg, wave_cap, n_pts, grid, nullptr, distinct, pairs, time_us, flags, theta5, 5);
 }
 
-static int select_impl(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles, const int32_t *wave_cap,
-                       const float *theta, const int32_t *expert_counts, int flags, int *best_idx, double *pred_us,
-                       int n_theta)
+extern "C" int ramp_cost_model_fit_rounds(int n_cfg, const int32_t *wave_cap, int n_pts, const int64_t *grid,
+                                          const int64_t *grid_rounds, const int64_t *distinct, const int64_t *pairs,
+                                          const double *time_us, int flags, int n_terms, float *theta)
 {
+    return fit_impl(n_cfg, wave_cap, n_pts, grid, grid_rounds, distinct, pairs, time_us, flags, theta, n_terms);
+}
+
+// g_r of one configuration: the M-tiles of each of its two launches rounded up to whole hand-out rounds
+static inline int64_t rounded_grid(int64_t mt, const int32_t *r)
+{
+    int64_t g = 0;
+    for (int s = 0; s < 2; ++s) {
+        const int64_t R = r[2 * s], nt = r[2 * s + 1];
+        g += (mt + R - 1) / R * R * nt;
+    }
+    return g;
+}
+
+static int select_impl(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles, const int32_t *rounds,
+                       const int32_t *wave_cap, const float *theta, const int32_t *expert_counts, int flags,
+                       int *best_idx, double *pred_us, int n_theta)
+{
+    const bool use_rounds = (flags & RAMP_CM_ROUNDS) != 0;
     if (E <= 0 || n_cfg <= 0 || !cfgs || !ntiles || !wave_cap || !theta || !expert_counts || !best_idx ||
-        (flags & ~kAllFlags)) {
+        (use_rounds && !rounds) || (flags & ~kAllFlags) || (n_theta != 4 && n_theta != 5)) {
         ramp::set_error("cost_model_select: bad argument");
         return RAMP_EINVAL;
     }
@@ -199,12 +222,16 @@ static int select_impl(int E, int n_cfg, const ramp_config *cfgs, const int32_t 
         const double g = (double)(last_mt * (int64_t)ntiles[c]);
         const float *th = theta + (size_t)c * n_theta;
         double t = (double)th[0];
-        const double w = g / (double)wave_cap[c];
+        if (use_rounds && (rounds[4 * c] <= 0 || rounds[4 * c + 2] <= 0)) {
+            ramp::set_error("cost_model_select: config %d has a round of %d / %d M-tiles", c, rounds[4 * c], rounds[4 * c + 2]);
+            return RAMP_EINVAL;
+        }
+        const double w = (use_rounds ? (double)rounded_grid(last_mt, rounds + 4 * c) : g) / (double)wave_cap[c];
         t = t + (double)th[1] * ((wave_floor && w < 1.0) ? 1.0 : w);
         const double m = use_distinct ? (double)(active * (int64_t)ntiles[c]) : g;
         t = t + (double)th[2] * m;
         t = t + (double)th[3] * (use_pairs ? (double)pairs : std::log(g + 1.0));
-        if (n_theta == 5) t = t + (double)th[4] * (w * w);  // w = g/W, not floored
+        if (n_theta == 5) t = t + (double)th[4] * ((g / (double)wave_cap[c]) * (g / (double)wave_cap[c]));  // g/W, not floored
         if (pred_us) pred_us[c] = t;
         if (best < 0 || t < best_t) {
             best = c;
@@ -219,21 +246,29 @@ extern "C" int ramp_cost_model_select(int E, int n_cfg, const ramp_config *cfgs,
                                       const int32_t *wave_cap, const float *theta, const int32_t *expert_counts,
                                       int flags, int *best_idx, double *pred_us)
 {
-    return select_impl(E, n_cfg, cfgs, ntiles, wave_cap, theta, expert_counts, flags, best_idx, pred_us, 4);
+    return select_impl(E, n_cfg, cfgs, ntiles, nullptr, wave_cap, theta, expert_counts, flags, best_idx, pred_us, 4);
 }
 
 extern "C" int ramp_cost_model_select5(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
                                        const int32_t *wave_cap, const float *theta5, const int32_t *expert_counts,
                                        int flags, int *best_idx, double *pred_us)
 {
-    return select_impl(E, n_cfg, cfgs, ntiles, wave_cap, theta5, expert_counts, flags, best_idx, pred_us, 5);
+    return select_impl(E, n_cfg, cfgs, ntiles, nullptr, wave_cap, theta5, expert_counts, flags, best_idx, pred_us, 5);
+}
+
+extern "C" int ramp_cost_model_select_rounds(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles,
+                                             const int32_t *rounds, const int32_t *wave_cap, const float *theta,
+                                             const int32_t *expert_counts, int flags, int n_terms, int *best_idx,
+                                             double *pred_us)
+{
+    return select_impl(E, n_cfg, cfgs, ntiles, rounds, wave_cap, theta, expert_counts, flags, best_idx, pred_us, n_terms);
 }
 
 // Eq. 1 for every configuration on one histogram, with the other two histogram sums the model's columns use.
 extern "C" int ramp_grid(int E, int n_cfg, const ramp_config *cfgs, const int32_t *ntiles, const int32_t *expert_counts,
-                         int64_t *grid, int64_t *distinct, int64_t *pairs)
+                         int64_t *grid, int64_t *distinct, int64_t *pairs, const int32_t *rounds, int64_t *grid_rounds)
 {
-    if (E <= 0 || n_cfg <= 0 || !cfgs || !ntiles || !expert_counts || !grid) {
+    if (E <= 0 || n_cfg <= 0 || !cfgs || !ntiles || !expert_counts || !grid || (grid_rounds && !rounds)) {
         ramp::set_error("grid: bad argument");
         return RAMP_EINVAL;
     }
@@ -255,6 +290,13 @@ extern "C" int ramp_grid(int E, int n_cfg, const ramp_config *cfgs, const int32_
         }
         grid[c] = mt * (int64_t)ntiles[c];
         if (distinct) distinct[c] = active * (int64_t)ntiles[c];
+        if (grid_rounds) {
+            if (rounds[4 * c] <= 0 || rounds[4 * c + 2] <= 0) {
+                ramp::set_error("grid: config %d has a round of %d / %d M-tiles", c, rounds[4 * c], rounds[4 * c + 2]);
+                return RAMP_EINVAL;
+            }
+            grid_rounds[c] = rounded_grid(mt, rounds + 4 * c);
+        }
     }
     if (pairs) *pairs = total;
     return RAMP_OK;

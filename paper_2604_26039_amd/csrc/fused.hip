@@ -314,6 +314,24 @@ extern "C" int ramp_config_ntiles(const ramp_shape *shape, const ramp_config *cf
     return (2 * shape->I + cfg->bn - 1) / cfg->bn + (shape->H + cfg->bn - 1) / cfg->bn;
 }
 
+extern "C" int ramp_config_rounds(const ramp_shape *shape, const ramp_config *cfg, int32_t out[4])
+{
+    if (!shape || !cfg || !out || cfg->bn <= 0 || shape->H <= 0 || shape->I <= 0) {
+        set_error("config_rounds: bad argument");
+        return RAMP_EINVAL;
+    }
+    const int nt[2] = {(2 * shape->I + cfg->bn - 1) / cfg->bn, (shape->H + cfg->bn - 1) / cfg->bn};
+    for (int s = 0; s < 2; ++s) {
+        int gm = 1, gn = 1;
+        // only the persistent kernels walk the map with a fixed set of workgroups; the others are dispatched
+        // tile by tile as compute units free up
+        if ((cfg->mode & kModePingPong) && !(cfg->mode & kModeFp8)) xcd_block_shape(nt[s], group_m_of_mode(cfg->mode), &gm, &gn);
+        out[2 * s] = (cfg->mode & kModePingPong) && !(cfg->mode & kModeFp8) ? 8 * gm : 1;
+        out[2 * s + 1] = nt[s];
+    }
+    return RAMP_OK;
+}
+
 extern "C" int ramp_config_wave_capacity(const ramp_config *cfg)
 {
     if (!cfg) {

@@ -200,24 +200,7 @@ __device__ __forceinline__ void tile_of_workgroup(const GemmArgs &a, int &n_tile
 // Picks the block shape for the launch and returns the (overlaunched) number of tile ids that tile_of_id expects.
 inline unsigned xcd_grid(GemmArgs &g)
 {
-    if (g.group_m_req > 0) {
-        // GROUP_M mode of the configuration: blocks of group_m M-tiles x about 32/group_m N-tiles (one XCD runs 32
-        // large-tile workgroups at a time); the N extent is the largest divisor of the N-tile count below that
-        g.group_m = g.group_m_req;
-        int gn = 32 / g.group_m;
-        if (gn < 1) gn = 1;
-        if (gn > g.n_tiles) gn = g.n_tiles;
-        while (g.n_tiles % gn) --gn;
-        g.group_n = gn;
-    } else {
-        // Default: a block spans all N-tiles: the token rows of its few M-tiles (group_m * bm * K * 2 bytes) then stay
-        // in the 4 MB L2 across the whole walk over N; the 8 XCDs work on neighbouring M-tiles, i.e. mostly the same
-        // expert, and share its weights through the memory-side cache.
-        g.group_n = g.n_tiles;
-        g.group_m = 32 / g.n_tiles;
-        if (g.group_m < 1) g.group_m = 1;
-        if (g.group_m > 8) g.group_m = 8;
-    }
+    xcd_block_shape(g.n_tiles, g.group_m_req, &g.group_m, &g.group_n);
     const int per_round = 8 * g.group_m;  // M-tiles handed out per round over the 8 XCDs
     const int rounds = (g.m_tiles_cap + per_round - 1) / per_round;
     return (unsigned)rounds * (unsigned)per_round * (unsigned)g.n_tiles;

@@ -118,6 +118,29 @@ constexpr int kModeGroupShift = 12;
 constexpr int kModeGroupMask = 0xF << kModeGroupShift;
 inline int group_m_of_mode(int mode) { const int v = (mode & kModeGroupMask) >> kModeGroupShift; return v ? (1 << v) : 0; }
 
+// Block shape of the XCD-aware workgroup -> tile map of one launch: every XCD takes blocks of group_m M-tiles x
+// group_n N-tiles, the 8 XCDs 8 * group_m M-tiles per hand-out round.  group_m_req > 0: the GROUP_M mode of the
+// configuration (group_n = the largest divisor of n_tiles up to 32 / group_m).  Default: a block spans all N-tiles, so
+// the token rows of its few M-tiles (group_m * bm * K * 2 bytes) stay in the 4 MB L2 across the walk over N while the
+// 8 XCDs work on neighbouring M-tiles, i.e. mostly the same expert, and share its weights through the memory-side cache.
+inline void xcd_block_shape(int n_tiles, int group_m_req, int *group_m, int *group_n)
+{
+    if (group_m_req > 0) {
+        int gn = 32 / group_m_req;
+        if (gn < 1) gn = 1;
+        if (gn > n_tiles) gn = n_tiles;
+        while (n_tiles % gn) --gn;
+        *group_m = group_m_req;
+        *group_n = gn;
+    } else {
+        int gm = 32 / n_tiles;
+        if (gm < 1) gm = 1;
+        if (gm > 8) gm = 8;
+        *group_m = gm;
+        *group_n = n_tiles;
+    }
+}
+
 struct DecodeArgs;
 struct DecodeDownArgs;
 struct KernelInfo {

@@ -25,8 +25,9 @@ struct TableHeader {
 struct TableRow {
     int32_t bm_slot, ntiles, wave_cap, reserved;
     float theta[4];
+    int32_t rounds[4];  // M-tiles per hand-out round and N-tiles of the two launches (RAMP_CM_ROUNDS)
 };
-static_assert(sizeof(TableHeader) == 128 && sizeof(TableRow) == 32, "table layout is part of the ABI");
+static_assert(sizeof(TableHeader) == 128 && sizeof(TableRow) == 48, "table layout is part of the ABI");
 constexpr int32_t kMagic = 0x52614d50;
 
 // Result block: word = best << 32 | ticket (one 64-bit store, written last) | n_cfg | 0 | pred_us[n_cfg] (fp64) | counts[E]
@@ -90,6 +91,7 @@ __global__ __launch_bounds__(NT) void select_kernel(const int32_t *ids, int P, i
     const bool use_distinct = (flags & RAMP_CM_DISTINCT_TILES) != 0;
     const bool wave_floor = (flags & RAMP_CM_WAVE_FLOOR) != 0;
     const bool use_pairs = (flags & RAMP_CM_PAIRS) != 0;
+    const bool use_rounds = (flags & RAMP_CM_ROUNDS) != 0;
     const long long active = active_pairs[0], pairs = active_pairs[1];
     int best = -1;
     double best_t = 0.0;
@@ -97,7 +99,17 @@ __global__ __launch_bounds__(NT) void select_kernel(const int32_t *ids, int P, i
         const TableRow r = rows[c];
         const double g = (double)((long long)mt[r.bm_slot] * (long long)r.ntiles);
         double t = (double)r.theta[0];
-        const double w = g / (double)r.wave_cap;
+        double gw = g;
+        if (use_rounds) {
+            const long long m = mt[r.bm_slot];
+            long long gr = 0;
+            for (int s = 0; s < 2; ++s) {
+                const long long R = r.rounds[2 * s], nt = r.rounds[2 * s + 1];
+                gr += (m + R - 1) / R * R * nt;
+            }
+            gw = (double)gr;
+        }
+        const double w = gw / (double)r.wave_cap;
         t = t + (double)r.theta[1] * ((wave_floor && w < 1.0) ? 1.0 : w);
         const double m = use_distinct ? (double)(active * (long long)r.ntiles) : g;
         t = t + (double)r.theta[2] * m;
@@ -145,10 +157,12 @@ extern "C" size_t ramp_select_table_bytes(int n_cfg)
 }
 
 extern "C" int ramp_select_table_build(int n_cfg, const ramp_config *cfgs, const int32_t *ntiles, const int32_t *wave_cap,
-                                       const float *theta, int flags, void *table, size_t table_bytes)
+                                       const float *theta, int flags, const int32_t *rounds, void *table,
+                                       size_t table_bytes)
 {
     using namespace ramp;
-    if (n_cfg <= 0 || n_cfg > 1024 || !cfgs || !ntiles || !wave_cap || !theta || !table) {
+    if (n_cfg <= 0 || n_cfg > 1024 || !cfgs || !ntiles || !wave_cap || !theta || !table ||
+        ((flags & RAMP_CM_ROUNDS) && !rounds)) {
         set_error("select_table_build: bad argument (1 <= n_cfg <= 1024, no NULL)");
         return RAMP_EINVAL;
     }
@@ -175,7 +189,12 @@ extern "C" int ramp_select_table_build(int n_cfg, const ramp_config *cfgs, const
             }
             h.bm[h.n_bm++] = cfgs[c].bm;
         }
-        rows[c] = TableRow{slot, ntiles[c], wave_cap[c], 0, {theta[4 * c], theta[4 * c + 1], theta[4 * c + 2], theta[4 * c + 3]}};
+        if (rounds && (rounds[4 * c] <= 0 || rounds[4 * c + 2] <= 0)) {
+            set_error("select_table_build: config %d has a round of %d / %d M-tiles", c, rounds[4 * c], rounds[4 * c + 2]);
+            return RAMP_EINVAL;
+        }
+        rows[c] = TableRow{slot, ntiles[c], wave_cap[c], 0, {theta[4 * c], theta[4 * c + 1], theta[4 * c + 2], theta[4 * c + 3]},
+                           {rounds ? rounds[4 * c] : 1, rounds ? rounds[4 * c + 1] : ntiles[c], rounds ? rounds[4 * c + 2] : 1, rounds ? rounds[4 * c + 3] : 0}};
     }
     *static_cast<TableHeader *>(table) = h;
     return RAMP_OK;

@@ -18,7 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libramp.so")
 
 OK, EINVAL, ENOSPC, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
-CM_EQ6, CM_RELATIVE, CM_DISTINCT_TILES, CM_WAVE_FLOOR, CM_PAIRS = 0, 1, 2, 4, 8
+CM_EQ6, CM_RELATIVE, CM_DISTINCT_TILES, CM_WAVE_FLOOR, CM_PAIRS, CM_ROUNDS = 0, 1, 2, 4, 8, 16
 
 
 class Shape(ctypes.Structure):
@@ -136,14 +136,20 @@ def lib() -> ctypes.CDLL:
         L.ramp_cost_model_fit5.argtypes = [ci, vp, ci, vp, vp, vp, vp, ci, vp]
         L.ramp_cost_model_select5.restype = ci
         L.ramp_cost_model_select5.argtypes = [ci, ci, cp, vp, vp, vp, vp, ci, ctypes.POINTER(ci), vp]
+        L.ramp_cost_model_fit_rounds.restype = ci
+        L.ramp_cost_model_fit_rounds.argtypes = [ci, vp, ci, vp, vp, vp, vp, vp, ci, ci, vp]
+        L.ramp_cost_model_select_rounds.restype = ci
+        L.ramp_cost_model_select_rounds.argtypes = [ci, ci, cp, vp, vp, vp, vp, vp, ci, ci, ctypes.POINTER(ci), vp]
+        L.ramp_config_rounds.restype = ci
+        L.ramp_config_rounds.argtypes = [sp, cp, ctypes.POINTER(ctypes.c_int32)]
         L.ramp_grid.restype = ci
-        L.ramp_grid.argtypes = [ci, ci, cp, vp, vp, vp, vp, vp]
+        L.ramp_grid.argtypes = [ci, ci, cp, vp, vp, vp, vp, vp, vp, vp]
         L.ramp_region_classify.restype = ci
         L.ramp_region_classify.argtypes = [sp, cp, ctypes.c_longlong, ctypes.POINTER(RegionThresholds), ctypes.POINTER(Region)]
         L.ramp_select_table_bytes.restype = sz
         L.ramp_select_table_bytes.argtypes = [ci]
         L.ramp_select_table_build.restype = ci
-        L.ramp_select_table_build.argtypes = [ci, cp, vp, vp, vp, ci, vp, sz]
+        L.ramp_select_table_build.argtypes = [ci, cp, vp, vp, vp, ci, vp, vp, sz]
         L.ramp_select_result_bytes.restype = sz
         L.ramp_select_result_bytes.argtypes = [ci, ci]
         L.ramp_select_device.restype = ci
@@ -171,7 +177,8 @@ EXPORTS = [
     "ramp_fused_moe_selected_workspace_bytes", "ramp_fused_moe_selected",
     "ramp_fp8_num_configs", "ramp_fp8_get_config", "ramp_fp8_config_wave_capacity", "ramp_fp8_pack_bytes", "ramp_fp8_pack_weights",
     "ramp_fp8_pack_layout", "ramp_fp8_quantize_rows", "ramp_fused_moe_fp8_workspace_bytes", "ramp_fused_moe_fp8",
-    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_cost_model_fit5", "ramp_cost_model_select5", "ramp_grid", "ramp_region_classify", "ramp_select_table_bytes", "ramp_select_table_build",
+    "ramp_cost_model_fit", "ramp_cost_model_select", "ramp_cost_model_fit5", "ramp_cost_model_select5",
+    "ramp_cost_model_fit_rounds", "ramp_cost_model_select_rounds", "ramp_config_rounds", "ramp_grid", "ramp_region_classify", "ramp_select_table_bytes", "ramp_select_table_build",
     "ramp_select_result_bytes", "ramp_select_device", "ramp_select_poll", "ramp_select_wait", "ramp_copy_bytes", "ramp_mfma_rate_probe", "ramp_probe_enable", "ramp_probe_read",
 ]
 
@@ -395,9 +402,9 @@ def mfma_rate_probe(operands: torch.Tensor, rounds: int, sink: torch.Tensor, str
 # ----------------------------------------------------------------------------- cost model (host)
 
 def cost_model_fit(wave_cap: Sequence[int], grid, time_us, distinct=None, pairs=None, flags: int = CM_EQ6,
-                   terms: int = 4) -> np.ndarray:
-    """grid, time_us (and distinct with CM_DISTINCT_TILES): [n_cfg, n_pts]; pairs (with CM_PAIRS): [n_pts].
-    Returns theta float32 [n_cfg, terms]; terms = 5 calls ramp_cost_model_fit5 (Sec. 5.3 ablation)."""
+                   terms: int = 4, grid_rounds=None) -> np.ndarray:
+    """grid, time_us (and distinct with CM_DISTINCT_TILES, grid_rounds with CM_ROUNDS): [n_cfg, n_pts]; pairs (with
+    CM_PAIRS): [n_pts].  Returns theta float32 [n_cfg, terms]; terms = 5 is the Sec. 5.3 ablation."""
     assert terms in (4, 5)
     grid = _np(grid, np.int64)
     time_us = _np(time_us, np.float64)
@@ -412,6 +419,16 @@ def cost_model_fit(wave_cap: Sequence[int], grid, time_us, distinct=None, pairs=
     wc = _np(wave_cap, np.int32)
     assert wc.size == n_cfg
     theta = np.zeros((n_cfg, terms), np.float32)
+    if grid_rounds is not None or (flags & CM_ROUNDS):
+        if grid_rounds is not None:
+            grid_rounds = _np(grid_rounds, np.int64)
+            assert grid_rounds.shape == (n_cfg, n_pts)
+        _check(lib().ramp_cost_model_fit_rounds(n_cfg, wc.ctypes.data, n_pts, grid.ctypes.data,
+                                                grid_rounds.ctypes.data if grid_rounds is not None else None,
+                                                distinct.ctypes.data if distinct is not None else None,
+                                                pairs.ctypes.data if pairs is not None else None, time_us.ctypes.data,
+                                                flags, terms, theta.ctypes.data))
+        return theta
     fn = lib().ramp_cost_model_fit if terms == 4 else lib().ramp_cost_model_fit5
     _check(fn(n_cfg, wc.ctypes.data, n_pts, grid.ctypes.data,
               distinct.ctypes.data if distinct is not None else None,
@@ -420,7 +437,8 @@ def cost_model_fit(wave_cap: Sequence[int], grid, time_us, distinct=None, pairs=
 
 
 def cost_model_select(E: int, cfgs: Sequence[Config], ntiles, wave_cap, theta, expert_counts, want_pred=False,
-                      flags: int = CM_EQ6, terms: int = 4):
+                      flags: int = CM_EQ6, terms: int = 4, rounds=None):
+    """rounds: int32 [n_cfg, 4] (config_rounds of every configuration), required with CM_ROUNDS."""
     assert terms in (4, 5)
     n = len(cfgs)
     arr = (Config * n)(*cfgs)
@@ -430,14 +448,30 @@ def cost_model_select(E: int, cfgs: Sequence[Config], ntiles, wave_cap, theta, e
     assert counts.size == E and nt.size == n and wc.size == n
     best = ctypes.c_int(-1)
     pred = np.zeros(n, np.float64) if want_pred else None
+    if rounds is not None or (flags & CM_ROUNDS):
+        rd = None if rounds is None else _np(rounds, np.int32)
+        assert rd is None or rd.shape == (n, 4)
+        _check(lib().ramp_cost_model_select_rounds(E, n, arr, nt.ctypes.data, rd.ctypes.data if rd is not None else None,
+                                                   wc.ctypes.data, th.ctypes.data,
+                                                   counts.ctypes.data, flags, terms, ctypes.byref(best),
+                                                   pred.ctypes.data if want_pred else None))
+        return (best.value, pred) if want_pred else best.value
     fn = lib().ramp_cost_model_select if terms == 4 else lib().ramp_cost_model_select5
     _check(fn(E, n, arr, nt.ctypes.data, wc.ctypes.data, th.ctypes.data, counts.ctypes.data,
               flags, ctypes.byref(best), pred.ctypes.data if want_pred else None))
     return (best.value, pred) if want_pred else best.value
 
 
-def grid(E: int, cfgs: Sequence[Config], ntiles, expert_counts):
-    """Eq. 1 per configuration on one histogram: (grid int64 [n_cfg], distinct int64 [n_cfg], pairs int)."""
+def config_rounds(shape: Shape, cfg: Config) -> np.ndarray:
+    """{R_up, ntiles_up, R_down, ntiles_down}: M-tiles per hand-out round and N-tiles of the two launches."""
+    out = (ctypes.c_int32 * 4)()
+    _check(lib().ramp_config_rounds(ctypes.byref(shape), ctypes.byref(cfg), out))
+    return np.array(list(out), np.int32)
+
+
+def grid(E: int, cfgs: Sequence[Config], ntiles, expert_counts, rounds=None):
+    """Eq. 1 per configuration on one histogram: (grid int64 [n_cfg], distinct int64 [n_cfg], pairs int), and with
+    rounds (int32 [n_cfg, 4]) a fourth value: grid_rounds int64 [n_cfg], the g_r of CM_ROUNDS."""
     n = len(cfgs)
     arr = (Config * n)(*cfgs)
     nt = _np(ntiles, np.int32)
@@ -445,22 +479,32 @@ def grid(E: int, cfgs: Sequence[Config], ntiles, expert_counts):
     assert counts.size == E and nt.size == n
     g, d = np.zeros(n, np.int64), np.zeros(n, np.int64)
     pairs = ctypes.c_int64(0)
+    if rounds is not None:
+        rd = _np(rounds, np.int32)
+        assert rd.shape == (n, 4)
+        gr = np.zeros(n, np.int64)
+        _check(lib().ramp_grid(E, n, arr, nt.ctypes.data, counts.ctypes.data, g.ctypes.data, d.ctypes.data,
+                               ctypes.addressof(pairs), rd.ctypes.data, gr.ctypes.data))
+        return g, d, int(pairs.value), gr
     _check(lib().ramp_grid(E, n, arr, nt.ctypes.data, counts.ctypes.data, g.ctypes.data, d.ctypes.data,
-                           ctypes.addressof(pairs)))
+                           ctypes.addressof(pairs), None, None))
     return g, d, int(pairs.value)
 
 
 # ----------------------------------------------------------------------------- device-resident dispatch
 
-def select_table_build(cfgs: Sequence[Config], ntiles, wave_cap, theta, flags: int = CM_EQ6) -> np.ndarray:
-    """Host image (uint8) of the table ramp_select_device reads; copy it to the device once."""
+def select_table_build(cfgs: Sequence[Config], ntiles, wave_cap, theta, flags: int = CM_EQ6, rounds=None) -> np.ndarray:
+    """Host image (uint8) of the table ramp_select_device reads; copy it to the device once.  rounds: int32 [n_cfg, 4],
+    required with CM_ROUNDS."""
     n = len(cfgs)
     arr = (Config * n)(*cfgs)
     nt, wc = _np(ntiles, np.int32), _np(wave_cap, np.int32)
     th = _np(theta, np.float32).reshape(n, 4)
     table = np.zeros(lib().ramp_select_table_bytes(n), np.uint8)
+    rd = None if rounds is None else _np(rounds, np.int32)
+    assert rd is None or rd.shape == (n, 4)
     _check(lib().ramp_select_table_build(n, arr, nt.ctypes.data, wc.ctypes.data, th.ctypes.data, flags,
-                                         table.ctypes.data, table.nbytes))
+                                         rd.ctypes.data if rd is not None else None, table.ctypes.data, table.nbytes))
     return table
 
 

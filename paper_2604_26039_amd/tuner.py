@@ -148,6 +148,11 @@ class Family:
     cfgs: List[ramp.Config]
     ntiles: np.ndarray
     wave_cap: np.ndarray
+    rounds: np.ndarray = None   # int32 [n_cfg, 4]: M-tiles per hand-out round and N-tiles of the two launches
+
+    def __post_init__(self):
+        if self.rounds is None:
+            self.rounds = np.stack([ramp.config_rounds(self.shape, c) for c in self.cfgs]).astype(np.int32)
 
     @staticmethod
     def of(s: synth.Shape, T: int = 1, fp8: bool = False) -> "Family":
@@ -179,9 +184,15 @@ def profile(layers: LayerSet, fam: Family, points: Sequence[Point], log=None, **
     return grid, t_us
 
 
-# The dispatch model used on this chip: Eq. 6 with the traffic term on distinct weight tiles,
-# fitted on relative residuals.  EQ6 (= 0) is the model exactly as printed.
-MI355X_MODEL = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES | ramp.CM_WAVE_FLOOR | ramp.CM_PAIRS
+# The dispatch model used on this chip: Eq. 6 fitted on relative residuals, with the traffic term on distinct weight
+# tiles, a wave term that has a floor of one wave and counts whole hand-out rounds of the persistent kernels, and the
+# routed pairs as fourth term.  EQ6 (= 0) is the model exactly as printed.
+MI355X_MODEL = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES | ramp.CM_WAVE_FLOOR | ramp.CM_PAIRS | ramp.CM_ROUNDS
+
+
+def grid_rounds(fam: Family, counts_list: Sequence[np.ndarray]) -> np.ndarray:
+    """[n_cfg, n_pts]: the g_r of CM_ROUNDS at every point (from the library)."""
+    return np.stack([ramp.grid(fam.shape.E, fam.cfgs, fam.ntiles, c, rounds=fam.rounds)[3] for c in counts_list], axis=1)
 
 
 def distinct_tiles(fam: Family, counts_list: Sequence[np.ndarray]) -> np.ndarray:
@@ -194,7 +205,8 @@ def fit(fam: Family, grid: np.ndarray, t_us: np.ndarray, counts_list=None, flags
     pairs = None
     if flags & ramp.CM_PAIRS:
         pairs = np.array([ramp.grid(fam.shape.E, fam.cfgs, fam.ntiles, c)[2] for c in counts_list], np.int64)
-    return ramp.cost_model_fit(fam.wave_cap, grid, t_us, distinct=distinct, pairs=pairs, flags=flags)
+    gr = grid_rounds(fam, counts_list) if (flags & ramp.CM_ROUNDS) else None
+    return ramp.cost_model_fit(fam.wave_cap, grid, t_us, distinct=distinct, pairs=pairs, flags=flags, grid_rounds=gr)
 
 
 def fit5(fam: Family, grid: np.ndarray, t_us: np.ndarray, counts_list=None, flags: int = ramp.CM_EQ6) -> np.ndarray:
@@ -203,15 +215,18 @@ def fit5(fam: Family, grid: np.ndarray, t_us: np.ndarray, counts_list=None, flag
     pairs = None
     if flags & ramp.CM_PAIRS:
         pairs = np.array([ramp.grid(fam.shape.E, fam.cfgs, fam.ntiles, c)[2] for c in counts_list], np.int64)
-    return ramp.cost_model_fit(fam.wave_cap, grid, t_us, distinct=distinct, pairs=pairs, flags=flags, terms=5)
+    gr = grid_rounds(fam, counts_list) if (flags & ramp.CM_ROUNDS) else None
+    return ramp.cost_model_fit(fam.wave_cap, grid, t_us, distinct=distinct, pairs=pairs, flags=flags, terms=5, grid_rounds=gr)
 
 
 def select5(fam: Family, theta5: np.ndarray, counts: np.ndarray, flags: int = ramp.CM_EQ6) -> int:
-    return ramp.cost_model_select(fam.shape.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta5, counts, flags=flags, terms=5)
+    return ramp.cost_model_select(fam.shape.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta5, counts, flags=flags, terms=5,
+                                  rounds=fam.rounds if (flags & ramp.CM_ROUNDS) else None)
 
 
 def select(fam: Family, theta: np.ndarray, counts: np.ndarray, flags: int = ramp.CM_EQ6) -> int:
-    return ramp.cost_model_select(fam.shape.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, counts, flags=flags)
+    return ramp.cost_model_select(fam.shape.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, counts, flags=flags,
+                                  rounds=fam.rounds if (flags & ramp.CM_ROUNDS) else None)
 
 
 def save_model(path: str, fam: Family, theta: np.ndarray, flags: int, extra: dict = None) -> None:
@@ -269,6 +284,7 @@ class Dispatcher:
         self._cfgs = (ramp.Config * len(fam.cfgs))(*fam.cfgs)
         self._nt = np.ascontiguousarray(fam.ntiles, np.int32)
         self._wc = np.ascontiguousarray(fam.wave_cap, np.int32)
+        self._rounds = np.ascontiguousarray(fam.rounds, np.int32)
         self._theta = np.ascontiguousarray(theta, np.float32)
         self.d_counts = torch.zeros(self.E, dtype=torch.int32, device=device)
         self.h_counts = torch.zeros(self.E, dtype=torch.int32).pin_memory()
@@ -278,7 +294,7 @@ class Dispatcher:
         self._best_ref = ctypes.byref(self._best)
         self._lib = ramp.lib()
         # device-resident path: table on the device, two result blocks in pinned host memory used in turn
-        self.table = torch.from_numpy(ramp.select_table_build(fam.cfgs, fam.ntiles, fam.wave_cap, theta, flags)).to(device)
+        self.table = torch.from_numpy(ramp.select_table_build(fam.cfgs, fam.ntiles, fam.wave_cap, theta, flags, rounds=fam.rounds)).to(device)
         nbytes = ramp.select_result_bytes(self.E, self.n_cfg)
         self.results = [torch.zeros(nbytes, dtype=torch.uint8).pin_memory() for _ in range(2)]
         self._res_ptr = [r.data_ptr() for r in self.results]
@@ -335,9 +351,9 @@ class Dispatcher:
         ramp.moe_histogram(d_ids, self.T, self.k, self.E, self.d_counts, self.ws, stream)
         self.h_counts.copy_(self.d_counts, non_blocking=True)
         stream.synchronize()  # this path's one host sync
-        rc = self._lib.ramp_cost_model_select(self.E, len(self.fam.cfgs), self._cfgs, self._nt.ctypes.data,
-                                              self._wc.ctypes.data, self._theta.ctypes.data, self._h_ptr, self.flags,
-                                              self._best_ref, None)
+        rc = self._lib.ramp_cost_model_select_rounds(self.E, len(self.fam.cfgs), self._cfgs, self._nt.ctypes.data,
+                                                     self._rounds.ctypes.data, self._wc.ctypes.data, self._theta.ctypes.data,
+                                                     self._h_ptr, self.flags, 4, self._best_ref, None)
         if rc != ramp.OK:
             raise ramp.RampError(rc, ramp.last_error())
         return self._best.value

@@ -12,7 +12,8 @@ from paper_2604_26039_amd import ramp, synth, tuner
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
-ALL_FLAGS = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES | ramp.CM_WAVE_FLOOR | ramp.CM_PAIRS
+ALL_FLAGS = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES | ramp.CM_WAVE_FLOOR | ramp.CM_PAIRS | ramp.CM_ROUNDS
+NO_ROUNDS = ALL_FLAGS & ~ramp.CM_ROUNDS
 
 
 def family(name, T):
@@ -35,7 +36,7 @@ def synthetic_theta(fam, seed):
 
 def device_select(ids_np, T, s, fam, theta, flags, result=None, ticket=1, guard=True):
     n = len(fam.cfgs)
-    table = torch.from_numpy(ramp.select_table_build(fam.cfgs, fam.ntiles, fam.wave_cap, theta, flags)).to(DEV)
+    table = torch.from_numpy(ramp.select_table_build(fam.cfgs, fam.ntiles, fam.wave_cap, theta, flags, rounds=fam.rounds)).to(DEV)
     nbytes = ramp.select_result_bytes(s.E, n)
     if result is None:
         result = torch.zeros(nbytes + (64 if guard else 0), dtype=torch.uint8).pin_memory()
@@ -62,6 +63,10 @@ def oracle_histogram(ids, k, E):
 
 def oracle_select(fam, theta, counts, flags):
     bm = [c.bm for c in fam.cfgs]
+    if flags & ramp.CM_ROUNDS:
+        return oracle.select_rounds(bm, fam.ntiles, fam.wave_cap, theta, counts, fam.rounds,
+                                    distinct_tiles=bool(flags & ramp.CM_DISTINCT_TILES),
+                                    wave_floor=bool(flags & ramp.CM_WAVE_FLOOR), pairs_term=bool(flags & ramp.CM_PAIRS))
     return oracle.select(bm, fam.ntiles, fam.wave_cap, theta, counts,
                          distinct_tiles=bool(flags & ramp.CM_DISTINCT_TILES),
                          wave_floor=bool(flags & ramp.CM_WAVE_FLOOR), pairs_term=bool(flags & ramp.CM_PAIRS))
@@ -77,7 +82,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("name,T,beta", CASES)
-@pytest.mark.parametrize("flags", [ALL_FLAGS, ramp.CM_EQ6])
+@pytest.mark.parametrize("flags", [ALL_FLAGS, NO_ROUNDS, ramp.CM_EQ6])
 def test_select_device_matches_oracle(name, T, beta, flags):
     s, fam = family(name, T)
     ids, _ = synth.routing(T, s, beta, seed=3 * T + 1)
@@ -94,7 +99,8 @@ def test_select_device_matches_oracle(name, T, beta, flags):
         assert np.abs(pred - p_o).max() <= 1e-12 * np.abs(p_o).max()
         assert best == b_o or abs(p_o[best] - p_o[b_o]) <= 1e-12 * abs(p_o[b_o])
     # and the host entry point agrees with both
-    b_h, p_h = ramp.cost_model_select(s.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, ref_counts, want_pred=True, flags=flags)
+    b_h, p_h = ramp.cost_model_select(s.E, fam.cfgs, fam.ntiles, fam.wave_cap, theta, ref_counts, want_pred=True, flags=flags,
+                                      rounds=fam.rounds if flags & ramp.CM_ROUNDS else None)
     assert b_h == b_o and np.array_equal(p_h, p_o)
 
 
@@ -236,7 +242,7 @@ def test_select_and_layer_in_one_hip_graph():
     packed = torch.empty(ramp.pack_bytes(rs), dtype=torch.uint8, device=DEV)
     ramp.pack_weights(rs, Wg, Wu, Wd, packed)
     n = len(cands)
-    table = torch.from_numpy(ramp.select_table_build(cands, fam.ntiles, fam.wave_cap, theta, ALL_FLAGS)).to(DEV)
+    table = torch.from_numpy(ramp.select_table_build(cands, fam.ntiles, fam.wave_cap, theta, ALL_FLAGS, rounds=fam.rounds)).to(DEV)
     result = torch.zeros(ramp.select_result_bytes(s.E, n), dtype=torch.uint8, device=DEV)  # device block: nothing is polled
     sel = torch.full((1,), -1, dtype=torch.int32, device=DEV)
     d_ids = torch.zeros((T, s.k), dtype=torch.int32, device=DEV)

@@ -292,6 +292,63 @@ def test_mi355x_model_fit_and_select_match_oracle():
         ramp.cost_model_fit(wc, g, t, distinct=u, pairs=P, flags=flags | 64)  # unknown flag
 
 
+def test_config_rounds_and_the_rounds_model_against_the_oracle():
+    """ramp_config_rounds by hand (a persistent launch hands out 8 * group_m M-tiles per round, group_m = 32 / N-tiles
+    clamped to 1..8 or the GROUP_M mode; every other kernel one M-tile), ramp_grid's g_r and the fit / select entry
+    points with RAMP_CM_ROUNDS against the oracle."""
+    sh = shape_of("dsv3", 8192)
+    by_key = {c.key(): c for c in ramp.configs(sh)}
+    assert list(ramp.config_rounds(sh, by_key[(256, 256, 32, 8, 4, 1025)])) == [16, 16, 8, 28]     # 32/16 = 2, 32/28 -> 1
+    assert list(ramp.config_rounds(sh, by_key[(272, 256, 32, 8, 4, 1025)])) == [16, 16, 8, 28]
+    assert list(ramp.config_rounds(sh, by_key[(256, 128, 32, 8, 4, 1027)])) == [8, 32, 8, 56]
+    assert list(ramp.config_rounds(sh, ramp.Config(256, 256, 32, 8, 4, 9217))) == [32, 16, 32, 28]   # GROUP_M 4
+    assert list(ramp.config_rounds(sh, ramp.Config(256, 256, 32, 8, 4, 13313))) == [64, 16, 64, 28]  # GROUP_M 8
+    assert list(ramp.config_rounds(sh, by_key[(256, 256, 32, 8, 4, 1)])) == [1, 16, 1, 28]           # not persistent
+    q = shape_of("qwen3", 8192)
+    assert list(ramp.config_rounds(q, ramp.Config(256, 256, 32, 8, 4, 1025))) == [40, 6, 32, 8]      # 32/6 = 5, 32/8 = 4
+    o = shape_of("olmoe", 4096)
+    assert list(ramp.config_rounds(o, ramp.Config(128, 256, 32, 8, 4, 1025))) == [32, 8, 32, 8]
+    with pytest.raises(ramp.RampError):
+        ramp.config_rounds(sh, ramp.Config(256, 0, 32, 8, 4, 1025))
+    for name, T, beta in (("qwen3", 2048, 0.3), ("dsv3", 8192, 1.0), ("olmoe", 64, 0.2)):
+        s = synth.SHAPES[name]
+        rs = shape_of(name, T)
+        cfgs = ramp.configs(rs)
+        n = len(cfgs)
+        nt = np.array([ramp.config_ntiles(rs, c) for c in cfgs], np.int32)
+        wc = np.array([ramp.config_wave_capacity(c) for c in cfgs], np.int32)
+        rounds = np.stack([ramp.config_rounds(rs, c) for c in cfgs])
+        assert np.array_equal(rounds[:, 1] + rounds[:, 3], nt)
+        rng = np.random.default_rng(T)
+        hists = [np.bincount(synth.routing(T, s, beta, seed=i)[0].reshape(-1), minlength=s.E).astype(np.int32) for i in range(12)]
+        g = np.stack([ramp.grid(s.E, cfgs, nt, h)[0] for h in hists], 1)
+        gr = np.stack([ramp.grid(s.E, cfgs, nt, h, rounds=rounds)[3] for h in hists], 1)
+        u = np.stack([ramp.grid(s.E, cfgs, nt, h)[1] for h in hists], 1)
+        P = np.array([int(h.sum()) for h in hists], np.int64)
+        for i, c in enumerate(cfgs):
+            for j, h in enumerate(hists):
+                assert gr[i, j] == oracle.grid_rounds(h, c.bm, rounds[i])
+            if not c.mode & 0x400:
+                assert np.array_equal(gr[i], g[i])
+        t = 20.0 + 3.0 * gr / wc[:, None] + 0.01 * u + 1e-3 * P[None, :] * rng.uniform(0.9, 1.1, (n, len(hists)))
+        flags = ramp.CM_RELATIVE | ramp.CM_DISTINCT_TILES | ramp.CM_WAVE_FLOOR | ramp.CM_PAIRS | ramp.CM_ROUNDS
+        theta = ramp.cost_model_fit(wc, g, t, distinct=u, pairs=P, flags=flags, grid_rounds=gr)
+        for i in range(n):
+            th_o, _ = oracle.fit_cost_model(g[i], t[i], int(wc[i]), distinct=u[i], relative=True, wave_floor=True, pairs=P,
+                                            wave_grid=gr[i])
+            X = oracle.design_matrix(g[i], int(wc[i]), u[i], True, P, gr[i])
+            assert np.allclose(X @ theta[i].astype(np.float64), X @ th_o, rtol=2e-5)
+        for h in hists[:4]:
+            best, pred = ramp.cost_model_select(s.E, cfgs, nt, wc, theta, h, want_pred=True, flags=flags, rounds=rounds)
+            b_o, p_o = oracle.select_rounds([c.bm for c in cfgs], nt, wc, theta, h, rounds, distinct_tiles=True,
+                                            wave_floor=True, pairs_term=True)
+            assert best == b_o and np.array_equal(pred, p_o)
+        with pytest.raises(ramp.RampError):
+            ramp.cost_model_fit(wc, g, t, distinct=u, pairs=P, flags=flags)                  # g_r required with the flag
+        with pytest.raises(ramp.RampError):
+            ramp.cost_model_select(s.E, cfgs, nt, wc, theta, hists[0], flags=flags)         # and the rounds in the selection
+
+
 def test_select_table_layout_and_host_polling():
     """Host pieces of the device-resident dispatch: the table image follows the documented layout and the
     poll / wait calls read a result block without touching the GPU."""
@@ -301,19 +358,26 @@ def test_select_table_layout_and_host_polling():
     nt = np.array([ramp.config_ntiles(sh, c) for c in cfgs], np.int32)
     wc = np.array([ramp.config_wave_capacity(c) for c in cfgs], np.int32)
     theta = np.arange(4 * n, dtype=np.float32).reshape(n, 4)
-    table = ramp.select_table_build(cfgs, nt, wc, theta, flags=10)
-    assert table.nbytes == 128 + 32 * n == ramp.lib().ramp_select_table_bytes(n)
+    rounds = np.stack([ramp.config_rounds(sh, c) for c in cfgs])
+    table = ramp.select_table_build(cfgs, nt, wc, theta, flags=26, rounds=rounds)
+    assert table.nbytes == 128 + 48 * n == ramp.lib().ramp_select_table_bytes(n)
     hdr = table[:128].view(np.int32)
-    assert hdr[1] == n and hdr[3] == 10
+    assert hdr[1] == n and hdr[3] == 26
     bms = list(hdr[4:4 + hdr[2]])
     assert sorted(bms) == sorted({c.bm for c in cfgs}) and len(set(bms)) == len(bms)
-    rows = table[128:].reshape(n, 32)
+    rows = table[128:].reshape(n, 48)
     ints = rows[:, :16].copy().view(np.int32).reshape(n, 4)
     assert [bms[i] for i in ints[:, 0]] == [c.bm for c in cfgs]
     assert np.array_equal(ints[:, 1], nt) and np.array_equal(ints[:, 2], wc)
-    assert np.array_equal(rows[:, 16:].copy().view(np.float32).reshape(n, 4), theta)
+    assert np.array_equal(rows[:, 16:32].copy().view(np.float32).reshape(n, 4), theta)
+    assert np.array_equal(rows[:, 32:].copy().view(np.int32).reshape(n, 4), rounds)
+    # without rounds the rows say "one M-tile per round" (the plain grid)
+    plain = ramp.select_table_build(cfgs, nt, wc, theta, flags=10)[128:].reshape(n, 48)[:, 32:].copy().view(np.int32).reshape(n, 4)
+    assert (plain[:, 0] == 1).all() and (plain[:, 2] == 1).all() and np.array_equal(plain[:, 1], nt)
     with pytest.raises(ramp.RampError):
         ramp.select_table_build(cfgs, nt, np.zeros(n, np.int32), theta)   # wave capacity must be positive
+    with pytest.raises(ramp.RampError):
+        ramp.select_table_build(cfgs, nt, wc, theta, flags=16)            # the rounds flag needs the rounds
     # result block: word (best << 32 | ticket) | n_cfg | 0 | pred | counts
     nbytes = ramp.select_result_bytes(sh.E, n)
     assert nbytes >= 16 + 8 * n + 4 * sh.E and nbytes % 64 == 0

@@ -317,6 +317,73 @@ def test_select_with_wave_floor_and_pairs_matches_brute_force():
         assert p_floor[c] - p_plain[c] == pytest.approx(float(theta[c, 1]) * (max(g / W[c], 1.0) - g / W[c]), abs=1e-9)
 
 
+# ----------------------------------------------------------------------------- whole hand-out rounds in the wave term
+
+def test_grid_rounds_reduces_to_eq1_and_steps_at_whole_rounds():
+    rng = np.random.default_rng(21)
+    for _ in range(20):
+        counts = rng.integers(0, 700, rng.integers(1, 130)) * (rng.random() < 0.9)
+        bm, nt_up, nt_down = int(rng.choice([16, 64, 256, 272])), int(rng.integers(1, 120)), int(rng.integers(1, 60))
+        # rounds of one M-tile: Eq. 1 with ntiles = the N-tiles of both launches
+        assert oracle.grid_rounds(counts, bm, (1, nt_up, 1, nt_down)) == oracle.grid(counts, bm, nt_up + nt_down)
+        r_up, r_down = int(rng.choice([8, 16, 32, 40, 64])), int(rng.choice([8, 16, 32, 40, 64]))
+        g, gr = oracle.grid(counts, bm, nt_up + nt_down), oracle.grid_rounds(counts, bm, (r_up, nt_up, r_down, nt_down))
+        assert g <= gr < g + r_up * nt_up + r_down * nt_down        # rounding up, by less than one round per launch
+        assert gr % np.gcd(r_up * nt_up, r_down * nt_down) == 0
+    # by hand: 39 experts of 420 pairs, bm 256 -> 2 M-tiles each = 78; up-projection 6 N-tiles in rounds of 40 M-tiles
+    # (2 rounds = 80), down-projection 8 N-tiles in rounds of 32 (3 rounds = 96): 80*6 + 96*8
+    assert oracle.grid_rounds([420] * 39, 256, (40, 6, 32, 8)) == 80 * 6 + 96 * 8 == 1248
+    assert oracle.grid_rounds([420] * 39, 256, (32, 6, 32, 8)) == 96 * 14            # the 4 x 8 block shape: one round more
+    assert oracle.grid_rounds([], 256, (40, 6, 32, 8)) == 0 and oracle.grid_rounds([0, 0], 16, (8, 3, 8, 5)) == 0
+    assert oracle.grid_rounds([1], 256, (16, 16, 8, 28)) == 16 * 16 + 8 * 28         # one M-tile still costs one round
+
+
+def test_fit_and_select_with_the_wave_term_on_whole_rounds():
+    W = 256
+    rng = np.random.default_rng(22)
+    mt = rng.integers(1, 400, 25)
+    nt_up, nt_down, r_up, r_down = 16, 28, 16, 8
+    g = (mt * (nt_up + nt_down)).astype(float)
+    gr = (np.ceil(mt / r_up) * r_up * nt_up + np.ceil(mt / r_down) * r_down * nt_down).astype(float)
+    u = rng.integers(8, 256, 25).astype(float) * (nt_up + nt_down)
+    P = rng.integers(8, 70000, 25).astype(float)
+    a, b, c, d = 14.0, 33.0, 0.125, 2.5e-3
+    t = a + b * np.maximum(gr / W, 1.0) + c * u + d * P
+    theta, _ = oracle.fit_cost_model(g, t, W, distinct=u, relative=True, wave_floor=True, pairs=P, wave_grid=gr)
+    assert np.allclose(theta, [a, b, c, d], rtol=1e-7)
+    th_plain, _ = oracle.fit_cost_model(g, t, W, distinct=u, relative=True, wave_floor=True, pairs=P)
+    assert not np.allclose(th_plain, [a, b, c, d], rtol=1e-3)    # the plain grid does not explain the steps
+    # the other columns keep the plain g: as printed (m = g, l = ln(g+1)) with only the wave column on rounds
+    t2 = a + b * gr / W + c * g + d * np.log(g + 1.0)
+    g_small = np.minimum(g, 200.0)                                 # median below one wave -> the log column is on
+    th2, used = oracle.fit_cost_model(g, t2, 10 ** 6, wave_grid=gr)
+    assert used and np.allclose(np.array([1.0, gr[3] / 10 ** 6, g[3], np.log(g[3] + 1.0)]) @ th2, t2[3], rtol=1e-9)
+    # select: rounds of one M-tile give back the plain selection; otherwise brute force
+    n = 10
+    bm = rng.choice([16, 64, 256, 272], n)
+    rounds = np.stack([rng.choice([1, 8, 16, 32, 40], n), rng.integers(1, 40, n), rng.choice([1, 8, 16, 32], n), rng.integers(1, 40, n)], 1)
+    nt = rounds[:, 1] + rounds[:, 3]
+    Wc = rng.choice([256, 512], n)
+    th = (np.abs(rng.normal(0, 1, (n, 4))) * [10, 5, 0.05, 1e-3]).astype(np.float32)
+    for trial in range(5):
+        counts = rng.integers(0, 10 ** (1 + trial % 3), 64) * (rng.random(64) < 0.5)
+        ones = rounds.copy()
+        ones[:, 0] = ones[:, 2] = 1
+        b1, p1 = oracle.select_rounds(bm, nt, Wc, th, counts, ones, distinct_tiles=True, wave_floor=True, pairs_term=True)
+        b0, p0 = oracle.select(bm, nt, Wc, th, counts, distinct_tiles=True, wave_floor=True, pairs_term=True)
+        assert b1 == b0 and np.array_equal(p1, p0)
+        best, pred = oracle.select_rounds(bm, nt, Wc, th, counts, rounds, distinct_tiles=True, wave_floor=True, pairs_term=True)
+        active, pairs = int((counts > 0).sum()), int(counts.sum())
+        exp = []
+        for cfg in range(n):
+            m_tiles = sum(-(-int(x) // int(bm[cfg])) for x in counts)
+            ru, nu, rd, nd = (int(v) for v in rounds[cfg])
+            g_r = -(-m_tiles // ru) * ru * nu + -(-m_tiles // rd) * rd * nd
+            aa, bb, cc, dd = (float(np.float32(v)) for v in th[cfg])
+            exp.append(aa + bb * max(g_r / Wc[cfg], 1.0) + cc * (active * int(nt[cfg])) + dd * pairs)
+        assert np.allclose(pred, exp, rtol=1e-14) and best == int(np.argmin(exp))
+
+
 # ----------------------------------------------------------------------------- five-term ablation (Sec. 5.3)
 
 def test_five_term_fit_is_a_quadratic_polynomial_fit_when_the_log_is_off():
