@@ -376,7 +376,7 @@ def main():
 
     if args.heldout > 0:
         rng = np.random.default_rng(7)
-        regs, regs_eq6 = [], []
+        regs, regs_eq6, regs_nr = [], [], []
         t0 = time.time()
         for h in range(args.heldout):
             T = int(rng.choice(sweep["T"][1:]))
@@ -385,13 +385,16 @@ def main():
             times = np.array([tuner.time_config(layers, c, p, warmup=2, iters=8, budget_ms=30.0) for c in fam.cfgs])
             regs.append(times[tuner.select(fam, theta, p.counts, dispatch_flags)] / times.min() - 1.0)
             regs_eq6.append(times[tuner.select(fam, thetas["eq6"], p.counts, MODELS["eq6"])] / times.min() - 1.0)
+            regs_nr.append(times[tuner.select(fam, thetas["all_but_rounds"], p.counts, MODELS["all_but_rounds"])] / times.min() - 1.0)
             if h % 20 == 19:
                 log(f"[bench] held-out {h + 1}/{args.heldout}: mean regret so far {100 * np.mean(regs):.2f}%")
         summary["heldout_histograms"] = dict(n=args.heldout, mean_regret=float(np.mean(regs)), max_regret=float(np.max(regs)),
                                              median_regret=float(np.median(regs)),
-                                             mean_regret_eq6_as_printed=float(np.mean(regs_eq6)))
+                                             mean_regret_eq6_as_printed=float(np.mean(regs_eq6)),
+                                             mean_regret_all_but_rounds=float(np.mean(regs_nr)),
+                                             max_regret_all_but_rounds=float(np.max(regs_nr)))
         log(f"[bench] held-out histograms {time.time() - t0:.1f}s: mean {100 * np.mean(regs):.2f}% max {100 * np.max(regs):.2f}% "
-            f"(Eq. 6 as printed: mean {100 * np.mean(regs_eq6):.2f}%)")
+            f"(Eq. 6 as printed: mean {100 * np.mean(regs_eq6):.2f}%; all flags but rounds: mean {100 * np.mean(regs_nr):.2f}% max {100 * np.max(regs_nr):.2f}%)")
 
     # ------------------------------------------------------------------ headline: K timed steps of the whole path
     p = tuner.Point(T_head, beta_head, seed=4242).materialise(s)

@@ -67,6 +67,12 @@ struct PingPongTraits {
     static_assert(LDS_BYTES <= kLdsBytesPerCU, "tile does not fit in LDS");
 };
 
+// Read-only table entry at a wave-uniform address that no launch in flight writes.
+__device__ __forceinline__ int32_t load_uniform_i32(const int32_t *p)
+{
+    return *(const __attribute__((address_space(4))) int32_t *)(p);
+}
+
 // Wait until at most n vector-memory operations of this wavefront are outstanding (n wave-uniform).
 __device__ __forceinline__ void wait_vmcnt_upto(int n)
 {
@@ -122,6 +128,10 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     auto next_tile = [&](int id, int &n_tile, int &m_tile) __attribute__((always_inline)) -> int {
         for (; id < a.total_tiles; id += (int)gridDim.x) {
             tile_of_id(a, id, n_tile, m_tile);
+            // wave-uniform by construction; saying so lets the per-tile table reads below be scalar loads, which do not
+            // count on vmcnt (a vector load would have to be waited for in order, behind every LDS-direct load in flight)
+            n_tile = __builtin_amdgcn_readfirstlane(n_tile);
+            m_tile = __builtin_amdgcn_readfirstlane(m_tile);
             if (m_tile < m_tiles) return id;
         }
         return -1;
@@ -129,25 +139,20 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
 
     // ---- global element offsets of this lane's loads for k-slice 0 of a tile ----
     auto tile_offsets = [&](int n_tile, int m_tile, uint32_t *xo, uint32_t *wo, const uint16_t *&wexp, int &rows) __attribute__((always_inline)) {
-        rows = a.tile_rows[m_tile];  // real rows of the tile (they come first, the sentinel padding after them)
-        const int e = a.tile_expert[m_tile];
+        // the two per-tile table entries (written by the align launch before this one) through the constant address
+        // space: m_tile is wave-uniform, so these become scalar loads, which do not count on vmcnt
+        rows = load_uniform_i32(a.tile_rows + m_tile);  // real rows of the tile (they come first, the sentinel padding after them)
+        const int e = load_uniform_i32(a.tile_expert + m_tile);
         wexp = a.wpacked + (size_t)e * a.expert_stride;
         const int f0 = n_tile * FEAT_PER_TILE;
         if (PT::ROWX) {
-            // all index loads first, then the arithmetic (token = pair / k by multiplication)
-            int pair[TSLOTS];
+            // only the index loads here; token_offsets() turns them into offsets when the first load of the tile is
+            // issued, most of a tile later: nothing waits for these loads while the LDS-direct loads are in flight
 #pragma unroll
             for (int t = 0; t < TSLOTS; ++t) {
                 const int tr = (wave + t * NWAVE) * 8 + (lane >> 3);
                 // (the surplus load slots of a tail tile never fetch rows, see token_loads: any slot of the tile will do)
-                pair[t] = a.sorted[m_tile * BM + (PT::X_BLOCKS % NWAVE == 0 || tr < BM ? tr : BM - 1)];
-            }
-#pragma unroll
-            for (int t = 0; t < TSLOTS; ++t) {
-                const int tr = (wave + t * NWAVE) * 8 + (lane >> 3);  // 8 rows per 1 KB block, 8 lanes (128 B) per row
-                const uint32_t p = (pair[t] < a.P) ? (uint32_t)pair[t] : 0u;
-                const uint32_t row = (uint32_t)(((unsigned long long)p * a.topk_magic) >> 40);
-                xo[t] = row * (uint32_t)K + (uint32_t)(((lane & 7) ^ ((tr >> 1) & 7)) * 8);
+                xo[t] = (uint32_t)a.sorted[m_tile * BM + (PT::X_BLOCKS % NWAVE == 0 || tr < BM ? tr : BM - 1)];
             }
         } else {
 #pragma unroll
@@ -170,6 +175,17 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
                 base = (uint32_t)(f0 / 16 + rb) * (uint32_t)KST * kFragElems;
             }
             wo[s] = base + (uint32_t)ks * kFragElems + (uint32_t)lane * 8;
+        }
+    };
+    // pair indices (as loaded by tile_offsets) -> element offsets of the token rows (token = pair / k by multiplication)
+    auto token_offsets = [&](uint32_t *xo) __attribute__((always_inline)) {
+        if (!PT::ROWX) return;
+#pragma unroll
+        for (int t = 0; t < TSLOTS; ++t) {
+            const int tr = (wave + t * NWAVE) * 8 + (lane >> 3);  // 8 rows per 1 KB block, 8 lanes (128 B) per row
+            const uint32_t p = (xo[t] < (uint32_t)a.P) ? xo[t] : 0u;
+            const uint32_t row = (uint32_t)(((unsigned long long)p * a.topk_magic) >> 40);
+            xo[t] = row * (uint32_t)K + (uint32_t)(((lane & 7) ^ ((tr >> 1) & 7)) * 8);
         }
     };
     constexpr uint32_t XSTEP = PT::ROWX ? (uint32_t)PT::XK : (uint32_t)(KS * kFragElems);
@@ -302,6 +318,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     if (id < 0) return;
     int rows_cur = 0, rows_next = 0;
     tile_offsets(n_tile, m_tile, xoff, woff, wexp_w, rows_cur);
+    token_offsets(xoff);
     nb_valid = blocks_valid(rows_cur);
     tail_valid = TAILB && rows_cur > BMAIN;
     txv = token_loads(rows_cur);
@@ -343,19 +360,21 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         // stage 2: destination pair and router weight of this lane's token rows
         int out_pair[NB];
         float out_wgt[NB];
-        if (STAGE == 2) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int tr = (nb * WM + wm) * 16 + r16;
-                out_pair[nb] = (nb < nb_valid) ? a.sorted[m_tile * BM + tr] : a.P;
-                out_wgt[nb] = (out_pair[nb] < a.P) ? a.topk_w[out_pair[nb]] : 0.0f;
-            }
-        }
+        // All index loads are issued together and unconditionally (the padding slots of a tile hold the sentinel P), then
+        // all weight loads: two round trips per tile.  One load, one wait, one dependent load per token block would be
+        // sixteen, each of them also draining the LDS-direct loads in flight (vmcnt counts in order).
         int tail_pair = a.P;
         float tail_wgt = 0.0f;
-        if (STAGE == 2 && TAILB && tail_valid) {
-            tail_pair = a.sorted[m_tile * BM + BMAIN + r16];
-            tail_wgt = (tail_pair < a.P) ? a.topk_w[tail_pair] : 0.0f;
+        if (STAGE == 2) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) out_pair[nb] = a.sorted[m_tile * BM + (nb * WM + wm) * 16 + r16];
+            if (TAILB) tail_pair = a.sorted[m_tile * BM + BMAIN + r16];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) out_wgt[nb] = a.topk_w[out_pair[nb] < a.P ? out_pair[nb] : 0];
+            if (TAILB) tail_wgt = a.topk_w[tail_pair < a.P ? tail_pair : 0];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) out_wgt[nb] = (out_pair[nb] < a.P) ? out_wgt[nb] : 0.0f;
+            if (TAILB) tail_wgt = (tail_pair < a.P) ? tail_wgt : 0.0f;
         }
 
         // mode_c: 1 = every token block of the wavefront is real, 0 = some are, 2 = none (a ragged tile that ends
@@ -377,7 +396,12 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             }
             if (kt == KT - (NX - 1) * XS) {
 #pragma unroll
-                for (int t = 0; t < TSLOTS; ++t) xoff[t] = xoff_n[t];
+                for (int t = 0; t < TSLOTS; ++t) {
+                    xoff[t] = xoff_n[t];
+                    // keeps the arithmetic (and with it the wait for the index loads) here instead of in front of the slice loop
+                    if (PT::ROWX) asm volatile("" : "+v"(xoff[t]));
+                }
+                token_offsets(xoff);
                 txv = txv_n;
             }
             bool x_issued = false;
