@@ -113,7 +113,7 @@ __device__ void block_scan_and_emit(int n_e, int E, int bm, int cap, int dropped
 // cursor[e] + (#pairs of e before p in this chunk); cursors then advance past the chunk.
 // wcnt: LDS [NW*E] words tagged with `stamp` so they never need re-zeroing.
 __device__ void block_scatter_chunk(const int32_t *ids, int base, int P, int E, int *cursor, unsigned *wcnt,
-                                    unsigned stamp, int32_t *sorted)
+                                    unsigned stamp, int32_t *sorted, AlignSlotWeights slot_weights)
 {
     const int ebits = 32 - __clz((E - 1) | 1);  // bits that tell the experts apart
     const int lane = lane_id(), wv = threadIdx.x >> 6;
@@ -146,6 +146,7 @@ __device__ void block_scatter_chunk(const int32_t *ids, int base, int P, int E, 
             if (w < wv && (v >> 8) == stamp) before += (int)(v & 0xffu);
         }
         sorted[cursor[e] + before + rank] = p;
+        if (slot_weights.slot_w) slot_weights.slot_w[cursor[e] + before + rank] = slot_weights.topk_w[p];
     }
     __syncthreads();
     for (int x = threadIdx.x; x < E; x += NT) {
@@ -175,7 +176,8 @@ size_t lds_ints(int E) { return (size_t)E + (E + 1) + NW + 1 + (size_t)NW * E; }
 __global__ __launch_bounds__(NT) void align_single_kernel(const int32_t *ids, int P, int E, int bm, int cap,
                                                           int32_t *sorted, int32_t *tile_expert, int32_t *tile_rows,
                                                           int32_t *counts, int32_t *meta, int scatter,
-                                                          const int32_t *pred, int pred_value)
+                                                          const int32_t *pred, int pred_value,
+                                                          AlignSlotWeights slot_weights)
 {
     if (launch_deselected(pred, pred_value)) return;
     extern __shared__ int lds[];
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(NT) void align_single_kernel(const int32_t *ids, in
     __syncthreads();
     unsigned stamp = 1;
     for (int base = 0; base < P; base += NT, ++stamp)
-        block_scatter_chunk(ids, base, P, E, cursor, wcnt, stamp, sorted);
+        block_scatter_chunk(ids, base, P, E, cursor, wcnt, stamp, sorted, slot_weights);
 }
 
 // ---- up to 64 pairs (decode-sized calls): one wavefront, one pair per lane, no workgroup-wide steps ----
@@ -212,14 +214,15 @@ constexpr int kAlignTinyMaxCap = 4096;
 __global__ __launch_bounds__(kWave) void align_tiny_kernel(const int32_t *ids, int P, int E, int bm, int cap,
                                                            int32_t *sorted, int32_t *tile_expert, int32_t *tile_rows,
                                                            int32_t *counts, int32_t *meta, const int32_t *pred,
-                                                           int pred_value)
+                                                           int pred_value, AlignSlotWeights slot_weights)
 {
     if (launch_deselected(pred, pred_value)) return;
     __shared__ int n_lds[kAlignMaxE];
     __shared__ int toff[kAlignMaxE + 1];
     int e, rank;
     tiny_align_wavefront(ids, P, E, bm, (int)threadIdx.x, n_lds, toff, e, rank);
-    tiny_align_emit(P, E, bm, cap, (int)threadIdx.x, n_lds, toff, e, rank, ids, sorted, tile_expert, tile_rows, counts, meta);
+    tiny_align_emit(P, E, bm, cap, (int)threadIdx.x, n_lds, toff, e, rank, ids, sorted, tile_expert, tile_rows, counts, meta,
+                    slot_weights);
 }
 
 // ---- several workgroups: histogram per chunk -> scan -> scatter ----
@@ -282,7 +285,7 @@ __global__ __launch_bounds__(NT) void align_scan_scatter_kernel(const int32_t *i
                                                                 const int32_t *block_dropped, int32_t *sorted,
                                                                 int32_t *tile_expert, int32_t *tile_rows,
                                                                 int32_t *counts, int32_t *meta, const int32_t *pred,
-                                                                int pred_value)
+                                                                int pred_value, AlignSlotWeights slot_weights)
 {
     if (launch_deselected(pred, pred_value)) return;
     extern __shared__ int lds[];
@@ -314,7 +317,7 @@ __global__ __launch_bounds__(NT) void align_scan_scatter_kernel(const int32_t *i
     const int end = min(P, begin + kAlignChunk);
     unsigned stamp = 1;
     for (int base = begin; base < end; base += NT, ++stamp)
-        block_scatter_chunk(ids, base, end, E, cursor, wcnt, stamp, sorted);
+        block_scatter_chunk(ids, base, end, E, cursor, wcnt, stamp, sorted, slot_weights);
 }
 
 int num_blocks(int P) { return (P + kAlignChunk - 1) / kAlignChunk; }
@@ -338,7 +341,8 @@ int allow_lds(Kernel kernel, size_t bytes)
 // scatter = 0: histogram only (sorted / tile_expert / meta untouched, may be NULL)
 static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
                              int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes,
-                             hipStream_t stream, int scatter, const int32_t *pred = nullptr, int pred_value = 0)
+                             hipStream_t stream, int scatter, const int32_t *pred = nullptr, int pred_value = 0,
+                             AlignSlotWeights slot_weights = {nullptr, nullptr})
 {
     if (T < 0 || k < 0 || E <= 0 || E > kAlignMaxE || bm < 1 || bm > 1024) {
         set_error("align: bad sizes T=%d k=%d E=%d bm=%d (need E<=%d, 1<=bm<=1024)", T, k, E, bm, kAlignMaxE);
@@ -357,14 +361,14 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
     const int cap = scatter ? (int)ramp_align_capacity(T, k, E, bm) : 0;
     if (scatter && P <= kAlignTinyMaxP && cap <= kAlignTinyMaxCap) {
         hipLaunchKernelGGL(align_tiny_kernel, dim3(1), dim3(kWave), 0, stream, ids, P, E, bm, cap, sorted, tile_expert,
-                           tile_rows, counts, meta, pred, pred_value);
+                           tile_rows, counts, meta, pred, pred_value, slot_weights);
         return check_launch("align_tiny_kernel");
     }
     if (P <= kAlignSingleMaxP) {
         size_t lds = lds_ints(E) * sizeof(int);
         if (int rc = allow_lds(align_single_kernel, lds)) return rc;
         hipLaunchKernelGGL(align_single_kernel, dim3(1), dim3(NT), lds, stream, ids, P, E, bm, cap, sorted,
-                           tile_expert, tile_rows, counts, meta, scatter, pred, pred_value);
+                           tile_expert, tile_rows, counts, meta, scatter, pred, pred_value, slot_weights);
         return check_launch("align_single_kernel");
     }
     const int B = num_blocks(P);
@@ -388,7 +392,8 @@ static int launch_align_impl(const int32_t *ids, int T, int k, int E, int bm, in
     const size_t scatter_lds = ((size_t)(E + 1) + NW + E + (size_t)NW * E) * sizeof(int);
     if (int rc2 = allow_lds(align_scan_scatter_kernel, scatter_lds)) return rc2;
     hipLaunchKernelGGL(align_scan_scatter_kernel, dim3(B), dim3(NT), scatter_lds, stream, ids, P, B, E, bm, cap,
-                       block_counts, block_dropped, sorted, tile_expert, tile_rows, counts, meta, pred, pred_value);
+                       block_counts, block_dropped, sorted, tile_expert, tile_rows, counts, meta, pred, pred_value,
+                       slot_weights);
     return check_launch("align_scan_scatter_kernel");
 }
 
@@ -412,10 +417,14 @@ int launch_chunk_histograms(const int32_t *ids, int P, int E, void *ws, size_t w
 
 int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
                  int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream,
-                 const int32_t *pred, int pred_value)
+                 const int32_t *pred, int pred_value, AlignSlotWeights slot_weights)
 {
+    if ((slot_weights.slot_w != nullptr) != (slot_weights.topk_w != nullptr)) {
+        set_error("align: slot weights need both the router weights and the output");
+        return RAMP_EINVAL;
+    }
     return launch_align_impl(ids, T, k, E, bm, sorted, tile_expert, tile_rows, counts, meta, ws, ws_bytes, stream, 1,
-                             pred, pred_value);
+                             pred, pred_value, slot_weights);
 }
 
 }  // namespace ramp

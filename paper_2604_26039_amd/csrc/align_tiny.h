@@ -79,7 +79,8 @@ __device__ __forceinline__ void tiny_align_tile(int m, int E, int bm, const int 
 // Writes the align result to global memory (same wavefront, after tiny_align_wavefront).
 __device__ __forceinline__ void tiny_align_emit(int P, int E, int bm, int cap, int lane, const int *n_lds, const int *toff, int e,
                                                 int rank, const int32_t *ids, int32_t *sorted, int32_t *tile_expert,
-                                                int32_t *tile_rows, int32_t *counts, int32_t *meta)
+                                                int32_t *tile_rows, int32_t *counts, int32_t *meta,
+                                                AlignSlotWeights slot_weights = {nullptr, nullptr})
 {
     for (int s = lane; s < cap; s += kWave) sorted[s] = P;
     const int dropped = __popcll(__ballot(lane < P && e < 0));
@@ -101,7 +102,10 @@ __device__ __forceinline__ void tiny_align_emit(int P, int E, int bm, int cap, i
     // the sentinel fill above was done by this wavefront: order it before the scatter of the same addresses
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    if (e >= 0) sorted[toff[e] + rank] = lane;
+    if (e >= 0) {
+        sorted[toff[e] + rank] = lane;
+        if (slot_weights.slot_w) slot_weights.slot_w[toff[e] + rank] = slot_weights.topk_w[lane];
+    }
     (void)ids;
 }
 

@@ -145,7 +145,7 @@ struct ProbeScope {
 constexpr size_t kPairRowsBf16Elems = (size_t)8 << 20;
 
 struct Workspace {
-    size_t sorted, tile_expert, tile_rows, counts, meta, align_ws, a_buf, y_buf, total;
+    size_t sorted, tile_expert, tile_rows, counts, meta, align_ws, a_buf, y_buf, slot_w, total;
     size_t cap, align_ws_bytes;
 };
 
@@ -168,6 +168,8 @@ Workspace workspace_layout(const ramp_shape &s, const ramp_config &c)
     w.align_ws = take(w.align_ws_bytes);
     w.a_buf = take(align_up(w.cap, 16) * (size_t)s.I * 2);  // fragment-major: whole blocks of 16 slots
     w.y_buf = take((size_t)s.T * s.k * s.H * 4);
+    // router weight per sorted slot, for the kernels that read it by slot (persistent ping-pong down-projection)
+    w.slot_w = (c.mode & kModePingPong) ? take(w.cap * 4) : off;
     w.total = off;
     return w;
 }
@@ -498,13 +500,16 @@ int enqueue_projections(const ramp_shape &s, const ramp_config &cfg, const Kerne
     int rc;
     {
         ProbeScope probe(1, st);
+        AlignSlotWeights sw = {nullptr, nullptr};
+        if (cfg.mode & kModePingPong) sw = AlignSlotWeights{topk_w, reinterpret_cast<float *>(base + w.slot_w)};
         rc = launch_align(topk_ids, s.T, s.k, s.E, cfg.bm, sorted, tile_expert, tile_rows, counts, meta, base + w.align_ws,
-                          w.align_ws_bytes, st, pred, pred_value);
+                          w.align_ws_bytes, st, pred, pred_value, sw);
     }
     if (rc) return rc;
 
     GemmArgs g = {};
     g.sorted = sorted;
+    g.slot_w = (cfg.mode & kModePingPong) ? reinterpret_cast<const float *>(base + w.slot_w) : nullptr;
     g.tile_expert = tile_expert;
     g.tile_rows = tile_rows;
     g.topk_magic = topk_magic_of(s.k);

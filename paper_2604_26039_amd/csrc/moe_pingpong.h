@@ -360,9 +360,11 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         // stage 2: destination pair and router weight of this lane's token rows
         int out_pair[NB];
         float out_wgt[NB];
-        // All index loads are issued together and unconditionally (the padding slots of a tile hold the sentinel P), then
-        // all weight loads: two round trips per tile.  One load, one wait, one dependent load per token block would be
-        // sixteen, each of them also draining the LDS-direct loads in flight (vmcnt counts in order).
+        // All index and weight loads are issued together and unconditionally (the padding slots of a tile hold the
+        // sentinel P; the weights are read by slot, from the copy the align step made, not through the pair index), and
+        // nothing uses them before the epilogue: no round trip on the way into the tile.  One load, one wait, one
+        // dependent load per token block would be sixteen round trips, each of them also draining the LDS-direct loads
+        // in flight (vmcnt counts in order).
         int tail_pair = a.P;
         float tail_wgt = 0.0f;
         if (STAGE == 2) {
@@ -370,11 +372,8 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             for (int nb = 0; nb < NB; ++nb) out_pair[nb] = a.sorted[m_tile * BM + (nb * WM + wm) * 16 + r16];
             if (TAILB) tail_pair = a.sorted[m_tile * BM + BMAIN + r16];
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) out_wgt[nb] = a.topk_w[out_pair[nb] < a.P ? out_pair[nb] : 0];
-            if (TAILB) tail_wgt = a.topk_w[tail_pair < a.P ? tail_pair : 0];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) out_wgt[nb] = (out_pair[nb] < a.P) ? out_wgt[nb] : 0.0f;
-            if (TAILB) tail_wgt = (tail_pair < a.P) ? tail_wgt : 0.0f;
+            for (int nb = 0; nb < NB; ++nb) out_wgt[nb] = a.slot_w[m_tile * BM + (nb * WM + wm) * 16 + r16];
+            if (TAILB) tail_wgt = a.slot_w[m_tile * BM + BMAIN + r16];
         }
 
         // mode_c: 1 = every token block of the wavefront is real, 0 = some are, 2 = none (a ragged tile that ends

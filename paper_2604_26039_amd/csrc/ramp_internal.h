@@ -34,9 +34,16 @@ constexpr int kAlignChunk = 1024;     // pairs per workgroup in the multi-workgr
 constexpr int kAlignSingleMaxP = 2048; // up to this many pairs one workgroup does everything
 constexpr int kAlignMaxE = 1024;
 
+// Optional second output of the scatter: slot_w[s] = topk_w[sorted[s]] for the slots that hold a pair (the others are
+// left as they are), so that a kernel can read the router weight of a slot without first waiting for its pair index.
+struct AlignSlotWeights {
+    const float *topk_w;
+    float *slot_w;
+};
+
 int launch_align(const int32_t *ids, int T, int k, int E, int bm, int32_t *sorted, int32_t *tile_expert,
                  int32_t *tile_rows, int32_t *counts, int32_t *meta, void *ws, size_t ws_bytes, hipStream_t stream,
-                 const int32_t *pred = nullptr, int pred_value = 0);
+                 const int32_t *pred = nullptr, int pred_value = 0, AlignSlotWeights slot_weights = {nullptr, nullptr});
 
 // ---- packed weights ----
 // One fragment = 16 weight rows x 32 k-values = 512 bf16 = 1 KB, stored in the lane order
@@ -83,6 +90,7 @@ struct GemmArgs {
     unsigned long long topk_magic;  // ceil(2^40 / k): pair / k == (pair * topk_magic) >> 40 for pair < 2^30
     const int32_t *meta;        // [4]
     const float *topk_w;        // stage 2: [P]
+    const float *slot_w;        // stage 2, ping-pong kernels: router weight of every sorted slot that holds a pair [cap]
     uint16_t *a_out;            // stage 1: A [cap,I]
     float *y_out;               // stage 2: Y [P,H] (fp32, or bf16 in the same buffer when y_bf16 != 0)
     int y_bf16;                 // large batches keep the per-pair rows in bf16 to halve their HBM traffic
