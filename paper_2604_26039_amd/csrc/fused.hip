@@ -164,12 +164,12 @@ Workspace workspace_layout(const ramp_shape &s, const ramp_config &c)
     w.tile_rows = take((w.cap / (size_t)c.bm) * 4);
     w.counts = take((size_t)s.E * 4);
     w.meta = take(16);
+    // router weight per sorted slot, for the kernels that read it by slot (persistent ping-pong down-projection)
+    w.slot_w = (c.mode & kModePingPong) ? take(w.cap * 4) : off;
     w.align_ws_bytes = ramp_align_workspace_bytes(s.T, s.k, s.E);
     w.align_ws = take(w.align_ws_bytes);
     w.a_buf = take(align_up(w.cap, 16) * (size_t)s.I * 2);  // fragment-major: whole blocks of 16 slots
-    w.y_buf = take((size_t)s.T * s.k * s.H * 4);
-    // router weight per sorted slot, for the kernels that read it by slot (persistent ping-pong down-projection)
-    w.slot_w = (c.mode & kModePingPong) ? take(w.cap * 4) : off;
+    w.y_buf = take((size_t)s.T * s.k * s.H * 4);  // last: the device-selected variant shares one copy between candidates
     w.total = off;
     return w;
 }
