@@ -146,7 +146,7 @@ def test_expert_row_counts_around_the_tile_and_tail_block_sizes():
     between its wavefront rows), 272 (that tile full), one row more or less, two tiles, an empty expert, fewer rows
     than a block.  top-1 routing makes the counts exact; every element against the oracle on every ping-pong
     configuration."""
-    counts = [256, 257, 260, 271, 272, 273, 288, 529, 0, 15, 255, 544]
+    counts = [256, 257, 260, 271, 272, 273, 287, 288, 289, 304, 529, 0, 15, 255, 544, 561, 577]
     shape = synth.Shape("edge", 256, 128, len(counts), 1)
     T = sum(counts)
     L = Layer(shape, T, seed=11, x_std=1.5)
