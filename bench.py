@@ -120,6 +120,33 @@ def mfma_ceiling(torch, ramp, dev, rounds=20000):
     return out
 
 
+def vendor_gemm_reference(torch, s, P, dev, iters=10):
+    """Context only, never part of the timed path: what the vendor library's dense bf16 GEMM (torch.matmul) sustains on
+    this box on N(0,1) operands, at the up-projection's dimensions with the pairs as one dense batch (no gather, no
+    expert grouping, no SwiGLU): the practical ceiling of an MFMA-bound kernel under the chip's power limit."""
+    try:
+        M, N, K = int(min(max(P, 4096), 16384)), 2 * s.I, s.H
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(5)
+        a = torch.randn(M, K, generator=gen, device=dev).to(torch.bfloat16)
+        b = torch.randn(N, K, generator=gen, device=dev).to(torch.bfloat16)
+        for _ in range(3):
+            c = a @ b.t()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(iters):
+            c = a @ b.t()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / iters
+        del a, b, c
+        return dict(shape_mnk=[M, N, K], us=us, pflops=2.0 * M * N * K / us * 1e-9, operands="N(0,1) bf16",
+                    what="torch.matmul (vendor GEMM library), dense, reference only")
+    except Exception as exc:  # a missing or failing vendor library must not fail the benchmark
+        return dict(error=str(exc)[:200])
+
+
 def fp8_rows(torch, ramp, synth, tuner, rows, iters, dev, log_fn):
     """W8A8 FP8 variant: exhaustive pass over its tile family at each point (one layer set per model shape),
     against the FP8 roofline (weights one byte each, 5.0 PFLOP/s)."""
@@ -314,6 +341,7 @@ def main():
             if p.beta == 1.0 or p.beta == sweep["beta"][0]:
                 static_of_T.setdefault(p.T, int(np.argmin(t_ev[:, j])))
         regrets = {name: [] for name in MODELS}
+        regrets_h2h = []
         abl_regrets = {k: [] for k in ABLATION}
         regrets5 = {name: [] for name in theta5}
         speedups = {}
@@ -332,6 +360,19 @@ def main():
                 regrets5[name].append(t_ev[tuner.select5(fam, th5, p.counts, MODELS[name]), j] / t_ev[best, j] - 1.0)
             chosen = picks[DISPATCH]
             reg = regrets[DISPATCH][-1]
+            # The minimum over all configurations of one noisy timing each is biased low (the winner is partly the luckiest
+            # measurement), which inflates the regret of near-ties.  Second figure: the three fastest of the sweep and the
+            # dispatched configuration timed again in alternation, regret against the fastest of those medians.
+            reg_h2h = 0.0
+            if chosen != best:
+                cand = list(dict.fromkeys([chosen] + [int(i) for i in np.argsort(t_ev[:, j])[:3]]))
+                again = {c: [] for c in cand}
+                for _ in range(3):
+                    for c in cand:
+                        again[c].append(tuner.time_config(layers, fam.cfgs[c], p, warmup=2, iters=min(args.iters, 10), budget_ms=40.0))
+                med = {c: float(np.median(v)) for c, v in again.items()}
+                reg_h2h = med[chosen] / min(med.values()) - 1.0
+            regrets_h2h.append(reg_h2h)
             hot_us = tuner.time_config(layers, fam.cfgs[chosen], p, warmup=3, iters=min(args.iters, 20), budget_ms=60.0, hot=True)
             spd = t_ev[st, j] / t_ev[chosen, j]
             speedups.setdefault(str(p.beta), []).append(spd)
@@ -339,7 +380,8 @@ def main():
             bound = "hbm" if t_hbm >= t_mfma else "mfma"
             frac = max(t_hbm, t_mfma) / t_ev[chosen, j]
             row = dict(T=p.T, beta=p.beta, beta_entropy=tuner.entropy_beta(p.counts), best_us=t_ev[best, j],
-                       ra_us=t_ev[chosen, j], ra_hot_us=hot_us, static_us=t_ev[st, j], regret=reg, regret_eq6=regrets["eq6"][-1],
+                       ra_us=t_ev[chosen, j], ra_hot_us=hot_us, static_us=t_ev[st, j], regret=reg, regret_remeasured=reg_h2h,
+                       regret_eq6=regrets["eq6"][-1],
                        ra_over_static=spd, bound=bound, roofline_frac=frac, roofline_frac_best=max(t_hbm, t_mfma) / t_ev[best, j],
                        tflops=flops / t_ev[chosen, j] * 1e-6, gbs=nbytes / t_ev[chosen, j] * 1e-3,
                        best_cfg=fam.cfgs[best].key(), ra_cfg=fam.cfgs[chosen].key(), static_cfg=fam.cfgs[st].key(),
@@ -353,6 +395,7 @@ def main():
         summary = dict(dispatch_model=DISPATCH,
                        mean_regret=float(np.mean(regrets[DISPATCH])), max_regret=float(np.max(regrets[DISPATCH])),
                        median_regret=float(np.median(regrets[DISPATCH])),
+                       mean_regret_remeasured=float(np.mean(regrets_h2h)), max_regret_remeasured=float(np.max(regrets_h2h)),
                        mean_regret_eq6_as_printed=float(np.mean(regrets["eq6"])),
                        max_regret_eq6_as_printed=float(np.max(regrets["eq6"])),
                        model_variants={name: dict(flags=int(MODELS[name]), mean_regret=float(np.mean(v)), max_regret=float(np.max(v)))
@@ -365,7 +408,8 @@ def main():
                        best_over_static_geomean_skewed=geomean([r["static_us"] / r["best_us"] for r in skew]),
                        paper_context=dict(mean_regret=0.0093, ra_over_static=1.22, hardware="H200 FP8"))
         log(f"[bench] sweep {time.time() - t0:.1f}s: mean regret {100 * summary['mean_regret']:.2f}% "
-            f"(median {100 * summary['median_regret']:.2f}%, max {100 * summary['max_regret']:.2f}%); RA/static geomean on skewed points "
+            f"(median {100 * summary['median_regret']:.2f}%, max {100 * summary['max_regret']:.2f}%; top three and the pick timed again: "
+            f"mean {100 * summary['mean_regret_remeasured']:.2f}%, max {100 * summary['max_regret_remeasured']:.2f}%); RA/static geomean on skewed points "
             f"{summary['ra_over_static_geomean_skewed']:.3f}x (exhaustive ceiling {summary['best_over_static_geomean_skewed']:.3f}x), "
             f"worst uniform point {summary['ra_over_static_min_uniform']:.3f}x")
         log("[bench] mean / max regret by model variant: " + "; ".join(
@@ -522,6 +566,9 @@ def main():
     ceiling = mfma_ceiling(torch, ramp, dev)
     log(f"[bench] register-resident MFMA loop: {ceiling['zeros_operands_pflops']:.2f} PFLOP/s on zeros, "
         f"{ceiling['normal_operands_pflops']:.2f} PFLOP/s on N(0,1) bf16 operands (nominal peak {MFMA_PEAK_PFLOPS})")
+    ceiling["vendor_gemm"] = vendor_gemm_reference(torch, s, T_head * s.k, dev)
+    if "pflops" in ceiling["vendor_gemm"]:
+        log(f"[bench] vendor dense GEMM {ceiling['vendor_gemm']['shape_mnk']} on N(0,1) bf16 operands: {ceiling['vendor_gemm']['pflops']:.2f} PFLOP/s (reference only)")
     rec = RECORDED_TRAFFIC.get((args.model, T_head, str(beta_head)))
     if rec and tuple(cfg_head.key()[:5]) != rec[1]:
         rec = None
