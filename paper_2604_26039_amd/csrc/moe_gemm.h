@@ -200,6 +200,29 @@ __device__ __forceinline__ void tile_of_id(const GemmArgs &a, int id, int &n_til
     m_tile = (mb * 8 + xcd) * a.group_m + dm;
 }
 
+// The same map for the persistent kernels, whose workgroup c of an XCD walks slots c, c + 32, ...  With the static map
+// a workgroup gets the same position of every block and an XCD every eighth M-tile; where the experts have a full
+// M-tile followed by a ragged one (two tiles per expert: block positions and XCDs alternate full, ragged) half of the
+// workgroups, or half of the XCDs, then only ever get ragged tiles, finish early and run ahead of the siblings they
+// share weights with.  So the position inside the block moves on by one per block, and the XCD -> M-tile assignment
+// inside a round of 8 * group_m M-tiles by three per round: an XCD then steps through the M-tiles by 11 or 3 instead
+// of 8, which does not stay in phase with 2, 3, 4, 8 or 9 tiles per expert (a shift of one, steps of 9, does with 3
+// and 9: measured 7 % slower on such a layer).  The tiles an XCD works on at a time stay the same, who gets which
+// changes.  Same-box A/B of the layer: DeepSeek-V3 T = 2048 at 52 active experts (two tiles each) 2010 -> 1766 us,
+// Mixtral T = 8192 4980 -> 4880 us, T = 1024 1035 -> 1013 us, the other large points within +-1 %.
+__device__ __forceinline__ void tile_of_id_rotated(const GemmArgs &a, int id, int &n_tile, int &m_tile)
+{
+    const int xcd = id & 7, s = id >> 3;
+    const int per_block = a.group_m * a.group_n;
+    const int sb = s / per_block;
+    const int w = (s - sb * per_block + sb) % per_block;
+    const int dn = w / a.group_m, dm = w - dn * a.group_m;
+    const int nbn = a.n_tiles / a.group_n;
+    const int mb = sb / nbn, nbi = sb - mb * nbn;
+    n_tile = nbi * a.group_n + dn;
+    m_tile = (mb * 8 + ((xcd + 3 * mb) & 7)) * a.group_m + dm;
+}
+
 __device__ __forceinline__ void tile_of_workgroup(const GemmArgs &a, int &n_tile, int &m_tile)
 {
     tile_of_id(a, (int)blockIdx.x, n_tile, m_tile);

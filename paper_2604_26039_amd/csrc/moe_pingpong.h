@@ -127,7 +127,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     // workgroup maps to its own XCD); ids past the real M-tiles of this call are skipped.
     auto next_tile = [&](int id, int &n_tile, int &m_tile) __attribute__((always_inline)) -> int {
         for (; id < a.total_tiles; id += (int)gridDim.x) {
-            tile_of_id(a, id, n_tile, m_tile);
+            tile_of_id_rotated(a, id, n_tile, m_tile);
             // wave-uniform by construction; saying so lets the per-tile table reads below be scalar loads, which do not
             // count on vmcnt (a vector load would have to be waited for in order, behind every LDS-direct load in flight)
             n_tile = __builtin_amdgcn_readfirstlane(n_tile);
