@@ -379,12 +379,12 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         // mode_c: 1 = every token block of the wavefront is real, 0 = some are, 2 = none (a ragged tile that ends
         // in the other wavefront row): such a wavefront issues its loads and keeps the barriers but neither reads
         // operands nor multiplies, which leaves the LDS bandwidth of the tile to the wavefronts that do
-        auto slice = [&](int kt, auto steady_c, auto mode_c) __attribute__((always_inline)) {
+        auto slice = [&](int kt, auto steady_c, auto mode_c, auto par_c) __attribute__((always_inline)) {
             constexpr bool STEADY = decltype(steady_c)::value;
             constexpr int MODE = decltype(mode_c)::value;
             // ---- M phase: both groups have read slice kt-1 (its buffers are free).  Operand reads first, then the
             // loads: the reads are what the barrier waits for, the loads only have to be issued.
-            const int par = (XS == 2) ? (kt & 1) : 0;  // position of the slice inside its token batch
+            constexpr int par = decltype(par_c)::value;  // position of the slice inside its token batch (kt & 1 for two-slice batches)
             // (the down-projection has no registers to spare for the conditional form of the reads)
             if (MODE != 2) read_all(par * KS, xbat_cur % NX, wbuf_cur, std::integral_constant<bool, MODE == 0 && STAGE == 1>{});
             // the load stream crosses into the next tile NSTAGE-1 slices (one token batch) before this one ends
@@ -437,21 +437,34 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         using Full = std::integral_constant<int, 1>;
         using None = std::integral_constant<int, 2>;
         int kt = 0;
-        const int kt_steady = has_next ? KT : KT - (NSTAGE - 1 > (NX - 1) * XS ? NSTAGE - 1 : (NX - 1) * XS);
+        // (two-slice token batches: slices run in pairs, so the steady part ends on an even slice; K is a multiple of 64 there)
+        const int kt_steady = (has_next ? KT : KT - (NSTAGE - 1 > (NX - 1) * XS ? NSTAGE - 1 : (NX - 1) * XS)) & ~(XS - 1);
+        using P0 = std::integral_constant<int, 0>;
+        using P1 = std::integral_constant<int, 1>;
+        auto run = [&](int kt_end, auto steady_c, auto mode_c) __attribute__((always_inline)) {
+            if (XS == 2) {
+                for (; kt < kt_end; kt += 2) {
+                    slice(kt, steady_c, mode_c, P0{});
+                    slice(kt + 1, steady_c, mode_c, P1{});
+                }
+            } else {
+                for (; kt < kt_end; ++kt) slice(kt, steady_c, mode_c, P0{});
+            }
+        };
         // In the up-projection a wavefront with more than half of its token blocks real takes the branch-free form on
         // all of them (the products of its padding blocks are computed and never stored): the conditional operand reads
         // and per-block branches of the ragged form cost more than they save until half of the products go away
         // (same-box A/B: tiles of 240 of 272 rows, up-projection 286 -> 265 us).  The down-projection's ragged form reads
         // unconditionally and only skips products; there the exact rule stays.
         if (STAGE == 1 ? 2 * nb_valid > NB : nb_valid == NB) {
-            for (; kt < kt_steady; ++kt) slice(kt, True{}, Full{});
-            for (; kt < KT; ++kt) slice(kt, False{}, Some{});
+            run(kt_steady, True{}, Full{});
+            run(KT, False{}, Some{});
         } else if (nb_valid > 0) {
-            for (; kt < kt_steady; ++kt) slice(kt, True{}, Some{});
-            for (; kt < KT; ++kt) slice(kt, False{}, Some{});
+            run(kt_steady, True{}, Some{});
+            run(KT, False{}, Some{});
         } else {
-            for (; kt < kt_steady; ++kt) slice(kt, True{}, None{});
-            for (; kt < KT; ++kt) slice(kt, False{}, None{});
+            run(kt_steady, True{}, None{});
+            run(KT, False{}, None{});
         }
 
         // ---- epilogue: lane holds features fblock*16 + 4*q + {0..3} of token r16.  It runs while the other group
