@@ -29,6 +29,9 @@
 
 #include "moe_gemm.h"
 
+#ifndef RAMP_PP_XSPLIT
+#define RAMP_PP_XSPLIT 1  // 0: a two-slice token batch is issued whole in its even slice (for comparisons)
+#endif
 #ifndef RAMP_PINGPONG_NX2
 #define RAMP_PINGPONG_NX2 0  // 1: keep two token buffers everywhere (for comparisons)
 #endif
@@ -205,9 +208,10 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         return v < 0 ? 0 : (v > TSLOTS ? TSLOTS : v);
     };
 
-    auto issue_x = [&](int xbuf) __attribute__((always_inline)) {
+    auto issue_x = [&](int xbuf, int t0 = 0, int t1 = TSLOTS) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < TSLOTS; ++t) {
+            if (t < t0 || t >= t1) continue;
             // a block of nothing but padding rows re-reads one 16-byte piece instead (one cache line request, and
             // the load count that the vmcnt waits rely on stays the same)
             const uint32_t off = (t < txv) ? xoff[t] : 0u;
@@ -342,9 +346,17 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     // kt+1 has to be there; younger than it are the weight slices kt+2 .. kt+NSTAGE-1 and the token batches issued
     // with them (one per even slice, before the weight slice of that phase).  With two token buffers the batch for
     // slice kt+1 of an odd kt was issued one phase ago and has to be there too: only what followed it may remain.
-    constexpr int WAIT_EVEN = (NSTAGE - 2) * WSLOTS + (NX == 3 ? (NSTAGE - 3) / 2 + 1 : 1) * TSLOTS;
-    constexpr int WAIT_ODD = (NX == 3) ? (NSTAGE - 2) * WSLOTS + (NSTAGE >= 4 ? (NSTAGE - 4) / 2 + 1 : 0) * TSLOTS
-                                       : (NSTAGE - 2 < 2 ? NSTAGE - 2 : 2) * WSLOTS;
+    // With three token buffers a batch has slack enough to be issued in two halves, one in each slice of the pair before:
+    // the wavefronts of a group issue their loads at the same time into one address path (a 1 KB load every 16 clocks, and
+    // a wavefront whose load queues there issues nothing else), so the M phase of the even slices, which carried the whole
+    // batch, was the longer one.  Each slice then issues half a batch and a weight slice; behind weight slice kt+1 are the
+    // loads of the NSTAGE-2 slices after it.
+    constexpr bool XSPLIT = RAMP_PP_XSPLIT && XS == 2 && NX == 3 && TSLOTS % 2 == 0;
+    constexpr int WAIT_EVEN = XSPLIT ? (NSTAGE - 2) * (WSLOTS + TSLOTS / 2)
+                                     : (NSTAGE - 2) * WSLOTS + (NX == 3 ? (NSTAGE - 3) / 2 + 1 : 1) * TSLOTS;
+    constexpr int WAIT_ODD = XSPLIT ? (NSTAGE - 2) * (WSLOTS + TSLOTS / 2)
+                             : (NX == 3) ? (NSTAGE - 2) * WSLOTS + (NSTAGE >= 4 ? (NSTAGE - 4) / 2 + 1 : 0) * TSLOTS
+                                         : (NSTAGE - 2 < 2 ? NSTAGE - 2 : 2) * WSLOTS;
 
     int wbuf_cur = 0, wbuf_issue = NSTAGE - 1;  // weight ring: buffer of the slice being read / being loaded
     int xbat_cur = 0;                           // token ring: batch being read (counts over all tiles)
@@ -404,7 +416,10 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
                 txv = txv_n;
             }
             bool x_issued = false;
-            if (par == 0 && (STEADY || kt + (NX - 1) * XS < KT)) {
+            if (XSPLIT) {
+                // (in the odd slice the batch of the pair is still "current": the same buffer, the other half)
+                if (STEADY || kt - par + (NX - 1) * XS < KT) issue_x((xbat_cur + NX - 1) % NX, par * (TSLOTS / 2), (par + 1) * (TSLOTS / 2));
+            } else if (par == 0 && (STEADY || kt + (NX - 1) * XS < KT)) {
                 issue_x((xbat_cur + NX - 1) % NX);  // into the buffer freed last
                 x_issued = true;
             }
@@ -412,8 +427,13 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             // this wavefront's part of the next slice has to be in LDS before the barrier after which the other group reads it
             if (STEADY) {
                 if (XS == 1) wait_vmcnt<(NSTAGE - 2) * (TSLOTS + WSLOTS)>();
+                // (the very first slice of a workgroup has the whole batches of the prologue behind it, not half batches:
+                // counting only the weight slices is right there and costs the first slice of later tiles next to nothing)
+                else if (XSPLIT && kt == 0) wait_vmcnt<(NSTAGE - 2) * WSLOTS>();
                 else if (par == 0) wait_vmcnt<WAIT_EVEN>();
                 else wait_vmcnt<WAIT_ODD>();
+            } else if (XSPLIT) {
+                if (kt + 1 < KT) wait_vmcnt<0>();  // the last slices of the last tile: whatever is in flight is needed next
             } else if (kt + 1 < KT) {
                 const int later = min(NSTAGE - 2, KT - 2 - kt);  // younger weight slices that may stay in flight
                 if (XS == 1) wait_vmcnt_upto(later * (TSLOTS + WSLOTS));
