@@ -39,11 +39,11 @@ FP8_PEAK_PFLOPS = 5.0    # dense FP8
 # per-kernel table.  Keyed by (model, T, beta), valid for the tile configuration (bm, bn, bk, waves, stages) that was
 # profiled; other workloads, or another dispatched configuration, report null.
 RECORDED_TRAFFIC = {
-    ("dsv3", 8192, "1.0"): (17.98e9 + 278.6e6, (272, 256, 32, 8, 4), "profiles/dsv3_T8192_uniform_pingpong_272x256_and_256x256_trace_traffic_sq.md"),
-    ("dsv3", 2048, "0.2"): (5.26e9 + 68.8e6, (256, 256, 32, 8, 4), "profiles/dsv3_T2048_beta02_and_mixtral_T8192_pingpong_256x256_trace_traffic_sq.md"),
+    ("dsv3", 8192, "1.0"): (17.97e9 + 278.7e6, (272, 256, 32, 8, 4), "profiles/dsv3_T8192_uniform_pingpong_272x256_and_256x256_trace_traffic_sq.md"),
+    ("dsv3", 2048, "0.2"): (5.43e9 + 68.8e6, (256, 256, 32, 8, 4), "profiles/dsv3_T2048_beta02_and_mixtral_T8192_pingpong_256x256_trace_traffic_sq.md"),
     ("mixtral", 8192, "1.0"): (16.56e9 + 471.6e6, (256, 256, 32, 8, 4), "profiles/dsv3_T2048_beta02_and_mixtral_T8192_pingpong_256x256_trace_traffic_sq.md"),
-    ("qwen3", 8192, "1.0"): (1.68e9 + 103.9e6, (272, 256, 32, 8, 4), "profiles/qwen3_T8192_and_olmoe_T4096_pingpong_trace_traffic_sq.md"),
-    ("olmoe", 4096, "1.0"): (1.11e9 + 68.1e6, (256, 256, 32, 8, 4), "profiles/qwen3_T8192_and_olmoe_T4096_pingpong_trace_traffic_sq.md"),
+    ("qwen3", 8192, "1.0"): (1.66e9 + 103.9e6, (272, 256, 32, 8, 4), "profiles/qwen3_T8192_and_olmoe_T4096_pingpong_trace_traffic_sq.md"),
+    ("olmoe", 4096, "1.0"): (1.14e9 + 68.1e6, (256, 256, 32, 8, 4), "profiles/qwen3_T8192_and_olmoe_T4096_pingpong_trace_traffic_sq.md"),
 }
 
 # Largest point of every other model shape, reported next to the headline.
