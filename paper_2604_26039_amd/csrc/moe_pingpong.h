@@ -208,7 +208,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         return v < 0 ? 0 : (v > TSLOTS ? TSLOTS : v);
     };
 
-    auto issue_x = [&](int xbuf, int t0 = 0, int t1 = TSLOTS) __attribute__((always_inline)) {
+    auto issue_x = [&](int xbuf, int t0 = 0, int t1 = PT::TSLOTS) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < TSLOTS; ++t) {
             if (t < t0 || t >= t1) continue;
