@@ -36,14 +36,15 @@ FP8_PEAK_PFLOPS = 5.0    # dense FP8
 # `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same
 # counter reads for the library's 1 GiB copy kernel).  These are RECORDED values, not measured in the
 # run that prints them: each entry names the text summary under profiles/ that holds the run and its
-# per-kernel table.  Keyed by (model, T, beta), valid for the tile configuration (bm, bn, bk, waves, stages) that was
+# per-kernel table.  Keyed by (model, T, beta), one entry per tile configuration (bm, bn, bk, waves, stages) that was
 # profiled; other workloads, or another dispatched configuration, report null.
 RECORDED_TRAFFIC = {
-    ("dsv3", 8192, "1.0"): (17.97e9 + 278.7e6, (272, 256, 32, 8, 4), "profiles/dsv3_T8192_uniform_pingpong_272x256_and_256x256_trace_traffic_sq.md"),
-    ("dsv3", 2048, "0.2"): (5.43e9 + 68.8e6, (256, 256, 32, 8, 4), "profiles/dsv3_T2048_beta02_and_mixtral_T8192_pingpong_256x256_trace_traffic_sq.md"),
-    ("mixtral", 8192, "1.0"): (16.56e9 + 471.6e6, (256, 256, 32, 8, 4), "profiles/dsv3_T2048_beta02_and_mixtral_T8192_pingpong_256x256_trace_traffic_sq.md"),
-    ("qwen3", 8192, "1.0"): (1.66e9 + 103.9e6, (272, 256, 32, 8, 4), "profiles/qwen3_T8192_and_olmoe_T4096_pingpong_trace_traffic_sq.md"),
-    ("olmoe", 4096, "1.0"): (1.14e9 + 68.1e6, (256, 256, 32, 8, 4), "profiles/qwen3_T8192_and_olmoe_T4096_pingpong_trace_traffic_sq.md"),
+    ("dsv3", 8192, "1.0"): [(16.24e9 + 286.7e6, (288, 256, 32, 8, 4), "profiles/dsv3_T8192_uniform_pingpong_288x256_272x256_256x256_trace_traffic_sq.md"),
+                            (17.98e9 + 278.7e6, (272, 256, 32, 8, 4), "profiles/dsv3_T8192_uniform_pingpong_288x256_272x256_256x256_trace_traffic_sq.md")],
+    ("dsv3", 2048, "0.2"): [(5.43e9 + 68.8e6, (256, 256, 32, 8, 4), "profiles/dsv3_T2048_beta02_and_mixtral_T8192_pingpong_256x256_trace_traffic_sq.md")],
+    ("mixtral", 8192, "1.0"): [(16.56e9 + 471.6e6, (256, 256, 32, 8, 4), "profiles/dsv3_T2048_beta02_and_mixtral_T8192_pingpong_256x256_trace_traffic_sq.md")],
+    ("qwen3", 8192, "1.0"): [(1.69e9 + 104.0e6, (272, 256, 32, 8, 4), "profiles/qwen3_T8192_and_olmoe_T4096_pingpong_trace_traffic_sq.md")],
+    ("olmoe", 4096, "1.0"): [(1.14e9 + 68.1e6, (256, 256, 32, 8, 4), "profiles/qwen3_T8192_and_olmoe_T4096_pingpong_trace_traffic_sq.md")],
 }
 
 # Largest point of every other model shape, reported next to the headline.
@@ -569,9 +570,7 @@ def main():
     ceiling["vendor_gemm"] = vendor_gemm_reference(torch, s, T_head * s.k, dev)
     if "pflops" in ceiling["vendor_gemm"]:
         log(f"[bench] vendor dense GEMM {ceiling['vendor_gemm']['shape_mnk']} on N(0,1) bf16 operands: {ceiling['vendor_gemm']['pflops']:.2f} PFLOP/s (reference only)")
-    rec = RECORDED_TRAFFIC.get((args.model, T_head, str(beta_head)))
-    if rec and tuple(cfg_head.key()[:5]) != rec[1]:
-        rec = None
+    rec = next((r for r in RECORDED_TRAFFIC.get((args.model, T_head, str(beta_head)), []) if tuple(cfg_head.key()[:5]) == r[1]), None)
     roof.update(traffic=rec[0] if rec else None, traffic_source=(rec[2] + " (recorded rocprofv3 --pmc value, not measured in this run)") if rec else None,
                 kernel=kernel_name(cfg_head), launches=probe_n)
     t_hbm, t_mfma, nbytes, flops = tuner.roofline_lower_bound_us(s, T_head, p.counts, HBM_PEAK_TBS, MFMA_PEAK_PFLOPS)

@@ -47,7 +47,9 @@ typedef struct {
 } ramp_shape;
 
 /* Tile configuration (Sec. 2.2, c = (bm, bn, wn, stg)) in this kernel's terms:
- *   bm     token-block rows per M-tile (1..256; padded to a multiple of 16 inside the MFMA)
+ *   bm     token-block rows per M-tile (4..288; padded to a multiple of 16 inside the MFMA; the
+ *          272- and 288-row tiles of the persistent kernel are a 256-row tile plus one or two
+ *          16-row tail blocks, for experts whose pairs just miss 256)
  *   bn     weight rows (columns of the paper's N) per workgroup tile: the up-projection
  *          tile holds bn/2 gate rows and the matching bn/2 up rows, the down-projection
  *          tile holds bn output features

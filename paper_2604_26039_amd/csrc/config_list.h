@@ -62,7 +62,8 @@
     X(128, 256, 32, 2, 4, 4) \
     X(128, 256, 32, 2, 4, 3) \
     X(256, 128, 32, 4, 2, 4) \
-    X(272, 256, 32, 2, 4, 4)
+    X(272, 256, 32, 2, 4, 4) \
+    X(288, 256, 32, 2, 4, 4)
 
 // Weight-streaming family (moe_stream.h): X(bm, FBW, WF, WK, U) ->
 // bn = WF*FBW*16 weight rows per tile, WF*WK wavefronts, K split WK ways inside the workgroup,

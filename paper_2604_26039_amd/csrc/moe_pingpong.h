@@ -1,6 +1,6 @@
-// Ping-pong variant of the LDS-staged expert projections for the large tiles (256 or 128 token rows,
-// 8 wavefronts): same tile decomposition and epilogues as moe_gemm_kernel, different main loop and
-// different token staging.
+// Ping-pong variant of the LDS-staged expert projections for the large tiles (128 or 256 token rows, or
+// 256 rows plus one or two 16-row tail blocks; 8 wavefronts): same tile decomposition and epilogues as
+// moe_gemm_kernel, different main loop and different token staging.
 //
 // Main loop.  The 8 wavefronts form two groups of four, one wavefront of each group per SIMD.  A
 // k-slice is handled in two phases separated by workgroup barriers: M (issue the LDS-direct loads of
@@ -40,9 +40,9 @@ namespace ramp {
 
 template <int STAGE, int BM, int BN, int BK, int WM, int WN, int NSTAGE>
 struct PingPongTraits {
-    // A tile of bm = (NB*WM + 1)*16 rows has one tail block beyond the blocks dealt to the wavefront rows; all
-    // wavefronts share it, each multiplying it with part of its weight fragments.
-    static constexpr int TAILB = (BM / 16) % WM;
+    // The token blocks of a tile come in eights, dealt to the wavefront rows; a tile of bm = (8*n + t)*16 rows has t tail
+    // blocks beyond them.  All wavefronts share a tail block, each multiplying it with part of its weight fragments.
+    static constexpr int TAILB = (BM / 16) % 8;
     static constexpr int BMAIN = BM - 16 * TAILB;
     using TT = TileTraits<BMAIN, BN, BK, WM, WN, 2>;  // tile geometry only; the ring depths are defined here
     static constexpr bool ROWX = (STAGE == 1);           // gathered rows, 128-byte pieces
@@ -60,10 +60,15 @@ struct PingPongTraits {
     static constexpr int WSLOTS = TT::W_FRAGS / TT::NWAVE;     // weight load instructions per wavefront per slice
     static constexpr int RING_BYTES = NX * X_BYTES + NSTAGE * W_BYTES;
     static constexpr int STG_BYTES = (STAGE == 2) ? 4096 * TT::NWAVE : 0;  // per-wavefront staging of bf16 output rows
-    static constexpr int LDS_BYTES = RING_BYTES + STG_BYTES;
+    // A down-projection tile with tail blocks has no registers to spare for the destination pair and router weight of its
+    // token rows through the whole tile: they wait in LDS instead (pairs and weights of up to 512 slots, two tiles deep).
+    static constexpr bool SLOT_LDS = (STAGE == 2) && TAILB > 0;
+    static constexpr int SLOT_BYTES = SLOT_LDS ? 2 * 4096 : 0;
+    static constexpr int LDS_BYTES = RING_BYTES + STG_BYTES + SLOT_BYTES;
+    static_assert(!SLOT_LDS || (BM <= 512 && BM % 4 == 0), "slot table: two 1 KB loads per array");
     static_assert(TT::NWAVE == 8, "ping-pong needs two groups of four wavefronts");
     static_assert(BK == 32 || BK == 64, "bk 32 or 64");
-    static_assert(BM % 16 == 0 && TAILB <= 1, "whole token blocks, at most one tail block");
+    static_assert(BM % 16 == 0 && TAILB <= 3, "whole token blocks, at most three tail blocks");
     static_assert(TAILB == 0 || (BK == 32 && WM == 2 && (STAGE == 1 ? TT::FB1 == 2 : TT::FB2 == 4)), "tail block: 256-wide tiles of two wavefront rows");
     static_assert(TT::W_FRAGS % TT::NWAVE == 0, "weight loads must split evenly");
     static_assert(NSTAGE >= 3 || XS == 1, "a two-slice token batch needs three weight stages");
@@ -117,6 +122,8 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     char *const lds_x = lds;
     char *const lds_w = lds + NX * PT::X_BYTES;
     char *const lds_stage = lds + PT::RING_BYTES;
+    char *const lds_slot = lds + PT::RING_BYTES + PT::STG_BYTES;
+    constexpr bool SLOT_LDS = PT::SLOT_LDS;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -208,6 +215,14 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         return v < 0 ? 0 : (v > TSLOTS ? TSLOTS : v);
     };
 
+    // Slot table (SLOT_LDS).  The last token load of wavefronts 4..7 is a surplus slot of the load round (past the blocks
+    // of the tile, it never fetches rows).  In the first slice of a tile these four loads copy the tile's part of the two
+    // per-slot tables into LDS instead, 1 KB each (16-byte pieces past the tile re-read its last piece): they ride in the
+    // load stream at no cost in loads or waits, and land with the slice, a whole tile before the epilogue reads them.
+    // slot_tile: tile whose first slice is issued next, or -1; slot_half: the half of the table it gets (the other half
+    // belongs to the tile being multiplied).
+    static_assert(!SLOT_LDS || (XS == 1 && (TSLOTS - 1) * NWAVE + 4 >= PT::X_BLOCKS), "slot table: wavefronts 4..7 need a surplus load slot");
+    int slot_tile = -1, slot_half = 0;
     auto issue_x = [&](int xbuf, int t0 = 0, int t1 = PT::TSLOTS) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < TSLOTS; ++t) {
@@ -215,9 +230,19 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             // a block of nothing but padding rows re-reads one 16-byte piece instead (one cache line request, and
             // the load count that the vmcnt waits rely on stays the same)
             const uint32_t off = (t < txv) ? xoff[t] : 0u;
-            load_to_lds_16B(a.act + off, lds_x + xbuf * PT::X_BYTES + (wave + t * NWAVE) * 1024);
+            if (SLOT_LDS && t == TSLOTS - 1 && wave >= 4 && slot_tile >= 0) {
+                const int arr = wave & 1, part = (wave >> 1) & 1;
+                const int c0 = part * 64 + lane;
+                const int c = c0 < BM / 4 ? c0 : BM / 4 - 1;
+                const void *src = arr ? (const void *)(a.slot_w + (size_t)slot_tile * BM + c * 4)
+                                      : (const void *)(a.sorted + (size_t)slot_tile * BM + c * 4);
+                load_to_lds_16B(src, lds_slot + slot_half * 4096 + arr * 2048 + part * 1024);
+            } else {
+                load_to_lds_16B(a.act + off, lds_x + xbuf * PT::X_BYTES + (wave + t * NWAVE) * 1024);
+            }
             xoff[t] += XSTEP;
         }
+        if (SLOT_LDS) slot_tile = -1;
     };
     auto issue_w = [&](int wbuf) __attribute__((always_inline)) {
 #pragma unroll
@@ -228,16 +253,20 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     };
 
     floatx4 acc[NACC][NB];
-    // tail block (TAILB): wavefront row wm multiplies it with two of its weight fragments: (gate, up) of feature
+    // tail blocks (TAILB): wavefront row wm multiplies each with two of its weight fragments: (gate, up) of feature
     // block wm in the up-projection, feature blocks 2*wm and 2*wm + 1 in the down-projection
-    floatx4 acc_t[2];
-    bool tail_valid = false;  // the current tile has real rows in its tail block
+    constexpr int NT = TAILB ? TAILB : 1;
+    floatx4 acc_t[2 * NT];
+    int tail_n = 0;  // tail blocks of the current tile with real rows
     auto zero_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NACC; ++i)
 #pragma unroll
             for (int j = 0; j < NB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if (TAILB) acc_t[0] = acc_t[1] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (TAILB) {
+#pragma unroll
+            for (int t = 0; t < 2 * NT; ++t) acc_t[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
     };
 
     // ---- LDS read offsets of this lane's operand fragments ----
@@ -245,7 +274,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     const int xrow_off = wm * 2048 + (r16 >> 3) * 1024 + (r16 & 7) * 128;  // token block nb of this wavefront is block nb*WM + wm
     const int xsw = (r16 >> 1) & 7;
     const int xtail_off = NB * WM * 2048 + (r16 >> 3) * 1024 + (r16 & 7) * 128;
-    bf16x8 fx[KS][NB], fw[KS][NACC], fx_t[KS];
+    bf16x8 fx[KS][NB], fw[KS][NACC], fx_t[KS][NT];
     int nb_valid = 0;  // token blocks of this wavefront with at least one real row in the current tile
     // kk0: 32-wide k-step of the slice inside its token batch; partial_c: skip the token fragments of all-padding blocks
     auto read_all = [&](int kk0, int xbuf, int wbuf, auto partial_c) __attribute__((always_inline)) {
@@ -268,13 +297,15 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
                 for (int nb = 0; nb < NB; ++nb)
                     if (!PARTIAL || nb < nb_valid)
                         fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + xrow_off + nb * (WM * 2048) + coff);
-                if (TAILB) fx_t[ks] = *reinterpret_cast<const bf16x8 *>(xs + xtail_off + coff);
+#pragma unroll
+                for (int t = 0; t < TAILB; ++t) fx_t[ks][t] = *reinterpret_cast<const bf16x8 *>(xs + xtail_off + t * 2048 + coff);
             } else {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
                     if (!PARTIAL || nb < nb_valid)
                         fx[ks][nb] = *reinterpret_cast<const bf16x8 *>(xs + ((nb * WM + wm) * KS + ks) * 1024 + lane * 16);
-                if (TAILB) fx_t[ks] = *reinterpret_cast<const bf16x8 *>(xs + (NB * WM * KS + ks) * 1024 + lane * 16);
+#pragma unroll
+                for (int t = 0; t < TAILB; ++t) fx_t[ks][t] = *reinterpret_cast<const bf16x8 *>(xs + ((NB * WM + t) * KS + ks) * 1024 + lane * 16);
             }
         }
     };
@@ -293,16 +324,20 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
                         acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][i], fx[ks][nb], acc[i][nb], 0, 0, 0);
                 }
             }
-        if (TAILB && tail_valid) {
+        if (TAILB && tail_n > 0) {
             constexpr int I0 = (STAGE == 1) ? 0 : 0, I1 = (STAGE == 1) ? FB : 1, STEP = (STAGE == 1) ? 1 : 2;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                if (wm == 0) {
-                    acc_t[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I0], fx_t[ks], acc_t[0], 0, 0, 0);
-                    acc_t[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I1], fx_t[ks], acc_t[1], 0, 0, 0);
-                } else {
-                    acc_t[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I0 + STEP], fx_t[ks], acc_t[0], 0, 0, 0);
-                    acc_t[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I1 + STEP], fx_t[ks], acc_t[1], 0, 0, 0);
+            for (int t = 0; t < TAILB; ++t) {
+                if (t > 0 && t >= tail_n) continue;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    if (wm == 0) {
+                        acc_t[2 * t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I0], fx_t[ks][t], acc_t[2 * t], 0, 0, 0);
+                        acc_t[2 * t + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I1], fx_t[ks][t], acc_t[2 * t + 1], 0, 0, 0);
+                    } else {
+                        acc_t[2 * t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I0 + STEP], fx_t[ks][t], acc_t[2 * t], 0, 0, 0);
+                        acc_t[2 * t + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][I1 + STEP], fx_t[ks][t], acc_t[2 * t + 1], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -317,6 +352,11 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         return v < 0 ? 0 : (v > NB ? NB : v);
     };
 
+    auto tail_blocks = [&](int rows) __attribute__((always_inline)) {  // tail blocks with at least one real row
+        const int v = (rows - BMAIN + 15) / 16;
+        return !TAILB || v < 0 ? 0 : (v > TAILB ? TAILB : v);
+    };
+
     int n_tile, m_tile;
     int id = next_tile((int)blockIdx.x, n_tile, m_tile);
     if (id < 0) return;
@@ -324,7 +364,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     tile_offsets(n_tile, m_tile, xoff, woff, wexp_w, rows_cur);
     token_offsets(xoff);
     nb_valid = blocks_valid(rows_cur);
-    tail_valid = TAILB && rows_cur > BMAIN;
+    tail_n = tail_blocks(rows_cur);
     txv = token_loads(rows_cur);
     zero_acc();
 
@@ -333,6 +373,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
     // so only the very first tile waits for a cold pipeline.  Loads are issued, and counted by vmcnt, in this
     // order: prologue X(0) W(0) [X(1)] W(1) ..., then in the M phase of slice kt: the token batch whose buffer
     // became free (if any), then weight slice kt+NSTAGE-1.
+    if (SLOT_LDS) slot_tile = m_tile;
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s) {
         if (XS == 1 || s == 0 || (s == 1 && NX == 3)) issue_x(s);
@@ -360,6 +401,7 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
 
     int wbuf_cur = 0, wbuf_issue = NSTAGE - 1;  // weight ring: buffer of the slice being read / being loaded
     int xbat_cur = 0;                           // token ring: batch being read (counts over all tiles)
+    int slot_par = 0;                           // slot table: half used by the current tile
     while (true) {
         // following tile of this workgroup (its first slices are loaded while this one finishes)
         int n_next = 0, m_next = 0;
@@ -377,15 +419,17 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         // nothing uses them before the epilogue: no round trip on the way into the tile.  One load, one wait, one
         // dependent load per token block would be sixteen round trips, each of them also draining the LDS-direct loads
         // in flight (vmcnt counts in order).
-        int tail_pair = a.P;
-        float tail_wgt = 0.0f;
-        if (STAGE == 2) {
+        int tail_pair[NT];
+        float tail_wgt[NT];
+        if (STAGE == 2 && !SLOT_LDS) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) out_pair[nb] = a.sorted[m_tile * BM + (nb * WM + wm) * 16 + r16];
-            if (TAILB) tail_pair = a.sorted[m_tile * BM + BMAIN + r16];
+#pragma unroll
+            for (int t = 0; t < TAILB; ++t) tail_pair[t] = a.sorted[m_tile * BM + BMAIN + t * 16 + r16];
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) out_wgt[nb] = a.slot_w[m_tile * BM + (nb * WM + wm) * 16 + r16];
-            if (TAILB) tail_wgt = a.slot_w[m_tile * BM + BMAIN + r16];
+#pragma unroll
+            for (int t = 0; t < TAILB; ++t) tail_wgt[t] = a.slot_w[m_tile * BM + BMAIN + t * 16 + r16];
         }
 
         // mode_c: 1 = every token block of the wavefront is real, 0 = some are, 2 = none (a ragged tile that ends
@@ -414,6 +458,10 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
                 }
                 token_offsets(xoff);
                 txv = txv_n;
+                if (SLOT_LDS && has_next) {
+                    slot_tile = m_next;
+                    slot_half = slot_par ^ 1;
+                }
             }
             bool x_issued = false;
             if (XSPLIT) {
@@ -490,6 +538,21 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         // ---- epilogue: lane holds features fblock*16 + 4*q + {0..3} of token r16.  It runs while the other group
         // is in a C phase; the stores are not waited for here.
         const int f0 = n_tile * FEAT_PER_TILE;
+        if (SLOT_LDS) {
+            const int *sp = reinterpret_cast<const int *>(lds_slot + slot_par * 4096);
+            const float *sw = reinterpret_cast<const float *>(lds_slot + slot_par * 4096 + 2048);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                out_pair[nb] = sp[(nb * WM + wm) * 16 + r16];
+                out_wgt[nb] = sw[(nb * WM + wm) * 16 + r16];
+            }
+#pragma unroll
+            for (int t = 0; t < TAILB; ++t) {
+                tail_pair[t] = sp[BMAIN + t * 16 + r16];
+                tail_wgt[t] = sw[BMAIN + t * 16 + r16];
+            }
+            slot_par ^= 1;
+        }
         if (STAGE == 2 && a.y_bf16) {
             // bf16 per-pair rows leave through LDS: a lane holds 16 consecutive features of one token, but a store
             // instruction should cover whole 128-byte lines.  Per chunk of two token blocks the wavefront writes its
@@ -540,11 +603,13 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
             }
         }
         }
-        if (TAILB && tail_valid) {
+#pragma unroll
+        for (int t = 0; t < TAILB; ++t) {
+            if (t >= tail_n) continue;
             if (STAGE == 1)
-                store_token_row<1, 1>(a, &acc_t[0], &acc_t[1], 1, (size_t)(m_tile * BM + BMAIN + r16), f0 / 16 + wn * FB + wm, q, 1.0f);
-            else if (tail_pair < a.P)
-                store_token_row<2, 2>(a, &acc_t[0], &acc_t[0], 1, (size_t)tail_pair * a.F, f0 / 16 + wn * FB + 2 * wm, q, tail_wgt);
+                store_token_row<1, 1>(a, &acc_t[2 * t], &acc_t[2 * t + 1], 1, (size_t)(m_tile * BM + BMAIN + t * 16 + r16), f0 / 16 + wn * FB + wm, q, 1.0f);
+            else if (tail_pair[t] < a.P)
+                store_token_row<2, 2>(a, &acc_t[2 * t], &acc_t[2 * t], 1, (size_t)tail_pair[t] * a.F, f0 / 16 + wn * FB + 2 * wm, q, tail_wgt[t]);
         }
         if (!has_next) break;
         id = id_next;
@@ -552,18 +617,19 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         m_tile = m_next;
         rows_cur = rows_next;
         nb_valid = blocks_valid(rows_cur);
-        tail_valid = TAILB && rows_cur > BMAIN;
+        tail_n = tail_blocks(rows_cur);
         zero_acc();
     }
     if (group == 0) phase_barrier();  // both groups execute the same number of barriers
 }
 
 // LDS stages of the down-projection, which stages tokens and weights per slice and keeps 32 KB for its output rows:
-// at most 4, and 3 for a tile with a tail block (its token buffers are padded to whole load rounds).
+// at most 4, and 3 for a tile with tail blocks (its token buffers are padded to whole load rounds, and it keeps 8 KB for
+// the per-slot tables of two tiles).
 template <int BM, int WM, int NSTAGE>
 constexpr int pingpong_down_stages()
 {
-    return ((BM / 16) % WM) ? 3 : (NSTAGE > 4 ? 4 : NSTAGE);
+    return ((BM / 16) % 8) ? 3 : (NSTAGE > 4 ? 4 : NSTAGE);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int NSTAGE>

@@ -142,10 +142,10 @@ def test_smallest_dimensions_many_tiles(H, I, E, k, T, beta):
 
 def test_expert_row_counts_around_the_tile_and_tail_block_sizes():
     """Experts whose pair counts sit on both sides of every row-block boundary that the large tiles know: 256 rows
-    (a full tile of the 256-row configurations; the start of the 16-row tail block that the 272-row tile shares
-    between its wavefront rows), 272 (that tile full), one row more or less, two tiles, an empty expert, fewer rows
-    than a block.  top-1 routing makes the counts exact; every element against the oracle on every ping-pong
-    configuration."""
+    (a full tile of the 256-row configurations; the start of the 16-row tail blocks that the 272- and 288-row tiles
+    share between their wavefront rows), 272 and 288 (those tiles full), one row more or less, two tiles, an empty
+    expert, fewer rows than a block.  top-1 routing makes the counts exact; every element against the oracle on every
+    ping-pong configuration."""
     counts = [256, 257, 260, 271, 272, 273, 287, 288, 289, 304, 529, 0, 15, 255, 544, 561, 577]
     shape = synth.Shape("edge", 256, 128, len(counts), 1)
     T = sum(counts)
@@ -157,8 +157,29 @@ def test_expert_row_counts_around_the_tile_and_tail_block_sizes():
     w = rng.uniform(0.25, 1.0, size=(T, 1)).astype(np.float32)
     ref = L.oracle_rows(ids, w)
     cfgs = [c for c in ramp.configs(L.rs) if c.mode & 0x400]
-    assert any(c.bm == 272 for c in cfgs) and any(c.bm == 256 for c in cfgs)
+    assert {256, 272, 288} <= {c.bm for c in cfgs}
     for cfg in cfgs:
+        assert_close(L.run(cfg, ids, w), ref, f"{cfg}")
+
+
+def test_persistent_workgroups_walk_several_tiles_every_row():
+    """More than 800 M-tiles of one N-tile each, so every one of the 256 persistent workgroups walks three or four
+    tiles in both projections: the load stream crosses tile boundaries, the token and weight rings wrap, and the
+    tail-block tiles keep the destination pairs and router weights of two tiles in LDS at a time.  Every element against
+    the oracle on every ping-pong configuration; 24 experts with uneven counts give full tiles, tiles that end inside
+    the tail blocks and ragged ones."""
+    shape = synth.Shape("edge", 256, 128, 24, 1)
+    T = 236_000
+    L = Layer(shape, T, seed=29, x_std=1.5)
+    ids, w = synth.routing(T, shape, 0.7, seed=31)
+    rng = np.random.default_rng(5)
+    w = rng.uniform(0.25, 1.0, size=w.shape).astype(np.float32)
+    ref = L.oracle_rows(ids, w)
+    cfgs = [c for c in ramp.configs(L.rs) if c.mode & 0x400]
+    assert {256, 272, 288} <= {c.bm for c in cfgs}
+    for cfg in cfgs:
+        print(f"case {cfg}", flush=True)
+        assert ramp.align_capacity(T, 1, 24, cfg.bm) // cfg.bm > 3 * 256
         assert_close(L.run(cfg, ids, w), ref, f"{cfg}")
 
 
