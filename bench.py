@@ -205,6 +205,21 @@ def extra_row(torch, ramp, synth, tuner, name, T, beta, iters, dev):
     return row
 
 
+def head_to_head_regret(tuner, layers, fam, p, chosen, times, iters):
+    """The minimum over all configurations of one noisy timing each is biased low (the winner is partly the luckiest
+    measurement), which inflates the regret of near-ties.  Second figure: the three fastest configurations of `times` and
+    the dispatched one timed again in alternation (three rounds), regret against the fastest of those medians."""
+    if chosen == int(np.argmin(times)):
+        return 0.0
+    cand = list(dict.fromkeys([chosen] + [int(i) for i in np.argsort(times)[:3]]))
+    again = {c: [] for c in cand}
+    for _ in range(3):
+        for c in cand:
+            again[c].append(tuner.time_config(layers, fam.cfgs[c], p, warmup=2, iters=iters, budget_ms=40.0))
+    med = {c: float(np.median(v)) for c, v in again.items()}
+    return med[chosen] / min(med.values()) - 1.0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -361,18 +376,7 @@ def main():
                 regrets5[name].append(t_ev[tuner.select5(fam, th5, p.counts, MODELS[name]), j] / t_ev[best, j] - 1.0)
             chosen = picks[DISPATCH]
             reg = regrets[DISPATCH][-1]
-            # The minimum over all configurations of one noisy timing each is biased low (the winner is partly the luckiest
-            # measurement), which inflates the regret of near-ties.  Second figure: the three fastest of the sweep and the
-            # dispatched configuration timed again in alternation, regret against the fastest of those medians.
-            reg_h2h = 0.0
-            if chosen != best:
-                cand = list(dict.fromkeys([chosen] + [int(i) for i in np.argsort(t_ev[:, j])[:3]]))
-                again = {c: [] for c in cand}
-                for _ in range(3):
-                    for c in cand:
-                        again[c].append(tuner.time_config(layers, fam.cfgs[c], p, warmup=2, iters=min(args.iters, 10), budget_ms=40.0))
-                med = {c: float(np.median(v)) for c, v in again.items()}
-                reg_h2h = med[chosen] / min(med.values()) - 1.0
+            reg_h2h = head_to_head_regret(tuner, layers, fam, p, chosen, t_ev[:, j], min(args.iters, 10))
             regrets_h2h.append(reg_h2h)
             hot_us = tuner.time_config(layers, fam.cfgs[chosen], p, warmup=3, iters=min(args.iters, 20), budget_ms=60.0, hot=True)
             spd = t_ev[st, j] / t_ev[chosen, j]
@@ -421,24 +425,31 @@ def main():
 
     if args.heldout > 0:
         rng = np.random.default_rng(7)
-        regs, regs_eq6, regs_nr = [], [], []
+        regs, regs_eq6, regs_nr, regs_h2h, rows_h = [], [], [], [], []
         t0 = time.time()
         for h in range(args.heldout):
             T = int(rng.choice(sweep["T"][1:]))
             b = sweep["beta"][int(rng.integers(len(sweep["beta"])))]
             p = tuner.Point(T, b, seed=900000 + h).materialise(s)
             times = np.array([tuner.time_config(layers, c, p, warmup=2, iters=8, budget_ms=30.0) for c in fam.cfgs])
-            regs.append(times[tuner.select(fam, theta, p.counts, dispatch_flags)] / times.min() - 1.0)
+            chosen = tuner.select(fam, theta, p.counts, dispatch_flags)
+            regs.append(times[chosen] / times.min() - 1.0)
+            regs_h2h.append(head_to_head_regret(tuner, layers, fam, p, chosen, times, 8))
+            rows_h.append(dict(T=T, beta=b, seed=900000 + h, regret=float(regs[-1]), regret_remeasured=float(regs_h2h[-1]),
+                               best_cfg=fam.cfgs[int(np.argmin(times))].key(), ra_cfg=fam.cfgs[chosen].key()))
             regs_eq6.append(times[tuner.select(fam, thetas["eq6"], p.counts, MODELS["eq6"])] / times.min() - 1.0)
             regs_nr.append(times[tuner.select(fam, thetas["all_but_rounds"], p.counts, MODELS["all_but_rounds"])] / times.min() - 1.0)
             if h % 20 == 19:
                 log(f"[bench] held-out {h + 1}/{args.heldout}: mean regret so far {100 * np.mean(regs):.2f}%")
         summary["heldout_histograms"] = dict(n=args.heldout, mean_regret=float(np.mean(regs)), max_regret=float(np.max(regs)),
                                              median_regret=float(np.median(regs)),
+                                             mean_regret_remeasured=float(np.mean(regs_h2h)), max_regret_remeasured=float(np.max(regs_h2h)),
+                                             histograms=rows_h,
                                              mean_regret_eq6_as_printed=float(np.mean(regs_eq6)),
                                              mean_regret_all_but_rounds=float(np.mean(regs_nr)),
                                              max_regret_all_but_rounds=float(np.max(regs_nr)))
         log(f"[bench] held-out histograms {time.time() - t0:.1f}s: mean {100 * np.mean(regs):.2f}% max {100 * np.max(regs):.2f}% "
+            f"(top three and the pick timed again: mean {100 * np.mean(regs_h2h):.2f}% max {100 * np.max(regs_h2h):.2f}%) "
             f"(Eq. 6 as printed: mean {100 * np.mean(regs_eq6):.2f}%; all flags but rounds: mean {100 * np.mean(regs_nr):.2f}% max {100 * np.max(regs_nr):.2f}%)")
 
     # ------------------------------------------------------------------ headline: K timed steps of the whole path
