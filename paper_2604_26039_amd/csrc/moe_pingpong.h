@@ -418,7 +418,8 @@ __global__ __launch_bounds__(512, 1) void moe_pingpong_kernel(GemmArgs a)
         // sentinel P; the weights are read by slot, from the copy the align step made, not through the pair index), and
         // nothing uses them before the epilogue: no round trip on the way into the tile.  One load, one wait, one
         // dependent load per token block would be sixteen round trips, each of them also draining the LDS-direct loads
-        // in flight (vmcnt counts in order).
+        // in flight (vmcnt counts in order).  Tail-block tiles have no registers for them: there the two tables came into LDS
+        // with the first token slice of the tile (issue_x) and the epilogue reads them back.
         int tail_pair[NT];
         float tail_wgt[NT];
         if (STAGE == 2 && !SLOT_LDS) {
